@@ -1,0 +1,394 @@
+"""Pins for the CPU oracle: everything here checks oracle/pq_oracle.c against something other than itself --
+a hand-worked example, reconstruction (Eq. 2 + Eq. 3) through numpy in float64, exact rational arithmetic,
+closed forms, special cases that reduce to library routines, and tie / permutation invariants."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2408_09992_amd import workloads as W
+
+
+# ---------------------------------------------------------------- helpers (independent of the oracle)
+
+def reconstruct(codes, centroids):
+    """Eq. 2 through numpy: W[i] = psi_{0,g_i0} || ... || psi_{m-1,g_i,m-1}, float64 [N][d]."""
+    m = centroids.shape[0]
+    return np.concatenate([centroids[k][codes[:, k]].astype(np.float64) for k in range(m)], axis=1)
+
+
+def rank_order(scores):
+    """ids sorted by score descending then id ascending, via numpy's lexsort (last key is primary)."""
+    ids = np.arange(len(scores))
+    return np.lexsort((ids, -np.asarray(scores, dtype=np.float64)))
+
+
+def round_f32(x: Fraction) -> np.float32:
+    """Correctly round an exact rational to fp32 (nearest, ties to even)."""
+    c = np.float32(float(x))
+    best = c
+    for cand in (np.nextafter(c, np.float32(-np.inf)), np.nextafter(c, np.float32(np.inf))):
+        dc, db = abs(Fraction(float(cand)) - x), abs(Fraction(float(best)) - x)
+        if dc < db or (dc == db and (int(np.float32(cand).view(np.uint32)) & 1) == 0
+                       and (int(np.float32(best).view(np.uint32)) & 1) == 1):
+            best = cand
+    return np.float32(best)
+
+
+def assert_topk_matches_f64(ids, scores, ref_scores_f64, K, rel=1e-5):
+    """ids/scores from the fp32 path against float64 scores of every item: scores within rel, and the id list
+    equal to the float64 ranking except where float64 scores are closer than the tolerance (then a swap is
+    legitimate)."""
+    order = rank_order(ref_scores_f64)
+    tol = rel * np.maximum(np.abs(ref_scores_f64), 1.0)
+    assert np.all(np.abs(scores.astype(np.float64) - ref_scores_f64[ids]) <= tol[ids])
+    for r in range(K):
+        if ids[r] != order[r]:
+            assert abs(ref_scores_f64[ids[r]] - ref_scores_f64[order[r]]) <= 2 * tol[order[r]], (r, ids, order[:K])
+    # nothing that clearly belongs in the top K is missing
+    kth = ref_scores_f64[order[K - 1]]
+    clear = np.nonzero(ref_scores_f64 > kth + 2 * rel * max(abs(kth), 1.0))[0]
+    assert set(clear.tolist()) <= set(ids.tolist())
+
+
+# ---------------------------------------------------------------- the hand-worked example (tests/golden)
+
+def load_golden(path):
+    out = {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        out[key] = [float(v) for v in vals]
+    return out
+
+
+def test_hand_example(oracle):
+    import os
+    g = load_golden(os.path.join(os.path.dirname(__file__), "golden", "hand_example.txt"))
+    d, m, b, K = (int(g[k][0]) for k in "dmbK")
+    s = d // m
+    cent = np.array([g["psi_0"], g["psi_1"]], dtype=np.float32).reshape(m, b, s)
+    phi = np.array(g["phi"], dtype=np.float32).reshape(1, d)
+    G = np.array(g["G"], dtype=np.uint8).reshape(-1, m)
+    S = oracle.subitem_scores(phi, cent)
+    assert S.shape == (1, m, b)
+    assert S.ravel().tolist() == g["S"]
+    assert oracle.item_scores(G, S[0]).tolist() == g["scores"]
+    assert oracle.item_scores(G, S[0], split_major=True).tolist() == g["scores"]
+    ids, sc = oracle.score_topk(G, S, K)
+    assert ids[0].tolist() == g["top_ids"] and sc[0].tolist() == g["top_scores"]
+    ids2, sc2 = oracle.pqtopk(G, cent, phi, K)
+    assert ids2[0].tolist() == g["top_ids"] and sc2[0].tolist() == g["top_scores"]
+    ids3, sc3 = oracle.bruteforce_topk(G, cent, phi, K)
+    assert ids3[0].tolist() == g["top_ids"] and sc3[0].tolist() == g["top_scores"]
+
+
+# ---------------------------------------------------------------- Eq. 4: the sub-id score matrix
+
+def test_subitem_scores_vs_numpy_f64(oracle):
+    cfg = W.CONFIGS["large"]
+    cent = W.centroids(cfg.m, cfg.b, cfg.d)
+    Q = W.queries(3, cfg.d)
+    S = oracle.subitem_scores(Q, cent)
+    s = cfg.d // cfg.m
+    ref = np.einsum("kjt,qkt->qkj", cent.astype(np.float64), Q.reshape(3, cfg.m, s).astype(np.float64))
+    assert np.abs(S - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())
+    # a transposed / mis-split operand would not survive this: split k must only see chunk k of phi
+    Q2 = Q.copy()
+    Q2[:, s:2 * s] += 1.0
+    S2 = oracle.subitem_scores(Q2, cent)
+    changed = np.any(S2 != S, axis=2)
+    assert changed[:, 1].all() and not changed[:, [0] + list(range(2, cfg.m))].any()
+
+
+def test_subitem_scores_exact_fma_chain(oracle):
+    """The chain acc <- round32(psi_t * phi_t + acc), t ascending, reproduced with exact rationals."""
+    m, b, s = 2, 5, 7
+    cent = W.centroids(m, b, m * s, seed=11)
+    Q = W.queries(2, m * s, seed=11)
+    S = oracle.subitem_scores(Q, cent)
+    differs_from_unfused = 0
+    for q in range(2):
+        for k in range(m):
+            for j in range(b):
+                acc = np.float32(0.0)
+                unf = np.float32(0.0)
+                for t in range(s):
+                    a, x = cent[k, j, t], Q[q, k * s + t]
+                    acc = round_f32(Fraction(float(a)) * Fraction(float(x)) + Fraction(float(acc)))
+                    unf = np.float32(np.float32(a * x) + unf)
+                assert S[q, k, j] == acc
+                differs_from_unfused += int(unf != acc)
+    assert differs_from_unfused > 0      # the case set can tell a fused chain from a two-rounding one
+
+
+def test_subitem_scores_single_product(oracle):
+    """s = 1 (m = d): every sub-id score is exactly one rounded product."""
+    d = 6
+    cent = W.centroids(d, 4, d, seed=5)
+    Q = W.queries(2, d, seed=5)
+    S = oracle.subitem_scores(Q, cent)
+    ref = cent[None, :, :, 0] * Q[:, :, None]
+    assert np.array_equal(S, ref.astype(np.float32))
+
+
+# ---------------------------------------------------------------- end to end against reconstruction (Eq. 2 + 3)
+
+def test_tiny_config_vs_reconstruction(oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, Q = W.make(cfg)
+    ids, sc = oracle.pqtopk(G, cent, Q, cfg.K)
+    ref = reconstruct(G, cent) @ Q[0].astype(np.float64)
+    assert_topk_matches_f64(ids[0], sc[0], ref, cfg.K)
+    bid, bsc = oracle.bruteforce_topk(G, cent, Q, cfg.K)
+    order = rank_order(ref)
+    assert np.allclose(bsc[0], ref[order[:cfg.K]], rtol=1e-12, atol=1e-12)
+    assert_topk_matches_f64(bid[0], bsc[0], ref, cfg.K, rel=1e-9)
+    # on this seed the top 10 are separated by far more than fp32 rounding, so the ids must agree outright
+    assert ids[0].tolist() == order[:cfg.K].tolist() == bid[0].tolist()
+
+
+def test_random_small_shapes_vs_reconstruction(oracle):
+    rng = np.random.default_rng(1234)
+    n_cases = 0
+    for m in (1, 2, 4, 8):
+        for b in (2, 4, 16, 256):
+            for rep in range(12):
+                s = int(rng.integers(1, 9))
+                d = m * s
+                N = int(rng.integers(1, 201))
+                K = int(rng.integers(1, min(N, 20) + 1))
+                B = int(rng.integers(1, 4))
+                seed = 1000 * m + 10 * b + rep
+                G = W.codes_uniform(N, m, b, seed=seed)
+                cent = W.centroids(m, b, d, seed=seed)
+                Q = W.queries(B, d, seed=seed)
+                ids, sc = oracle.pqtopk(G, cent, Q, K)
+                Wf = reconstruct(G, cent)
+                for q in range(B):
+                    assert_topk_matches_f64(ids[q], sc[q], Wf @ Q[q].astype(np.float64), K)
+                n_cases += 1
+    assert n_cases == 192
+
+
+def test_query_rows_are_independent(oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, _ = W.make(cfg)
+    Q = W.queries(4, cfg.d)
+    ids, sc = oracle.pqtopk(G, cent, Q, cfg.K)
+    for q in range(4):
+        i1, s1 = oracle.pqtopk(G, cent, Q[q:q + 1], cfg.K)
+        assert np.array_equal(i1[0], ids[q]) and np.array_equal(s1[0], sc[q])
+    assert len({tuple(r) for r in ids.tolist()}) == 4
+
+
+# ---------------------------------------------------------------- Eq. 5: closed forms and exact invariants
+
+def test_planted_argmax_and_bounds(oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, Q = W.make(cfg)
+    S = oracle.subitem_scores(Q, cent)
+    best_row = S[0].argmax(axis=1)
+    G = G.copy()
+    W.plant_rows(G, [4321], best_row)
+    sc = oracle.item_scores(G, S[0])
+    upper = np.float32(0)
+    lower = np.float32(0)
+    for k in range(cfg.m):           # same left-to-right fp32 sum as the definition, on the extremes
+        upper = S[0, k].max() if k == 0 else np.float32(upper + S[0, k].max())
+        lower = S[0, k].min() if k == 0 else np.float32(lower + S[0, k].min())
+    assert sc[4321] == upper
+    assert sc.max() == upper and sc.min() >= lower
+    ids, top = oracle.score_topk(G, S, cfg.K)
+    first = np.nonzero(sc == upper)[0].min()
+    assert ids[0, 0] == first and top[0, 0] == upper
+
+
+def test_per_split_linearity_scaling_negation(oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, Q = W.make(cfg)
+    s = cfg.d // cfg.m
+    S = oracle.subitem_scores(Q, cent)
+    for k in range(cfg.m):
+        Qk = np.zeros_like(Q)
+        Qk[:, k * s:(k + 1) * s] = Q[:, k * s:(k + 1) * s]
+        Sk = oracle.subitem_scores(Qk, cent)
+        assert np.array_equal(Sk[0, k], S[0, k])
+        assert not Sk[0, [j for j in range(cfg.m) if j != k]].any()
+        # only split k contributes: the item score is that one table entry (0 + x and x + 0 are exact)
+        assert np.array_equal(oracle.item_scores(G, Sk[0]), S[0, k][G[:, k]] + np.float32(0))
+    base = oracle.item_scores(G, S[0])
+    ids0, sc0 = oracle.score_topk(G, S, cfg.K)
+    for scale in (2.0, 0.125, 1024.0):
+        S2 = oracle.subitem_scores((Q * np.float32(scale)), cent)
+        assert np.array_equal(S2, S * np.float32(scale))
+        assert np.array_equal(oracle.item_scores(G, S2[0]), base * np.float32(scale))
+        ids2, sc2 = oracle.score_topk(G, S2, cfg.K)
+        assert np.array_equal(ids2, ids0) and np.array_equal(sc2, sc0 * np.float32(scale))
+    Sn = oracle.subitem_scores(-Q, cent)
+    assert np.array_equal(Sn, -S)
+    assert np.array_equal(oracle.item_scores(G, Sn[0]), -base + np.float32(0))
+    # the bottom of phi is the top of -phi
+    idn, scn = oracle.score_topk(G, Sn, 3)
+    worst = np.lexsort((np.arange(len(base)), base))[:3]
+    assert idn[0].tolist() == worst.tolist()
+
+
+def test_item_scores_left_to_right_fp32(oracle):
+    """The m-term sum is the left-to-right fp32 chain: reproduced with numpy fp32 scalar adds, and shown to
+    differ from a pairwise / float64 sum on some items (so the order is really pinned)."""
+    m, b, N = 16, 256, 4000
+    G = W.codes_uniform(N, m, b, seed=9)
+    S1 = W.normal_f32(W.stream_key(9, W.STREAM_QUERIES), m * b).reshape(m, b)
+    got = oracle.item_scores(G, S1)
+    chain = S1[0][G[:, 0]].copy()
+    for k in range(1, m):
+        chain = (chain + S1[k][G[:, k]]).astype(np.float32)
+    assert np.array_equal(got, chain + np.float32(0))
+    picked = np.stack([S1[k][G[:, k]] for k in range(m)], axis=1)
+    pairwise = picked.reshape(N, 8, 2).sum(axis=2, dtype=np.float32).reshape(N, 4, 2).sum(axis=2, dtype=np.float32)
+    pairwise = pairwise.reshape(N, 2, 2).sum(axis=2, dtype=np.float32).sum(axis=1, dtype=np.float32)
+    assert (pairwise != got).any()
+    assert np.abs(got - picked.astype(np.float64).sum(axis=1)).max() < 1e-5
+
+
+def test_loop_orders_agree_bitwise(oracle):
+    """Algorithm 1 (item-major) and Algorithm 2 (split-major accumulators) give the same bits."""
+    for m in (1, 3, 8, 16):
+        G = W.codes_uniform(5000, m, 256, seed=m)
+        S1 = W.normal_f32(W.stream_key(m, W.STREAM_QUERIES), m * 256).reshape(m, 256)
+        a = oracle.item_scores(G, S1)
+        b2 = oracle.item_scores(G, S1, split_major=True)
+        assert np.array_equal(a.view(np.uint32), b2.view(np.uint32))
+
+
+def test_negative_zero_is_canonicalised(oracle):
+    S1 = np.full((2, 4), -0.0, dtype=np.float32)
+    G = np.zeros((6, 2), dtype=np.uint8)
+    sc = oracle.item_scores(G, S1)
+    assert not np.signbit(sc).any()
+    S1[0, 1] = 0.0
+    G[3, 0] = 1
+    ids, top = oracle.score_topk(G, S1[None], 6)
+    assert ids[0].tolist() == [0, 1, 2, 3, 4, 5]          # -0 and +0 tie; id decides
+    assert not np.signbit(top).any()
+
+
+# ---------------------------------------------------------------- special cases that are library routines
+
+def test_m1_is_a_gather(oracle):
+    b, N, K = 256, 3000, 7
+    G = W.codes_uniform(N, 1, b, seed=2)
+    S = W.normal_f32(W.stream_key(2, W.STREAM_QUERIES), b).reshape(1, 1, b)
+    ids, sc = oracle.score_topk(G, S, K)
+    gathered = S[0, 0][G[:, 0]]
+    order = rank_order(gathered)[:K]
+    assert ids[0].tolist() == order.tolist() and np.array_equal(sc[0], gathered[order] + np.float32(0))
+
+
+def test_identity_codebook_is_matvec(oracle):
+    """m = 1, b = N, G[i] = i: PQTopK is the Transformer's default scoring r = W phi (Section 2)."""
+    N, d, K = 200, 1, 9
+    for d in (1, 5, 32):
+        cent = W.centroids(1, N, d, seed=d)          # W itself, [1][N][d]
+        Q = W.queries(2, d, seed=d)
+        G = np.arange(N, dtype=np.uint8).reshape(N, 1)
+        ids, sc = oracle.pqtopk(G, cent, Q, K)
+        r = cent[0].astype(np.float64) @ Q.astype(np.float64).T
+        for q in range(2):
+            assert_topk_matches_f64(ids[q], sc[q], r[:, q], K)
+
+
+def test_k1_is_argmax_and_kN_is_full_sort(oracle):
+    G = W.codes_uniform(777, 4, 16, seed=3)          # b = 16, m = 4: plenty of exact ties
+    S = np.round(W.normal_f32(W.stream_key(3, W.STREAM_QUERIES), 4 * 16).reshape(1, 4, 16) * 2) / 2
+    S = S.astype(np.float32)
+    sc = oracle.item_scores(G, S[0])
+    assert len(np.unique(sc)) < len(sc) // 4
+    ids1, s1 = oracle.score_topk(G, S, 1)
+    assert ids1[0, 0] == np.nonzero(sc == sc.max())[0].min() and s1[0, 0] == sc.max()
+    idsN, sN = oracle.score_topk(G, S, 777)
+    order = rank_order(sc)
+    assert idsN[0].tolist() == order.tolist() and np.array_equal(sN[0], sc[order])
+
+
+def test_topk_scan_equals_full_sort_definition(oracle):
+    rng = np.random.default_rng(7)
+    for trial in range(60):
+        N = int(rng.integers(1, 400))
+        K = int(rng.integers(1, N + 1))
+        levels = int(rng.integers(1, 50))
+        sc = rng.integers(-levels, levels + 1, size=N).astype(np.float32) / 4
+        a = oracle.topk(sc, K)
+        f = oracle.topk(sc, K, fullsort=True)
+        order = rank_order(sc)[:K]
+        assert a[0].tolist() == f[0].tolist() == order.tolist()
+        assert np.array_equal(a[1], sc[order]) and np.array_equal(f[1], sc[order])
+
+
+# ---------------------------------------------------------------- ties, duplicates, permutations
+
+def test_all_equal_codes(oracle):
+    G = np.full((500, 8), 17, dtype=np.uint8)
+    S = oracle.subitem_scores(W.queries(1, 64), W.centroids(8, 256, 64))
+    ids, sc = oracle.score_topk(G, S, 25)
+    assert ids[0].tolist() == list(range(25)) and len(set(sc[0].tolist())) == 1
+
+
+def test_duplicate_rows_tie_bitwise_and_straddle(oracle):
+    cfg = W.CONFIGS["finer"]
+    N, K = 30_000, cfg.K
+    G, cent, Q = W.make(cfg, B=2, N=N)
+    S = oracle.subitem_scores(Q, cent)
+    sc = oracle.item_scores(G, S[0])
+    _, src = W.duplicate_rows(W.codes_uniform(N, cfg.m, cfg.b, cfg.seed), 0.05, cfg.seed)
+    assert np.array_equal(sc.view(np.uint32), sc[src].view(np.uint32))
+    # K+3 copies of the best row: the tie straddles rank K and the K lowest ids win
+    planted = W.plant_ids(N, K + 3, seed=1)
+    W.plant_rows(G, planted, S[0].argmax(axis=1))
+    ids, top = oracle.score_topk(G, S, K)
+    assert ids[0].tolist() == planted[:K].tolist()
+    assert len(set(top[0].tolist())) == 1
+
+
+def test_permuting_items_permutes_ids(oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, Q = W.make(cfg)
+    S = oracle.subitem_scores(Q, cent)
+    ids, sc = oracle.score_topk(G, S, cfg.K)
+    perm = np.random.default_rng(0).permutation(cfg.N)
+    ids_p, sc_p = oracle.score_topk(np.ascontiguousarray(G[perm]), S, cfg.K)
+    assert np.array_equal(sc_p, sc)
+    assert perm[ids_p[0]].tolist() == ids[0].tolist()      # no ties in the top 10 on this seed
+
+
+def test_output_self_consistency(oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, _ = W.make(cfg)
+    Q = W.queries(5, cfg.d)
+    S = oracle.subitem_scores(Q, cent)
+    ids, sc = oracle.score_topk(G, S, 50)
+    for q in range(5):
+        full = oracle.item_scores(G, S[q])
+        assert np.array_equal(full[ids[q]], sc[q])
+        key = list(zip((-sc[q]).tolist(), ids[q].tolist()))
+        assert key == sorted(key) and len(set(key)) == 50
+        kth_s, kth_i = sc[q, -1], ids[q, -1]
+        ahead = np.sum((full > kth_s) | ((full == kth_s) & (np.arange(cfg.N) < kth_i)))
+        assert ahead == 49
+
+
+def test_argument_errors(oracle):
+    G = np.zeros((4, 2), dtype=np.uint8)
+    S = np.zeros((1, 2, 4), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.score_topk(G, S, 5)                 # K > N
+    with pytest.raises(ValueError):
+        oracle.score_topk(G, S, 0)
+    G[1, 1] = 4
+    with pytest.raises(ValueError):
+        oracle.score_topk(G, S, 1)                 # sub-id out of range for b = 4
+    with pytest.raises(ValueError):
+        oracle.subitem_scores(np.zeros((1, 5), np.float32), np.zeros((2, 4, 2), np.float32))
