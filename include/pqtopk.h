@@ -1,0 +1,98 @@
+/*
+ * pqtopk.h -- C ABI of the MI355X (gfx950) PQTopK scoring library.
+ *
+ * PQTopK (Petrov, Macdonald, Tonellotto, RecSys '24, Section 3) scores every item of a catalogue whose item
+ * embeddings are product-quantised (Section 2, "Sub-Id based recommendation"): item i carries m sub-ids
+ * G[i] = {g_i1..g_im} (Eq. 1), split k owns b sub-item embeddings psi_{k,j} of length d/m, and for a sequence
+ * embedding phi = phi_1 || .. || phi_m
+ *
+ *     S[k][j] = psi_{k,j} . phi_k                     (Eq. 4, the sub-id score matrix, once per query)
+ *     r_i     = sum_{k} S[k][G[i][k]]                 (Eq. 5, m additions per item)
+ *     result  = TopK(r, K)                            (Algorithm 1, V = I)
+ *
+ * Conventions shared by every entry point
+ *   - Indices are 0-based.  N = |I| items, d embedding dim, m splits, b sub-ids per split, B queries, K results.
+ *   - Every data pointer is a DEVICE pointer (HIP), dense row-major, owned by the caller for the whole call and
+ *     until the enqueued work has finished.  `codes` must be 16-byte aligned, every float / int array 4-byte
+ *     aligned (16-byte preferred).  The library allocates nothing, frees nothing and never synchronises: it
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is the default stream) and returns.
+ *   - Return value: PQ_OK (0) or a negative PQ_ERR_* code.  Arguments are validated on the host before any HIP
+ *     call; on an argument error nothing is enqueued and no output is touched.
+ *   - Arithmetic: fp32, round to nearest even, no flush to zero.  Eq. 4 is a left-to-right chain of fused
+ *     multiply-adds over the d/m elements starting from +0; Eq. 5 is a left-to-right chain of fp32 additions
+ *     over k = 0..m-1 starting from the k = 0 term; a finished score of -0 is returned as +0.
+ *   - TopK order: score descending, then item id ascending.  The result is unique and is returned sorted.
+ *   - Inputs must be finite and every sub-id must be < b; otherwise results are unspecified (no out-of-bounds
+ *     access happens for any uint8 sub-id).
+ */
+#ifndef PQTOPK_H
+#define PQTOPK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PQ_OK                0
+#define PQ_ERR_NULL         -1   /* a required pointer is NULL */
+#define PQ_ERR_SHAPE        -2   /* B, d, m, b, K or N < 1; d % m != 0; b > 256; K > N; N >= 2^31 */
+#define PQ_ERR_UNSUPPORTED  -3   /* valid problem, but outside what the kernels cover (see PQ_MAX_*) */
+#define PQ_ERR_WORKSPACE    -4   /* workspace smaller than pq_score_topk_workspace_bytes() */
+#define PQ_ERR_ALIGN        -5   /* a pointer is not aligned as required */
+#define PQ_ERR_HIP          -6   /* a HIP call (kernel launch) failed; pq_strerror() gives HIP's text */
+
+#define PQ_MAX_K     1024        /* largest K the top-K kernels keep per query */
+#define PQ_MAX_M      128        /* largest number of splits (score tables of m*256 floats must fit LDS) */
+#define PQ_MAX_B    65535        /* largest batch per call */
+
+/*
+ * Sub-id score matrix, Eq. 4 (Section 3): S[q][k][j] = psi_{k,j} . phi_{q,k}.
+ *   queries    in   float [B][d]        sequence embeddings; chunk k is elements k*d/m .. (k+1)*d/m - 1
+ *   centroids  in   float [m][b][d/m]   Psi_k, row j is psi_{k,j}
+ *   S          out  float [B][m][b]
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (B > PQ_MAX_B), PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_subitem_scores(const float* queries, const float* centroids, float* S,
+                      int B, int d, int m, int b, void* stream);
+
+/*
+ * Bytes of device workspace pq_score_topk() needs for this problem.  Pure host arithmetic, no HIP call.
+ * Returns 0 for arguments pq_score_topk() would reject.
+ */
+size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K);
+
+/*
+ * Algorithm 1 with V = I (Section 3): for each of B queries, score all N items by Eq. 5 from that query's S and
+ * return the K best <item id, score> pairs.  Item scores are never written to memory.
+ *   codes       in   uint8 [N][m]     codebook G (Eq. 1), sub-ids < b
+ *   S           in   float [B][m][b]  from pq_subitem_scores() (or any finite table)
+ *   out_ids     out  int32 [B][K]     rank r of query q at [q][r]; score descending, id ascending
+ *   out_scores  out  float [B][K]     the scores of those items
+ *   workspace        scratch of at least pq_score_topk_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned;
+ *                    contents on entry are irrelevant; calls sharing a workspace must not overlap in time
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (K > PQ_MAX_K, m > PQ_MAX_M, B > PQ_MAX_B, or m and K together
+ *         too large for the 160 KB of LDS: m*1 KB of score tables plus 32*nextpow2(K+64) bytes of candidates),
+ *         PQ_ERR_WORKSPACE, PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                  int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aid: runs pq_score_topk() `iters` times on `stream` with the catalogue scan kernel (the kernel that
+ * streams `codes`) bracketed by HIP events on that stream, waits for the stream, and stores the scan kernel's
+ * mean duration in milliseconds in *scan_ms (host pointer).  The one entry point that synchronises and that
+ * creates / destroys HIP events.  Same errors as pq_score_topk(); PQ_ERR_SHAPE if iters < 1.
+ */
+int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                          int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
+                          void* stream, int iters, float* scan_ms);
+
+/* Text for a PQ_* code; for PQ_ERR_HIP the text of the most recent HIP error seen by this thread. */
+const char* pq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQTOPK_H */

@@ -1,0 +1,129 @@
+"""Python names for the C ABI in include/pqtopk.h: argument marshalling only.
+
+Every computation happens in the HIP kernels of libpqtopk.so.  Tensors are torch CUDA (ROCm) tensors, used here
+only as device memory; work is enqueued on torch's current stream.  If the library has not been built the import
+of the first entry point raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpqtopk.so")
+
+PQ_OK, PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED, PQ_ERR_WORKSPACE, PQ_ERR_ALIGN, PQ_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+
+_lib = None
+
+
+class PQError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {pq_strerror(code)} (code {code})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it was never built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2408_09992_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        P, I, LL, SZ = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_size_t
+        L.pq_subitem_scores.argtypes = [P, P, P, I, I, I, I, P]
+        L.pq_subitem_scores.restype = I
+        L.pq_score_topk_workspace_bytes.argtypes = [LL, I, I, I, I]
+        L.pq_score_topk_workspace_bytes.restype = SZ
+        L.pq_score_topk.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
+        L.pq_score_topk.restype = I
+        L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
+        L.pq_score_topk_profile.restype = I
+        L.pq_strerror.argtypes = [I]
+        L.pq_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def pq_strerror(code: int) -> str:
+    return lib().pq_strerror(int(code)).decode()
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must live in device memory")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous {dtype}")
+    return t
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def pq_subitem_scores(queries: torch.Tensor, centroids: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 4: queries [B][d], centroids [m][b][d/m] -> S [B][m][b] (all fp32, on the device)."""
+    _dev(queries, torch.float32, "queries")
+    _dev(centroids, torch.float32, "centroids")
+    B, d = queries.shape
+    m, b, s = centroids.shape
+    if m * s != d:
+        raise PQError(PQ_ERR_SHAPE, "pq_subitem_scores")
+    S = out if out is not None else torch.empty((B, m, b), dtype=torch.float32, device=queries.device)
+    _dev(S, torch.float32, "S")
+    rc = lib().pq_subitem_scores(queries.data_ptr(), centroids.data_ptr(), S.data_ptr(), B, d, m, b, _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_subitem_scores")
+    return S
+
+
+def pq_score_topk_workspace_bytes(N: int, B: int, m: int, b: int, K: int) -> int:
+    return int(lib().pq_score_topk_workspace_bytes(N, B, m, b, K))
+
+
+def _topk_args(codes, S, K, workspace, out_ids, out_scores):
+    _dev(codes, torch.uint8, "codes")
+    _dev(S, torch.float32, "S")
+    N, m = codes.shape
+    B, m2, b = S.shape
+    if m2 != m:
+        raise PQError(PQ_ERR_SHAPE, "pq_score_topk")
+    need = pq_score_topk_workspace_bytes(N, B, m, b, K)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=codes.device)
+    if out_ids is None:
+        out_ids = torch.empty((B, K), dtype=torch.int32, device=codes.device)
+    if out_scores is None:
+        out_scores = torch.empty((B, K), dtype=torch.float32, device=codes.device)
+    _dev(out_ids, torch.int32, "out_ids")
+    _dev(out_scores, torch.float32, "out_scores")
+    return N, B, m, b, workspace, out_ids, out_scores
+
+
+def pq_score_topk(codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optional[torch.Tensor] = None,
+                  out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None
+                  ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Algorithm 1 (V = I): codes uint8 [N][m], S fp32 [B][m][b] -> (ids int32 [B][K], scores fp32 [B][K])."""
+    N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores)
+    rc = lib().pq_score_topk(codes.data_ptr(), S.data_ptr(), N, B, m, b, K, out_ids.data_ptr(),
+                             out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_score_topk")
+    return out_ids, out_scores
+
+
+def pq_score_topk_profile(codes: torch.Tensor, S: torch.Tensor, K: int, iters: int,
+                          workspace: Optional[torch.Tensor] = None) -> float:
+    """Mean duration (ms) of the catalogue scan kernel over `iters` calls, from HIP events on the stream."""
+    N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, None, None)
+    ms = ctypes.c_float(0.0)
+    rc = lib().pq_score_topk_profile(codes.data_ptr(), S.data_ptr(), N, B, m, b, K, out_ids.data_ptr(),
+                                     out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(),
+                                     iters, ctypes.byref(ms))
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_score_topk_profile")
+    return float(ms.value)

@@ -1,0 +1,132 @@
+"""The C-ABI library on a host without a GPU: it loads, exports what include/pqtopk.h declares, sizes its
+workspace by pure host arithmetic and rejects bad arguments before any HIP call (so dummy pointers are safe)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pqtopk.h")
+
+OK, NULL, SHAPE, UNSUPPORTED, WORKSPACE, ALIGN, HIP = 0, -1, -2, -3, -4, -5, -6
+
+
+@pytest.fixture(scope="module")
+def lib(pqlib_path):
+    L = ctypes.CDLL(pqlib_path)
+    P, I, LL, SZ = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_size_t
+    L.pq_subitem_scores.argtypes = [P, P, P, I, I, I, I, P]
+    L.pq_score_topk_workspace_bytes.argtypes = [LL, I, I, I, I]
+    L.pq_score_topk_workspace_bytes.restype = SZ
+    L.pq_score_topk.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
+    L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, P]
+    L.pq_strerror.argtypes = [I]
+    L.pq_strerror.restype = ctypes.c_char_p
+    return L
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert {"pq_subitem_scores", "pq_score_topk", "pq_score_topk_workspace_bytes", "pq_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_header_error_codes_match():
+    text = open(HEADER).read()
+    codes = dict(re.findall(r"#define\s+(PQ_[A-Z_]+)\s+(-?\d+)", text))
+    assert int(codes["PQ_OK"]) == OK and int(codes["PQ_ERR_NULL"]) == NULL and int(codes["PQ_ERR_SHAPE"]) == SHAPE
+    assert int(codes["PQ_ERR_UNSUPPORTED"]) == UNSUPPORTED and int(codes["PQ_ERR_WORKSPACE"]) == WORKSPACE
+    assert int(codes["PQ_ERR_ALIGN"]) == ALIGN and int(codes["PQ_ERR_HIP"]) == HIP
+
+
+def test_strerror(lib):
+    seen = set()
+    for c in (OK, NULL, SHAPE, UNSUPPORTED, WORKSPACE, ALIGN, HIP, -99):
+        msg = lib.pq_strerror(c)
+        assert msg and len(msg) > 1
+        seen.add(msg)
+    assert len(seen) == 8
+
+
+def test_workspace_bytes(lib):
+    ws = lib.pq_score_topk_workspace_bytes
+    big = ws(1_280_000, 1, 8, 256, 10)
+    assert big > 0 and big % 16 == 0
+    assert ws(1_280_000, 64, 8, 256, 10) >= 64 * 10 * 8
+    assert ws(50_000_000, 32, 8, 256, 10) > 0
+    assert ws(10, 1, 8, 256, 10) >= 80
+    for bad in ((0, 1, 8, 256, 10), (10, 0, 8, 256, 1), (10, 1, 0, 256, 1), (10, 1, 8, 0, 1), (10, 1, 8, 257, 1),
+                (10, 1, 8, 256, 0), (10, 1, 8, 256, 11), (2 ** 31, 1, 8, 256, 10), (10 ** 6, 1, 8, 256, 1025),
+                (10 ** 6, 1, 129, 256, 10), (10 ** 6, 65536, 8, 256, 10)):
+        assert ws(*bad) == 0, bad
+
+
+def test_subitem_scores_argument_errors(lib):
+    f = lib.pq_subitem_scores
+    p = 0x10000
+    assert f(None, p, p, 1, 64, 4, 256, None) == NULL
+    assert f(p, None, p, 1, 64, 4, 256, None) == NULL
+    assert f(p, p, None, 1, 64, 4, 256, None) == NULL
+    assert f(p, p, p, 0, 64, 4, 256, None) == SHAPE
+    assert f(p, p, p, 1, 0, 4, 256, None) == SHAPE
+    assert f(p, p, p, 1, 64, 0, 256, None) == SHAPE
+    assert f(p, p, p, 1, 64, 4, 0, None) == SHAPE
+    assert f(p, p, p, 1, 64, 4, 257, None) == SHAPE
+    assert f(p, p, p, 1, 66, 4, 256, None) == SHAPE          # d % m != 0
+    assert f(p, p, p, 65536, 64, 4, 256, None) == UNSUPPORTED
+    assert f(p + 2, p, p, 1, 64, 4, 256, None) == ALIGN
+
+
+def test_score_topk_argument_errors(lib):
+    f = lib.pq_score_topk
+    p = 0x10000
+    big = 1 << 30
+    good = dict(codes=p, S=p, N=1000, B=1, m=8, b=256, K=10, ids=p, sc=p, ws=p, wsb=big, st=None)
+
+    def call(**kw):
+        a = dict(good, **kw)
+        return f(a["codes"], a["S"], a["N"], a["B"], a["m"], a["b"], a["K"], a["ids"], a["sc"], a["ws"], a["wsb"],
+                 a["st"])
+
+    for name in ("codes", "S", "ids", "sc", "ws"):
+        assert call(**{name: None}) == NULL, name
+    assert call(N=0) == SHAPE and call(B=0) == SHAPE and call(m=0) == SHAPE and call(b=0) == SHAPE
+    assert call(K=0) == SHAPE and call(b=257) == SHAPE and call(K=1001) == SHAPE and call(N=2 ** 31) == SHAPE
+    assert call(N=10 ** 6, K=1025) == UNSUPPORTED and call(m=129) == UNSUPPORTED and call(B=65536) == UNSUPPORTED
+    assert call(N=10 ** 6, m=128, K=1024) == UNSUPPORTED                # tables + candidate lists exceed LDS
+    assert call(codes=p + 8) == ALIGN and call(ws=p + 4) == ALIGN and call(S=p + 1) == ALIGN
+    assert call(ids=p + 2) == ALIGN and call(sc=p + 3) == ALIGN
+    need = lib.pq_score_topk_workspace_bytes(1000, 1, 8, 256, 10)
+    assert call(wsb=need - 1) == WORKSPACE
+    # the profiling variant validates the same way, plus its own arguments
+    g = lib.pq_score_topk_profile
+    assert g(p, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 3, None) == NULL
+    out = ctypes.c_float(0)
+    assert g(p, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 0, ctypes.addressof(out)) == SHAPE
+    assert g(None, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 3, ctypes.addressof(out)) == NULL
+
+
+def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
+    from paper_2408_09992_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        binding.lib()
+
+
+def test_product_does_not_reach_the_oracle():
+    """Nothing in the package imports, loads or includes anything from oracle/."""
+    pkg = os.path.join(ROOT, "paper_2408_09992_amd")
+    pat = re.compile(r"^\s*(from|import)\s+oracle\b|pq_oracle|libpq_oracle|#include\s+\".*oracle", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                assert not pat.search(open(os.path.join(dirpath, fn)).read()), fn

@@ -1,0 +1,209 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+Bar: item ids bit-exact (ties to the lower id), scores within 1e-5 relative (they are in fact bit-equal, and the
+tests say so where they check it)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_09992_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-5
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_scores(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert np.all(np.abs(got - ref) <= REL * np.maximum(np.abs(ref), 1.0))
+
+
+def run_topk(pq, G, S, K):
+    ids, sc = pq.pq_score_topk(dev(G), dev(S), K)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), sc.cpu().numpy()
+
+
+def assert_same_topk(pq, oracle, G, S, K, tag=""):
+    print(f"case {tag} N={G.shape[0]} m={G.shape[1]} B={S.shape[0]} b={S.shape[2]} K={K}", flush=True)
+    ids, sc = run_topk(pq, G, S, K)
+    rid, rsc = oracle.score_topk(G, S, K)
+    assert np.array_equal(ids, rid), tag
+    check_scores(sc, rsc)
+    assert np.array_equal(sc.view(np.uint32), rsc.view(np.uint32)), tag      # stronger than the bar: same bits
+    return ids, sc
+
+
+# ---------------------------------------------------------------- Eq. 4
+
+@pytest.mark.parametrize("B,d,m,b", [(1, 64, 4, 256), (1, 512, 8, 256), (5, 512, 16, 256), (3, 96, 3, 7),
+                                     (2, 8, 8, 256), (64, 512, 8, 256), (2, 640, 5, 100), (1, 33, 1, 1)])
+def test_subitem_scores_bit_exact(pq, oracle, B, d, m, b):
+    print(f"case subitem B={B} d={d} m={m} b={b}", flush=True)
+    cent = W.centroids(m, b, d, seed=B + d)
+    Q = W.queries(B, d, seed=B + d)
+    S = pq.pq_subitem_scores(dev(Q), dev(cent))
+    torch.cuda.synchronize()
+    ref = oracle.subitem_scores(Q, cent)
+    got = S.cpu().numpy()
+    check_scores(got, ref)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+# ---------------------------------------------------------------- Algorithm 1, small shapes, several tiles + ragged tails
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 8, 16, 32, 64])
+def test_score_topk_small_shapes(pq, oracle, m):
+    for N in (1, 2, 5, 63, 64, 65, 127, 1000, 4099, 70_001):
+        for b in (256, 16):
+            for B in (1, 3):
+                G = W.codes_uniform(N, m, b, seed=N + m)
+                S = W.normal_f32(W.stream_key(N + m, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+                for K in sorted({1, min(N, 10), min(N, 100)}):
+                    assert_same_topk(pq, oracle, G, S, K, "small")
+
+
+def test_score_topk_large_k(pq, oracle):
+    for N, m, K in ((5000, 8, 1024), (3000, 4, 500), (1024, 16, 1024), (200_000, 8, 257)):
+        G = W.codes_uniform(N, m, 256, seed=K)
+        S = W.normal_f32(W.stream_key(K, W.STREAM_QUERIES), 2 * m * 256).reshape(2, m, 256)
+        assert_same_topk(pq, oracle, G, S, K, "largeK")
+
+
+# ---------------------------------------------------------------- ties and adversarial orders
+
+def test_all_items_equal(pq, oracle):
+    for N in (500, 100_000):
+        G = np.full((N, 8), 17, dtype=np.uint8)
+        S = W.normal_f32(W.stream_key(1, W.STREAM_QUERIES), 8 * 256).reshape(1, 8, 256)
+        ids, _ = assert_same_topk(pq, oracle, G, S, 25, "all-equal")
+        assert ids[0].tolist() == list(range(25))
+
+
+def test_coarse_tables_many_ties(pq, oracle):
+    G = W.codes_uniform(300_000, 4, 16, seed=3)
+    S = (np.round(W.normal_f32(W.stream_key(3, W.STREAM_QUERIES), 2 * 4 * 16) * 2) / 2).astype(np.float32)
+    assert_same_topk(pq, oracle, G, S.reshape(2, 4, 16), 100, "coarse")
+
+
+def digits_codes(N, m):
+    i = np.arange(N, dtype=np.int64)
+    return np.stack([(i >> (8 * k)) & 255 for k in range(m)], axis=1).astype(np.uint8)
+
+
+@pytest.mark.parametrize("sign", [1.0, -1.0])
+def test_monotone_scores(pq, oracle, sign):
+    """score == +-id exactly: ascending order makes every item beat the running threshold (worst case for the
+    candidate lists), descending makes none after the first K."""
+    N, m = 300_000, 4
+    G = digits_codes(N, m)
+    S = np.zeros((1, m, 256), dtype=np.float32)
+    for k in range(3):
+        S[0, k] = sign * np.arange(256, dtype=np.float32) * (256.0 ** k)
+    ids, sc = assert_same_topk(pq, oracle, G, S, 100, "monotone")
+    expect = np.arange(N - 1, N - 101, -1) if sign > 0 else np.arange(100)
+    assert ids[0].tolist() == expect.tolist()
+
+
+def test_negative_zero_tables(pq, oracle):
+    S = np.full((1, 2, 256), -0.0, dtype=np.float32)
+    S[0, 0, 1] = 0.0
+    G = W.codes_uniform(1000, 2, 2, seed=4)
+    ids, sc = assert_same_topk(pq, oracle, G, S, 50, "negzero")
+    assert ids[0].tolist() == list(range(50)) and not np.signbit(sc).any()
+
+
+def test_duplicates_and_straddle(pq, oracle):
+    cfg = W.CONFIGS["finer"]
+    N, K = 400_000, cfg.K
+    G, cent, Q = W.make(cfg, B=4, N=N)
+    S = pq.pq_subitem_scores(dev(Q), dev(cent)).cpu().numpy()
+    planted = W.plant_ids(N, K + 3, seed=1)
+    W.plant_rows(G, planted, S[0].argmax(axis=1))
+    ids, sc = assert_same_topk(pq, oracle, G, S, K, "dup+straddle")
+    assert ids[0].tolist() == planted[:K].tolist()
+
+
+def test_deterministic_and_workspace_reuse(pq, oracle):
+    cfg = W.CONFIGS["large"]
+    G, cent, Q = W.make(cfg, B=2, N=300_000)
+    Gd, Sd = dev(G), pq.pq_subitem_scores(dev(Q), dev(cent))
+    need = pq.pq_score_topk_workspace_bytes(G.shape[0], 2, cfg.m, cfg.b, cfg.K)
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")          # dirty workspace on purpose
+    a = pq.pq_score_topk(Gd, Sd, cfg.K, workspace=ws)
+    a = (a[0].clone(), a[1].clone())
+    ws.fill_(0x5C)
+    b2 = pq.pq_score_topk(Gd, Sd, cfg.K, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b2[0]) and torch.equal(a[1], b2[1])
+    rid, _ = oracle.score_topk(G, Sd.cpu().numpy(), cfg.K)
+    assert np.array_equal(a[0].cpu().numpy(), rid)
+
+
+def test_errors_reach_python(pq):
+    G = dev(W.codes_uniform(100, 8))
+    S = dev(np.zeros((1, 8, 256), dtype=np.float32))
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_score_topk(G, S, 101)
+    assert e.value.code == pq.PQ_ERR_SHAPE
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_score_topk(G, S, 10, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == pq.PQ_ERR_WORKSPACE
+
+
+# ---------------------------------------------------------------- the named configurations at full size
+
+def end_to_end(pq, oracle, cfg, B, G=None):
+    print(f"config {cfg.name} B={B}", flush=True)
+    G0, cent, Q = W.make(cfg, B=B) if G is None else (G, W.centroids(cfg.m, cfg.b, cfg.d, cfg.seed),
+                                                       W.queries(B, cfg.d, cfg.seed))
+    Gd = dev(G0)
+    S = pq.pq_subitem_scores(dev(Q), dev(cent))
+    ids, sc = pq.pq_score_topk(Gd, S, cfg.K)
+    torch.cuda.synchronize()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    rid, rsc = oracle.pqtopk(G0, cent, Q, cfg.K)
+    assert np.array_equal(ids, rid)
+    check_scores(sc, rsc)
+    assert np.array_equal(sc.view(np.uint32), rsc.view(np.uint32))
+    return G0, cent, Q, ids, sc
+
+
+def test_config_tiny_brute_force(pq, oracle):
+    cfg = W.CONFIGS["tiny"]
+    G, cent, Q, ids, sc = end_to_end(pq, oracle, cfg, 1)
+    bid, bsc = oracle.bruteforce_topk(G, cent, Q, cfg.K)
+    assert np.array_equal(ids, bid)
+    check_scores(sc, bsc)
+
+
+@pytest.fixture(scope="module")
+def large_codes():
+    return W.codes_uniform(1_280_000, 8)
+
+
+@pytest.mark.parametrize("B", [1, 64])
+def test_config_large(pq, oracle, large_codes, B):
+    end_to_end(pq, oracle, W.CONFIGS["large"], B, G=large_codes)
+
+
+def test_config_serving_zipf(pq, oracle):
+    end_to_end(pq, oracle, W.CONFIGS["serving"], 1024)
+
+
+def test_config_finer_with_duplicates(pq, oracle):
+    cfg = W.CONFIGS["finer"]
+    G, cent, Q, ids, sc = end_to_end(pq, oracle, cfg, 16)
+    # ties really occur among the returned entries
+    assert sum(len(set(row.tolist())) < cfg.K for row in sc) >= 1
+
+
+def test_config_huge(pq, oracle):
+    cfg = W.CONFIGS["huge"]
+    G = W.codes_uniform(cfg.N, cfg.m)
+    end_to_end(pq, oracle, cfg, 1, G=G)
+    end_to_end(pq, oracle, cfg, 32, G=G)
