@@ -43,7 +43,7 @@ extern "C" {
 #define PQ_ERR_ALIGN        -5   /* a pointer is not aligned as required */
 #define PQ_ERR_HIP          -6   /* a HIP call (kernel launch) failed; pq_strerror() gives HIP's text */
 
-#define PQ_MAX_K     1024        /* largest K the top-K kernels keep per query */
+#define PQ_MAX_K      512        /* largest K the top-K kernels keep per query */
 #define PQ_MAX_M      128        /* largest number of splits (score tables of m*256 floats must fit LDS) */
 #define PQ_MAX_B    65535        /* largest batch per call */
 
@@ -70,10 +70,14 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K);
  *   S           in   float [B][m][b]  from pq_subitem_scores() (or any finite table)
  *   out_ids     out  int32 [B][K]     rank r of query q at [q][r]; score descending, id ascending
  *   out_scores  out  float [B][K]     the scores of those items
- *   workspace        scratch of at least pq_score_topk_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned;
- *                    contents on entry are irrelevant; calls sharing a workspace must not overlap in time
+ *   workspace        scratch of at least pq_score_topk_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned.
+ *                    It needs no initialisation: its first words are per-query arrival tickets stamped with a
+ *                    40-bit per-call generation number, and a ticket that carries another generation (left by an
+ *                    earlier call, or arbitrary bytes) is restarted by the first workgroup that meets it.  Calls
+ *                    that share a workspace must not overlap in time
  * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (K > PQ_MAX_K, m > PQ_MAX_M, B > PQ_MAX_B, or m and K together
- *         too large for the 160 KB of LDS: m*1 KB of score tables plus 32*nextpow2(K+64) bytes of candidates),
+ *         too large for the 160 KB of LDS: m KB of score tables plus about 80*nextpow2(K+64) bytes of candidate
+ *         lists; every K <= 512 fits with m <= 64, and m = 128 fits with K <= 64),
  *         PQ_ERR_WORKSPACE, PQ_ERR_ALIGN, PQ_ERR_HIP.
  */
 int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,

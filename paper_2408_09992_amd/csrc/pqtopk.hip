@@ -6,21 +6,41 @@
 //
 // Total order used everywhere: a 64-bit key  (orderable(score) << 32) | ~id.  A larger key is a better item:
 // higher score first, lower id between equal scores.  Keys of distinct items are distinct, key 0 means "empty".
+//
+// Shape of pq_score_topk(): ONE launch.  grid = (item blocks, B).  A workgroup
+//   1. copies its query's m x b table into LDS and derives the score range [lo, hi] from the per-split extremes;
+//   2. scores a first round of items into registers and histograms them over 1024 equal-width score buckets; the
+//      bucket that holds the K-th best gives a score cut: everything below it is out for good;
+//   3. streams the rest of its share of G against that cut; survivors (a handful) go to small per-wave lists in
+//      LDS that are pruned exactly (by key) when they fill;
+//   4. selects its exact K best and writes them to the workspace; the workgroup that arrives last at the query's
+//      ticket folds all workgroups' lists into the final sorted K.
+// The histogram only ever prunes; every decision that picks a winner compares full keys, so the result is exact
+// for any input, including heavy ties (which merely take slower paths).
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
+
+#include <atomic>
+#include <chrono>
 
 #include "pqtopk.h"
 
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kScanThreads = 256;                 // 4 waves per workgroup
-constexpr int kScanWaves = kScanThreads / kWave;
-constexpr int kLutStride = 256;                   // table entries per split in LDS (uint8 sub-ids never run past it)
-constexpr int kMergeThreads = 256;
+constexpr int kThreads = 512;                     // scan workgroup: 8 waves
+constexpr int kWaves = kThreads / kWave;
+constexpr int kLutStride = 256;                   // table entries per split in LDS (a uint8 sub-id never runs past it)
+constexpr int kBins = 1024;                       // score buckets of the pruning histogram
+// 16-byte code vectors a thread holds per round: 4 for m >= 8, fewer for small m so a thread never holds > 16 items
+__host__ __device__ constexpr int vec_per_thread(int m) { return m >= 8 ? 4 : (m == 4 ? 2 : 1); }
+constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
+constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
 constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace
+constexpr int kTicketBytes = 256;                 // one ticket per query, padded
 
 __device__ __forceinline__ uint32_t orderable_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -62,24 +82,120 @@ __device__ void bitonic_sort_desc(uint64_t* a, int n, int tid, int nthr) {
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Eq. 4.  One thread per (query, split, sub-id): a left-to-right chain of fused multiply-adds over the d/m
-// elements, starting from +0.
-__global__ __launch_bounds__(256) void subitem_scores_kernel(const float* __restrict__ queries,
-                                                             const float* __restrict__ centroids,
-                                                             float* __restrict__ S, int d, int m, int b) {
-    const int s = d / m;
-    const int kj = blockIdx.x * 256 + threadIdx.x;       // k * b + j
-    const int q = blockIdx.y;
+// Eq. 4.  One thread per (split, sub-id) and a tile of queries: the thread keeps its sub-item embedding in
+// registers and, per query, runs the left-to-right chain of fused multiply-adds over the d/m elements from +0.
+constexpr int kSubThreads = 64;
+constexpr int kSubQueryTile = 16;
+
+template <int S_ELEMS>   // d/m when it is one of the unrolled sizes, else 0 (runtime loop)
+__global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float* __restrict__ queries,
+                                                                     const float* __restrict__ centroids,
+                                                                     float* __restrict__ S, int B, int d, int m, int b) {
+    const int s = S_ELEMS ? S_ELEMS : d / m;
+    const int kj = blockIdx.x * kSubThreads + threadIdx.x;       // k * b + j
+    const int q0 = blockIdx.y * kSubQueryTile;
     if (kj >= m * b) return;
     const int k = kj / b;
     const float* psi = centroids + (size_t)kj * s;
-    const float* phi = queries + (size_t)q * d + (size_t)k * s;
-    float acc = 0.0f;
-    for (int t = 0; t < s; ++t) acc = __builtin_fmaf(psi[t], phi[t], acc);
-    S[(size_t)q * m * b + kj] = acc;
+    int q1 = q0 + kSubQueryTile;
+    if (q1 > B) q1 = B;
+    if (S_ELEMS) {
+        float w[S_ELEMS ? S_ELEMS : 1];
+        if ((S_ELEMS % 4) == 0 && (((uintptr_t)psi) & 15) == 0) {
+            const float4* p4 = reinterpret_cast<const float4*>(psi);
+#pragma unroll
+            for (int t = 0; t < S_ELEMS / 4; ++t) {
+                float4 v = p4[t];
+                w[4 * t] = v.x; w[4 * t + 1] = v.y; w[4 * t + 2] = v.z; w[4 * t + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < S_ELEMS; ++t) w[t] = psi[t];
+        }
+        for (int q = q0; q < q1; ++q) {
+            const float* phi = queries + (size_t)q * d + (size_t)k * S_ELEMS;
+            float acc = 0.0f;
+#pragma unroll
+            for (int t = 0; t < S_ELEMS; ++t) acc = __builtin_fmaf(w[t], phi[t], acc);
+            S[(size_t)q * m * b + kj] = acc;
+        }
+    } else {
+        for (int q = q0; q < q1; ++q) {
+            const float* phi = queries + (size_t)q * d + (size_t)k * s;
+            float acc = 0.0f;
+            for (int t = 0; t < s; ++t) acc = __builtin_fmaf(psi[t], phi[t], acc);
+            S[(size_t)q * m * b + kj] = acc;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// Small per-workgroup control block in LDS.
+struct Ctl {
+    float lo;            // lower end of the score range
+    float scale;         // buckets per unit of score (0: range degenerate, histogram off)
+    float cut;           // scores <= cut cannot reach this workgroup's top K (valid after a histogram pass)
+    int bstar;           // bucket of the K-th best in the histogrammed set
+    int ncand;           // candidates collected for an exact selection
+    int is_last;         // this workgroup took the query's last ticket
+    int wave_cnt[kWaves];
+    float smin[PQ_MAX_M];
+    float smax[PQ_MAX_M];
+};
+
+__device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
+    // monotone non-decreasing in score: subtract, multiply by a non-negative, truncate (negative and NaN give 0)
+    float x = (score - lo) * scale;
+    int bkt = (x > 0.0f) ? (int)x : 0;
+    return bkt > kBins - 1 ? kBins - 1 : bkt;
+}
+
+// Wave 0: find the highest bucket b* such that buckets >= b* hold at least K entries (0 if there are fewer than K in
+// all), and a score cut that every entry of a bucket >= b* exceeds.  hist has kBins counters.
+__device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
+    constexpr int per = kBins / kWave;                       // 16 buckets per lane, lane 63 owns the top ones
+    uint32_t c[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < per; ++i) { c[i] = hist[lane * per + i]; mine += c[i]; }
+    uint32_t suffix = mine;                                  // entries in this lane's buckets and above
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        uint32_t other = __shfl_down(suffix, off, kWave);
+        if (lane + off < kWave) suffix += other;
+    }
+    uint64_t has = __ballot(suffix >= (uint32_t)K);
+    int bstar = 0;
+    if (has != 0) {
+        int owner = 63 - __builtin_clzll(has);               // highest lane whose suffix reaches K
+        if (lane == owner) {
+            uint32_t above = suffix - mine;
+            int found = -1;
+#pragma unroll
+            for (int i = per - 1; i >= 0; --i) {
+                above += c[i];
+                if (found < 0 && above >= (uint32_t)K) found = i;
+            }
+            ctl->bstar = lane * per + (found < 0 ? 0 : found);
+        }
+    } else if (lane == 0) {
+        ctl->bstar = 0;
+    }
+    wave_sync();
+    bstar = ctl->bstar;
+    if (lane == 0) {
+        // a score cut with bucket_of(cut) < b*: by monotonicity every entry of a bucket >= b* is > cut
+        float cut = -__builtin_inff();
+        if (bstar > 0 && ctl->scale > 0.0f) {
+            float width = 1.0f / ctl->scale;
+            cut = ctl->lo + ((float)bstar - 0.5f) * width;
+            for (int guard = 0; guard < 64 && bucket_of(cut, ctl->lo, ctl->scale) >= bstar; ++guard) cut -= width;
+            if (bucket_of(cut, ctl->lo, ctl->scale) >= bstar) cut = -__builtin_inff();
+        }
+        ctl->cut = cut;
+    }
+}
+
 // Per-wave candidate list in LDS: `cap` keys, `cnt` of them in use, `thr` = K-th best key once K are known.
 struct WaveTopK {
     uint64_t* buf;
@@ -97,7 +213,7 @@ struct WaveTopK {
     }
 
     // every lane offers one key (0 = nothing); keys above the threshold are appended
-    __device__ void offer(uint64_t key, int lane) {
+    __device__ __forceinline__ void offer(uint64_t key, int lane) {
         bool pass = key > thr;
         uint64_t mask = __ballot(pass);
         if (mask == 0) return;
@@ -115,147 +231,366 @@ struct WaveTopK {
     }
 };
 
-// Eq. 5 for one item whose m sub-ids sit in `c` (M bytes, little-endian packed): left-to-right fp32 sum.
+// Exact selection of the K best among the nonzero keys of src[0..n) (LDS, zeros allowed anywhere), written sorted
+// to dst[0..K) (zero-filled if fewer than K exist).  All kThreads threads call it.  `cand` holds candmax keys,
+// `hist` kBins counters.  If the histogram cannot narrow the set to candmax keys (ties, degenerate range), src is
+// sorted in place instead, which needs n to be a power of two.  dst may alias cand only if it does not alias src.
+__device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_t* cand, int candmax, uint32_t* hist,
+                             Ctl* ctl, int tid) {
+    const int lane = tid & (kWave - 1);
+    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+    if (tid == 0) ctl->ncand = 0;
+    __syncthreads();
+    const float lo = ctl->lo, scale = ctl->scale;
+    for (int i = tid; i < n; i += kThreads) {
+        uint64_t key = src[i];
+        if (key) atomicAdd(&hist[bucket_of(score_of_key(key), lo, scale)], 1u);
+    }
+    __syncthreads();
+    if (tid < kWave) find_cut(hist, K, ctl, lane);
+    __syncthreads();
+    const int bstar = ctl->bstar;
+    for (int i = tid; i < n; i += kThreads) {
+        uint64_t key = src[i];
+        if (key && bucket_of(score_of_key(key), lo, scale) >= bstar) {
+            int pos = atomicAdd(&ctl->ncand, 1);
+            if (pos < candmax) cand[pos] = key;
+        }
+    }
+    __syncthreads();
+    const int C = ctl->ncand;
+    if (C <= candmax) {
+        // rank by counting: position of a key = number of candidates that beat it
+        for (int i = tid; i < K; i += kThreads) dst[i] = 0;
+        __syncthreads();
+        for (int t = tid; t < C; t += kThreads) {
+            uint64_t mine = cand[t];
+            int rank = 0;
+            for (int u = 0; u < C; ++u) rank += (cand[u] > mine) ? 1 : 0;
+            if (rank < K) dst[rank] = mine;
+        }
+        __syncthreads();
+    } else {
+        bitonic_sort_desc<true>(src, n, tid, kThreads);
+        for (int i = tid; i < K; i += kThreads) dst[i] = src[i];
+        __syncthreads();
+    }
+}
+
+// One arrival at a query's ticket.  The ticket holds (generation << 24 | arrivals); a ticket left by an earlier call
+// carries another generation and is restarted by whoever sees it first.  Returns this arrival's number, 1-based.
+__device__ uint32_t ticket_arrive(unsigned long long* ticket, unsigned long long gen) {
+    unsigned long long old = atomicAdd(ticket, 1ull);
+    if ((old >> 24) == gen) return (uint32_t)(old & 0xFFFFFFull) + 1u;
+    for (;;) {                                    // each failed exchange means another arrival succeeded: bounded
+        unsigned long long cur = atomicAdd(ticket, 0ull);
+        unsigned long long nxt = ((cur >> 24) == gen) ? cur + 1ull : ((gen << 24) | 1ull);
+        if (atomicCAS(ticket, cur, nxt) == cur) return (uint32_t)(nxt & 0xFFFFFFull);
+    }
+}
+
+// LDS layout of the scan kernel (dynamic): lut | hist | ctl | wave lists | cand | sorted
+struct ScanLds {
+    float* lut;
+    uint32_t* hist;
+    Ctl* ctl;
+    uint64_t* lists;     // kWaves * cap, also the staging area of the grid-level fold
+    uint64_t* cand;      // candmax
+    uint64_t* sorted;    // K rounded up
+};
+
+__host__ __device__ inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+__host__ __device__ inline size_t scan_lds_bytes(int m, int cap, int candmax, int K, int stage_keys) {
+    size_t lists = (size_t)kWaves * cap;
+    if (lists < (size_t)stage_keys) lists = stage_keys;
+    return align16((size_t)m * kLutStride * sizeof(float)) + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)) +
+           lists * sizeof(uint64_t) + (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
+}
+
+__device__ inline ScanLds carve(unsigned char* smem, int m, int cap, int candmax, int stage_keys) {
+    ScanLds L;
+    size_t off = 0;
+    L.lut = reinterpret_cast<float*>(smem + off);        off += align16((size_t)m * kLutStride * sizeof(float));
+    L.hist = reinterpret_cast<uint32_t*>(smem + off);    off += kBins * sizeof(uint32_t);
+    L.ctl = reinterpret_cast<Ctl*>(smem + off);          off += align16(sizeof(Ctl));
+    size_t lists = (size_t)kWaves * cap;
+    if (lists < (size_t)stage_keys) lists = stage_keys;
+    L.lists = reinterpret_cast<uint64_t*>(smem + off);   off += lists * sizeof(uint64_t);
+    L.cand = reinterpret_cast<uint64_t*>(smem + off);    off += (size_t)candmax * sizeof(uint64_t);
+    L.sorted = reinterpret_cast<uint64_t*>(smem + off);
+    return L;
+}
+
+struct ScanArgs {
+    const uint8_t* codes;
+    const float* S;
+    long long N;
+    int m, b, K;
+    int cap;             // keys per wave list (power of two >= K + 64)
+    int candmax;         // keys of the exact-selection candidate array
+    int stage_keys;      // power of two: keys the fold stages per pass
+    unsigned long long* tickets;   // [B], kTicketBytes apart
+    uint64_t* ws_keys;   // [B][nblk][K]
+    unsigned long long gen;
+    int* out_ids;
+    float* out_scores;
+};
+
+// Items a thread holds per round and how it loads / scores them.  M > 0: m is M and one 16-byte vector carries
+// 16/M items; M == 0: any m, one item per slot, row loads sized by m's alignment.
 template <int M>
-__device__ __forceinline__ float item_score(const float* lut, const uint32_t* words, int first_byte) {
+struct Round {
+    static constexpr int kVecs = M ? vec_per_thread(M) : 0;
+    static constexpr int kItems = M ? kVecs * (16 / M) : kGenericItemsPerThread;
+    static constexpr int kUnitsPerThread = M ? kVecs : kGenericItemsPerThread;           // lane-sized units of work
+};
+
+template <int M>
+__device__ __forceinline__ float score_packed(const float* lut, const uint32_t* words, int first_byte) {
     float acc = 0.0f;
 #pragma unroll
     for (int k = 0; k < M; ++k) {
         int byte = first_byte + k;
         uint32_t code = (words[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
         float v = lut[k * kLutStride + code];
-        acc = (k == 0) ? v : acc + v;
+        acc = (k == 0) ? v : acc + v;                 // Eq. 5, left to right
+    }
+    return acc + 0.0f;                                // -0 becomes +0
+}
+
+__device__ float score_row(const float* lut, const uint8_t* row, int m) {
+    float acc = 0.0f;
+    if ((m & 15) == 0) {
+        const uint4* p = reinterpret_cast<const uint4*>(row);
+        for (int v = 0; v < (m >> 4); ++v) {
+            uint4 x = p[v];
+            uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                float t = lut[(v * 16 + k) * kLutStride + ((w[k >> 2] >> ((k & 3) * 8)) & 0xFFu)];
+                acc = (v == 0 && k == 0) ? t : acc + t;
+            }
+        }
+    } else if ((m & 3) == 0) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(row);
+        for (int v = 0; v < (m >> 2); ++v) {
+            uint32_t w = p[v];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float t = lut[(v * 4 + k) * kLutStride + ((w >> (k * 8)) & 0xFFu)];
+                acc = (v == 0 && k == 0) ? t : acc + t;
+            }
+        }
+    } else {
+        acc = lut[row[0]];
+        for (int k = 1; k < m; ++k) acc = acc + lut[k * kLutStride + row[k]];
     }
     return acc + 0.0f;
 }
 
-// Catalogue scan, m in {1,2,4,8,16}: one 16-byte load carries 16/M whole items.
-// grid = (item blocks, B).  Dynamic LDS: float lut[M*256]; uint64 wavebuf[kScanWaves][cap].
+// Scores of the items this thread owns in round `r` of its workgroup.  item ids in id[], validity by id < N.
 template <int M>
-__global__ __launch_bounds__(kScanThreads) void scan_topk_vec_kernel(const uint8_t* __restrict__ codes,
-                                                                     const float* __restrict__ S, long long N,
-                                                                     int b, int K, int cap,
-                                                                     uint64_t* __restrict__ ws) {
-    constexpr int IPV = 16 / M;
-    extern __shared__ __align__(16) unsigned char smem[];
-    float* lut = reinterpret_cast<float*>(smem);
-    uint64_t* bufs = reinterpret_cast<uint64_t*>(smem + (size_t)M * kLutStride * sizeof(float));
-
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int q = blockIdx.y, nblk = gridDim.x;
-
-    const float* Sq = S + (size_t)q * M * b;
-    for (int e = tid; e < M * kLutStride; e += kScanThreads) {
-        int k = e / kLutStride, j = e % kLutStride;
-        lut[e] = (j < b) ? Sq[k * b + j] : 0.0f;
-    }
-    __syncthreads();
-
-    WaveTopK top{bufs + (size_t)wave * cap, cap, K, 0, 0ull};
-
-    const long long total_bytes = N * M;
-    const long long total_vecs = (total_bytes + 15) / 16;
-    const long long full_vecs = total_bytes / 16;
-    const uint4* cvec = reinterpret_cast<const uint4*>(codes);
-
-    for (long long base = (long long)blockIdx.x * kScanThreads + wave * kWave; base < total_vecs;
-         base += (long long)nblk * kScanThreads) {
-        const long long v = base + lane;
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-        if (v < full_vecs) {
-            uint4 x = cvec[v];
-            w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
-        } else if (v < total_vecs) {                      // ragged last vector: byte loads
-            for (long long a = v * 16; a < total_bytes; ++a) {
-                int o = (int)(a - v * 16);
-                w[o >> 2] |= (uint32_t)codes[a] << ((o & 3) * 8);
+__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long unit_base, int tid,
+                                            float (&sc)[Round<M>::kItems], uint32_t (&id)[Round<M>::kItems]) {
+    if constexpr (M > 0) {
+        constexpr int IPV = 16 / M;
+        constexpr int kVecPerThread = Round<M>::kVecs;
+        const long long total_bytes = a.N * M;
+        const long long full_vecs = total_bytes / 16;
+        const long long total_vecs = (total_bytes + 15) / 16;
+        const uint4* cvec = reinterpret_cast<const uint4*>(a.codes);
+        uint32_t w[kVecPerThread][4];
+#pragma unroll
+        for (int u = 0; u < kVecPerThread; ++u) {
+            const long long v = unit_base + (long long)u * kThreads + tid;
+            w[u][0] = w[u][1] = w[u][2] = w[u][3] = 0u;
+            if (v < full_vecs) {
+                uint4 x = cvec[v];
+                w[u][0] = x.x; w[u][1] = x.y; w[u][2] = x.z; w[u][3] = x.w;
+            } else if (v < total_vecs) {              // ragged last vector: byte loads
+                for (long long p = v * 16; p < total_bytes; ++p) {
+                    int o = (int)(p - v * 16);
+                    w[u][o >> 2] |= (uint32_t)a.codes[p] << ((o & 3) * 8);
+                }
             }
         }
 #pragma unroll
-        for (int e = 0; e < IPV; ++e) {
-            const long long item = v * IPV + e;
-            float sc = item_score<M>(lut, w, e * M);
-            uint64_t key = (item < N) ? make_key(sc, (uint32_t)item) : 0ull;
+        for (int u = 0; u < kVecPerThread; ++u) {
+            const long long v = unit_base + (long long)u * kThreads + tid;
+#pragma unroll
+            for (int e = 0; e < IPV; ++e) {
+                id[u * IPV + e] = (uint32_t)(v * IPV + e);
+                sc[u * IPV + e] = score_packed<M>(lut, w[u], e * M);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kGenericItemsPerThread; ++u) {
+            const long long item = unit_base + (long long)u * kThreads + tid;
+            id[u] = (uint32_t)item;
+            sc[u] = (item < a.N) ? score_row(lut, a.codes + item * a.m, a.m) : 0.0f;
+        }
+    }
+}
+
+template <int M>
+__global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int m = M ? M : a.m;
+    const ScanLds L = carve(smem, m, a.cap, a.candmax, a.stage_keys);
+    Ctl* ctl = L.ctl;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int q = blockIdx.y, nblk = gridDim.x, K = a.K, b = a.b;
+    constexpr int kItems = Round<M>::kItems;
+    constexpr int kUnits = Round<M>::kUnitsPerThread;
+
+    // ---- 1. table into LDS, score range from the per-split extremes
+    const float* Sq = a.S + (size_t)q * m * b;
+    for (int e = tid; e < m * kLutStride; e += kThreads) {
+        int k = e / kLutStride, j = e % kLutStride;
+        L.lut[e] = (j < b) ? Sq[k * b + j] : 0.0f;
+    }
+    for (int i = tid; i < kBins; i += kThreads) L.hist[i] = 0;
+    __syncthreads();
+    for (int k = wave; k < m; k += kWaves) {              // one wave reduces one split
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        for (int j = lane; j < b; j += kWave) {
+            float v = L.lut[k * kLutStride + j];
+            mn = fminf(mn, v); mx = fmaxf(mx, v);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            mn = fminf(mn, __shfl_xor(mn, off, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        }
+        if (lane == 0) { ctl->smin[k] = mn; ctl->smax[k] = mx; }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float lo = 0.0f, hi = 0.0f;
+        for (int k = 0; k < m; ++k) { lo += ctl->smin[k]; hi += ctl->smax[k]; }
+        float range = hi - lo;
+        float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
+        if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
+        ctl->lo = lo;
+        ctl->scale = scale;
+        ctl->cut = -__builtin_inff();
+        ctl->bstar = 0;
+    }
+    __syncthreads();
+    const float lo = ctl->lo, scale = ctl->scale;
+
+    // ---- 2. first round: scores in registers, histogram, cut
+    const long long total_units = M ? (a.N * M + 15) / 16 : a.N;
+    const long long round_units = (long long)kThreads * kUnits;
+    const long long rounds = (total_units + round_units - 1) / round_units;
+
+    WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, 0, 0ull};
+
+    long long r = blockIdx.x;
+    if (r < rounds) {
+        float sc[kItems];
+        uint32_t id[kItems];
+        score_round<M>(a, L.lut, r * round_units, tid, sc, id);
+        int bk[kItems];
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            bk[e] = bucket_of(sc[e], lo, scale);
+            if (id[e] < a.N) atomicAdd(&L.hist[bk[e]], 1u);
+        }
+        __syncthreads();
+        if (tid < kWave) find_cut(L.hist, K, ctl, lane);
+        __syncthreads();
+        const int bstar = ctl->bstar;
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            uint64_t key = (id[e] < a.N && bk[e] >= bstar) ? make_key(sc[e], id[e]) : 0ull;
+            top.offer(key, lane);
+        }
+        r += nblk;
+    }
+
+    // ---- 3. stream the remaining rounds against the cut
+    const float cut = ctl->cut;
+    for (; r < rounds; r += nblk) {
+        float sc[kItems];
+        uint32_t id[kItems];
+        score_round<M>(a, L.lut, r * round_units, tid, sc, id);
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) any = any || (sc[e] > cut && id[e] < a.N);
+        if (__ballot(any) == 0) continue;
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            uint64_t key = (sc[e] > cut && id[e] < a.N) ? make_key(sc[e], id[e]) : 0ull;
             top.offer(key, lane);
         }
     }
 
-    // wave -> block: every wave leaves its K best (sorted) at the front of its buffer, zeros behind
-    top.prune(lane);
-    for (int t = top.cnt + lane; t < cap; t += kWave) top.buf[t] = 0;
+    // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
+    if (lane == 0) ctl->wave_cnt[wave] = top.cnt;
     __syncthreads();
-    bitonic_sort_desc<true>(bufs, kScanWaves * cap, tid, kScanThreads);
-    uint64_t* out = ws + ((size_t)q * nblk + blockIdx.x) * K;
-    for (int t = tid; t < K; t += kScanThreads) out[t] = bufs[t];
-}
-
-// Catalogue scan for any other m: one lane per item, byte loads.
-__global__ __launch_bounds__(kScanThreads) void scan_topk_item_kernel(const uint8_t* __restrict__ codes,
-                                                                      const float* __restrict__ S, long long N,
-                                                                      int m, int b, int K, int cap,
-                                                                      uint64_t* __restrict__ ws) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    float* lut = reinterpret_cast<float*>(smem);
-    uint64_t* bufs = reinterpret_cast<uint64_t*>(smem + (size_t)m * kLutStride * sizeof(float));
-
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int q = blockIdx.y, nblk = gridDim.x;
-
-    const float* Sq = S + (size_t)q * m * b;
-    for (int e = tid; e < m * kLutStride; e += kScanThreads) {
-        int k = e / kLutStride, j = e % kLutStride;
-        lut[e] = (j < b) ? Sq[k * b + j] : 0.0f;
+    int total = 0, before = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        int c = ctl->wave_cnt[w];
+        if (w < wave) before += c;
+        total += c;
     }
-    __syncthreads();
-
-    WaveTopK top{bufs + (size_t)wave * cap, cap, K, 0, 0ull};
-
-    for (long long base = (long long)blockIdx.x * kScanThreads + wave * kWave; base < N;
-         base += (long long)nblk * kScanThreads) {
-        const long long item = base + lane;
-        uint64_t key = 0ull;
-        if (item < N) {
-            const uint8_t* g = codes + item * m;
-            float acc = lut[g[0]];
-            for (int k = 1; k < m; ++k) acc = acc + lut[k * kLutStride + g[k]];
-            key = make_key(acc + 0.0f, (uint32_t)item);
-        }
-        top.offer(key, lane);
-    }
-
-    top.prune(lane);
-    for (int t = top.cnt + lane; t < cap; t += kWave) top.buf[t] = 0;
-    __syncthreads();
-    bitonic_sort_desc<true>(bufs, kScanWaves * cap, tid, kScanThreads);
-    uint64_t* out = ws + ((size_t)q * nblk + blockIdx.x) * K;
-    for (int t = tid; t < K; t += kScanThreads) out[t] = bufs[t];
-}
-
-// Grid-level merge: one workgroup per query folds the nblk*K candidate keys into the final K, sorted.
-// Dynamic LDS: uint64 buf[mcap], mcap a power of two >= 2*K.
-__global__ __launch_bounds__(kMergeThreads) void merge_topk_kernel(const uint64_t* __restrict__ ws, int nblk, int K,
-                                                                   int mcap, int* __restrict__ out_ids,
-                                                                   float* __restrict__ out_scores) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint64_t* buf = reinterpret_cast<uint64_t*>(smem);
-    const int tid = threadIdx.x, q = blockIdx.x;
-    const uint64_t* in = ws + (size_t)q * nblk * K;
-    const long long total = (long long)nblk * K;
-    int keep = 0;
-    long long done = 0;
-    while (done < total) {
-        long long take = total - done;
-        if (take > mcap - keep) take = mcap - keep;
-        for (int t = tid; t < mcap - keep; t += kMergeThreads) buf[keep + t] = (t < take) ? in[done + t] : 0ull;
+    if (total <= a.candmax) {
+        for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
+        for (int i = tid; i < K; i += kThreads) L.sorted[i] = 0;
         __syncthreads();
-        bitonic_sort_desc<true>(buf, mcap, tid, kMergeThreads);
+        for (int t = tid; t < total; t += kThreads) {
+            uint64_t mine = L.cand[t];
+            int rank = 0;
+            for (int u = 0; u < total; ++u) rank += (L.cand[u] > mine) ? 1 : 0;
+            if (rank < K) L.sorted[rank] = mine;
+        }
+        __syncthreads();
+    } else {
+        for (int t = top.cnt + lane; t < a.cap; t += kWave) top.buf[t] = 0;
+        __syncthreads();
+        block_select(L.lists, kWaves * a.cap, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
+    }
+    uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
+    for (int t = tid; t < K; t += kThreads) mine_out[t] = L.sorted[t];
+
+    // ---- 5. ticket: the last workgroup of this query folds every workgroup's list
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long* ticket = a.tickets + (size_t)q * (kTicketBytes / sizeof(unsigned long long));
+        ctl->is_last = (ticket_arrive(ticket, a.gen) == (uint32_t)nblk) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!ctl->is_last) return;
+    __threadfence();
+
+    const uint64_t* all = a.ws_keys + (size_t)q * nblk * K;
+    const long long nkeys = (long long)nblk * K;
+    uint64_t* stage = L.lists;                               // stage_keys slots, a power of two
+    int keep = 0;                                            // best-so-far keys carried at the front of stage
+    long long done = 0;
+    while (done < nkeys) {
+        long long take = nkeys - done;
+        if (take > a.stage_keys - keep) take = a.stage_keys - keep;
+        for (int t = tid; t < a.stage_keys - keep; t += kThreads)
+            stage[keep + t] = (t < take) ? __builtin_nontemporal_load(all + done + t) : 0ull;
+        __syncthreads();
+        block_select(stage, a.stage_keys, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
         done += take;
         keep = K;
+        if (done < nkeys) {
+            for (int t = tid; t < K; t += kThreads) stage[t] = L.sorted[t];
+            __syncthreads();
+        }
     }
-    for (int t = tid; t < K; t += kMergeThreads) {
-        uint64_t key = buf[t];
-        out_ids[(size_t)q * K + t] = id_of_key(key);
-        out_scores[(size_t)q * K + t] = score_of_key(key);
+    for (int t = tid; t < K; t += kThreads) {
+        uint64_t key = L.sorted[t];
+        a.out_ids[(size_t)q * K + t] = id_of_key(key);
+        a.out_scores[(size_t)q * K + t] = score_of_key(key);
     }
 }
 
@@ -277,12 +612,19 @@ int next_pow2(int x) {
     return p;
 }
 
+// 40-bit call generation: starts from a per-process value derived from the clock, then counts calls.
+unsigned long long next_generation() {
+    static std::atomic<unsigned long long> gen{
+        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull >> 24};
+    return (gen.fetch_add(1, std::memory_order_relaxed) + 1) & ((1ull << 40) - 1);
+}
+
 struct ScanPlan {
     int nblk;        // item blocks per query
-    int cap;         // keys per wave buffer
-    int mcap;        // keys in the merge buffer
-    size_t scan_lds;
-    size_t merge_lds;
+    int cap;         // keys per wave list
+    int candmax;     // keys of the candidate array
+    int stage_keys;  // keys staged per fold pass
+    size_t lds;
     bool vec;
 };
 
@@ -291,32 +633,41 @@ bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16; }
 ScanPlan make_plan(long long N, int B, int m, int K) {
     ScanPlan p;
     p.vec = is_vec_m(m);
-    long long units = p.vec ? (N * m + 15) / 16 : N;          // lane-sized pieces of work
-    long long want = (units + kScanThreads * 4 - 1) / (kScanThreads * 4);
-    long long most = (8LL * kAssumedCUs) / B;
-    if (most < 1) most = 1;
-    if (want > most) want = most;
-    if (want < 1) want = 1;
-    p.nblk = (int)want;
+    const long long units = p.vec ? (N * m + 15) / 16 : N;
+    const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
+    long long rounds = (units + per_round - 1) / per_round;
+    long long most = (4LL * kAssumedCUs) / B;                 // about 4 workgroups per CU over the whole grid
+    if (most < 8) most = 8;
+    long long nblk = rounds < most ? rounds : most;
+    if (nblk < 1) nblk = 1;
+    if (B > 1 && nblk >= 8) nblk &= ~7LL;                      // same item block of every query on the same XCD
+    p.nblk = (int)nblk;
     p.cap = next_pow2(K + kWave);
     if (p.cap < 128) p.cap = 128;
-    p.mcap = next_pow2(2 * K);
-    if (p.mcap < 2048) p.mcap = 2048;
-    p.scan_lds = (size_t)m * kLutStride * sizeof(float) + (size_t)kScanWaves * p.cap * sizeof(uint64_t);
-    p.merge_lds = (size_t)p.mcap * sizeof(uint64_t);
+    p.candmax = next_pow2(2 * K);
+    if (p.candmax < 512) p.candmax = 512;
+    p.stage_keys = next_pow2(2 * K);
+    if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
+    p.lds = scan_lds_bytes(m, p.cap, p.candmax, K, p.stage_keys);
     return p;
 }
 
+size_t workspace_bytes(const ScanPlan& p, int B, int K) {
+    size_t bytes = (size_t)B * kTicketBytes + (size_t)B * p.nblk * K * sizeof(uint64_t);
+    return (bytes + 255) & ~(size_t)255;
+}
+
 int check_topk_args(const void* codes, const void* S, long long N, int B, int m, int b, int K, const void* out_ids,
-                    const void* out_scores, const void* workspace, size_t workspace_bytes) {
+                    const void* out_scores, const void* workspace, size_t workspace_bytes_given) {
     if (!codes || !S || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return PQ_ERR_SHAPE;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
-    if (make_plan(N, B, m, K).scan_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
+    const ScanPlan p = make_plan(N, B, m, K);
+    if (p.lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)codes & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)S & 3) || ((uintptr_t)out_ids & 3) ||
         ((uintptr_t)out_scores & 3))
         return PQ_ERR_ALIGN;
-    if (workspace_bytes < pq_score_topk_workspace_bytes(N, B, m, b, K)) return PQ_ERR_WORKSPACE;
+    if (workspace_bytes_given < workspace_bytes(p, B, K)) return PQ_ERR_WORKSPACE;
     return PQ_OK;
 }
 
@@ -327,40 +678,47 @@ hipError_t allow_lds(KernelT kernel, size_t bytes) {
                                (int)bytes);
 }
 
-// Enqueue scan + merge.  With ev_start / ev_stop the scan kernel alone is bracketed by the two events.
+template <int M>
+hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st, hipEvent_t ev_start,
+                       hipEvent_t ev_stop) {
+    hipError_t e = allow_lds(scan_topk_kernel<M>, p.lds);
+    if (e != hipSuccess) return e;
+    dim3 grid(p.nblk, B), block(kThreads);
+    if (ev_start || ev_stop) {
+        hipExtLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.lds, st, ev_start, ev_stop, 0, a);
+    } else {
+        hipLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.lds, st, a);
+    }
+    return hipGetLastError();
+}
+
+// Enqueue the scan.  With events, they take the kernel's own start and end timestamps.
 int enqueue_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
                        float* out_scores, void* workspace, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     const ScanPlan p = make_plan(N, B, m, K);
-    uint64_t* ws = static_cast<uint64_t*>(workspace);
-    dim3 grid(p.nblk, B), block(kScanThreads);
-    hipError_t e = hipSuccess;
-    if (ev_start) { e = hipEventRecord(ev_start, st); if (e != hipSuccess) return record_hip(e); }
-#define PQ_LAUNCH_VEC(MM)                                                                                          \
-    case MM:                                                                                                       \
-        e = allow_lds(scan_topk_vec_kernel<MM>, p.scan_lds);                                                       \
-        if (e == hipSuccess)                                                                                       \
-            hipLaunchKernelGGL(scan_topk_vec_kernel<MM>, grid, block, p.scan_lds, st, codes, S, N, b, K, p.cap, ws); \
-        break;
-    if (p.vec) {
-        switch (m) {
-            PQ_LAUNCH_VEC(1) PQ_LAUNCH_VEC(2) PQ_LAUNCH_VEC(4) PQ_LAUNCH_VEC(8) PQ_LAUNCH_VEC(16)
-            default: break;
-        }
-    } else {
-        e = allow_lds(scan_topk_item_kernel, p.scan_lds);
-        if (e == hipSuccess)
-            hipLaunchKernelGGL(scan_topk_item_kernel, grid, block, p.scan_lds, st, codes, S, N, m, b, K, p.cap, ws);
+    ScanArgs a;
+    a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
+    a.cap = p.cap; a.candmax = p.candmax; a.stage_keys = p.stage_keys;
+    a.tickets = static_cast<unsigned long long*>(workspace);
+    a.ws_keys = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + (size_t)B * kTicketBytes);
+    a.gen = next_generation();
+    a.out_ids = out_ids; a.out_scores = out_scores;
+    hipError_t e;
+    switch (p.vec ? m : 0) {
+        case 1: e = launch_scan<1>(p, a, B, st, ev_start, ev_stop); break;
+        case 2: e = launch_scan<2>(p, a, B, st, ev_start, ev_stop); break;
+        case 4: e = launch_scan<4>(p, a, B, st, ev_start, ev_stop); break;
+        case 8: e = launch_scan<8>(p, a, B, st, ev_start, ev_stop); break;
+        case 16: e = launch_scan<16>(p, a, B, st, ev_start, ev_stop); break;
+        default: e = launch_scan<0>(p, a, B, st, ev_start, ev_stop); break;
     }
-#undef PQ_LAUNCH_VEC
-    if (e != hipSuccess) return record_hip(e);
-    e = hipGetLastError();
-    if (e != hipSuccess) return record_hip(e);
-    if (ev_stop) { e = hipEventRecord(ev_stop, st); if (e != hipSuccess) return record_hip(e); }
-    e = allow_lds(merge_topk_kernel, p.merge_lds);
-    if (e != hipSuccess) return record_hip(e);
-    hipLaunchKernelGGL(merge_topk_kernel, dim3(B), dim3(kMergeThreads), p.merge_lds, st, ws, p.nblk, K, p.mcap,
-                       out_ids, out_scores);
-    return record_hip(hipGetLastError());
+    return record_hip(e);
+}
+
+template <int S_ELEMS>
+void launch_subitem(const float* queries, const float* centroids, float* S, int B, int d, int m, int b, hipStream_t st) {
+    dim3 grid((m * b + kSubThreads - 1) / kSubThreads, (B + kSubQueryTile - 1) / kSubQueryTile);
+    hipLaunchKernelGGL(subitem_scores_kernel<S_ELEMS>, grid, dim3(kSubThreads), 0, st, queries, centroids, S, B, d, m, b);
 }
 
 }  // namespace
@@ -373,9 +731,13 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
     if (B < 1 || d < 1 || m < 1 || b < 1 || b > 256 || d % m != 0) return PQ_ERR_SHAPE;
     if (B > PQ_MAX_B || m > PQ_MAX_M) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)S & 3)) return PQ_ERR_ALIGN;
-    dim3 grid((m * b + 255) / 256, B);
-    hipLaunchKernelGGL(subitem_scores_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), queries,
-                       centroids, S, d, m, b);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (d / m) {
+        case 16: launch_subitem<16>(queries, centroids, S, B, d, m, b, st); break;
+        case 32: launch_subitem<32>(queries, centroids, S, B, d, m, b, st); break;
+        case 64: launch_subitem<64>(queries, centroids, S, B, d, m, b, st); break;
+        default: launch_subitem<0>(queries, centroids, S, B, d, m, b, st); break;
+    }
     return record_hip(hipGetLastError());
 }
 
@@ -383,24 +745,23 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K) {
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return 0;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return 0;
     const ScanPlan p = make_plan(N, B, m, K);
-    if (p.scan_lds > kMaxLdsBytes) return 0;
-    size_t bytes = (size_t)B * p.nblk * K * sizeof(uint64_t);
-    return (bytes + 255) & ~(size_t)255;
+    if (p.lds > kMaxLdsBytes) return 0;
+    return workspace_bytes(p, B, K);
 }
 
 int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
-                  float* out_scores, void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes);
+                  float* out_scores, void* workspace, size_t workspace_bytes_given, void* stream) {
+    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
     return enqueue_score_topk(codes, S, N, B, m, b, K, out_ids, out_scores, workspace,
                               static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
 int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                          int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes, void* stream,
-                          int iters, float* scan_ms) {
+                          int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes_given,
+                          void* stream, int iters, float* scan_ms) {
     if (!scan_ms) return PQ_ERR_NULL;
-    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes);
+    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
     if (iters < 1) return PQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -430,7 +791,8 @@ const char* pq_strerror(int code) {
         case PQ_OK: return "ok";
         case PQ_ERR_NULL: return "a required pointer is NULL";
         case PQ_ERR_SHAPE: return "bad shape: need B,d,m,b,K,N >= 1, d % m == 0, b <= 256, K <= N, N < 2^31";
-        case PQ_ERR_UNSUPPORTED: return "unsupported: K > 1024, m > 128, B > 65535, or score tables plus candidate lists exceed LDS";
+        case PQ_ERR_UNSUPPORTED:
+            return "unsupported: K > 512, m > 128, B > 65535, or score tables plus candidate lists exceed LDS";
         case PQ_ERR_WORKSPACE: return "workspace smaller than pq_score_topk_workspace_bytes()";
         case PQ_ERR_ALIGN: return "pointer alignment: codes and workspace 16 bytes, float/int arrays 4 bytes";
         case PQ_ERR_HIP: return g_hip_error;

@@ -64,7 +64,7 @@ def test_workspace_bytes(lib):
     assert ws(50_000_000, 32, 8, 256, 10) > 0
     assert ws(10, 1, 8, 256, 10) >= 80
     for bad in ((0, 1, 8, 256, 10), (10, 0, 8, 256, 1), (10, 1, 0, 256, 1), (10, 1, 8, 0, 1), (10, 1, 8, 257, 1),
-                (10, 1, 8, 256, 0), (10, 1, 8, 256, 11), (2 ** 31, 1, 8, 256, 10), (10 ** 6, 1, 8, 256, 1025),
+                (10, 1, 8, 256, 0), (10, 1, 8, 256, 11), (2 ** 31, 1, 8, 256, 10), (10 ** 6, 1, 8, 256, 513),
                 (10 ** 6, 1, 129, 256, 10), (10 ** 6, 65536, 8, 256, 10)):
         assert ws(*bad) == 0, bad
 
@@ -100,8 +100,8 @@ def test_score_topk_argument_errors(lib):
         assert call(**{name: None}) == NULL, name
     assert call(N=0) == SHAPE and call(B=0) == SHAPE and call(m=0) == SHAPE and call(b=0) == SHAPE
     assert call(K=0) == SHAPE and call(b=257) == SHAPE and call(K=1001) == SHAPE and call(N=2 ** 31) == SHAPE
-    assert call(N=10 ** 6, K=1025) == UNSUPPORTED and call(m=129) == UNSUPPORTED and call(B=65536) == UNSUPPORTED
-    assert call(N=10 ** 6, m=128, K=1024) == UNSUPPORTED                # tables + candidate lists exceed LDS
+    assert call(N=10 ** 6, K=513) == UNSUPPORTED and call(m=129) == UNSUPPORTED and call(B=65536) == UNSUPPORTED
+    assert call(N=10 ** 6, m=128, K=512) == UNSUPPORTED                # tables + candidate lists exceed LDS
     assert call(codes=p + 8) == ALIGN and call(ws=p + 4) == ALIGN and call(S=p + 1) == ALIGN
     assert call(ids=p + 2) == ALIGN and call(sc=p + 3) == ALIGN
     need = lib.pq_score_topk_workspace_bytes(1000, 1, 8, 256, 10)

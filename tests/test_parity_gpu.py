@@ -68,7 +68,7 @@ def test_score_topk_small_shapes(pq, oracle, m):
 
 
 def test_score_topk_large_k(pq, oracle):
-    for N, m, K in ((5000, 8, 1024), (3000, 4, 500), (1024, 16, 1024), (200_000, 8, 257)):
+    for N, m, K in ((5000, 8, 512), (3000, 4, 500), (512, 16, 512), (200_000, 8, 257), (100_000, 64, 512), (50_000, 128, 64)):
         G = W.codes_uniform(N, m, 256, seed=K)
         S = W.normal_f32(W.stream_key(K, W.STREAM_QUERIES), 2 * m * 256).reshape(2, m, 256)
         assert_same_topk(pq, oracle, G, S, K, "largeK")
