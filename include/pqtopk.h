@@ -70,11 +70,9 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K);
  *   S           in   float [B][m][b]  from pq_subitem_scores() (or any finite table)
  *   out_ids     out  int32 [B][K]     rank r of query q at [q][r]; score descending, id ascending
  *   out_scores  out  float [B][K]     the scores of those items
- *   workspace        scratch of at least pq_score_topk_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned.
- *                    It needs no initialisation: its first words are per-query arrival tickets stamped with a
- *                    40-bit per-call generation number, and a ticket that carries another generation (left by an
- *                    earlier call, or arbitrary bytes) is restarted by the first workgroup that meets it.  Calls
- *                    that share a workspace must not overlap in time
+ *   workspace        scratch of at least pq_score_topk_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned;
+ *                    contents on entry are irrelevant (it receives every workgroup's K best keys, which a second
+ *                    small launch folds into the result); calls sharing a workspace must not overlap in time
  * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (K > PQ_MAX_K, m > PQ_MAX_M, B > PQ_MAX_B, or m and K together
  *         too large for the 160 KB of LDS: m KB of score tables plus about 80*nextpow2(K+64) bytes of candidate
  *         lists; every K <= 512 fits with m <= 64, and m = 128 fits with K <= 64),

@@ -7,23 +7,20 @@
 // Total order used everywhere: a 64-bit key  (orderable(score) << 32) | ~id.  A larger key is a better item:
 // higher score first, lower id between equal scores.  Keys of distinct items are distinct, key 0 means "empty".
 //
-// Shape of pq_score_topk(): ONE launch.  grid = (item blocks, B).  A workgroup
-//   1. copies its query's m x b table into LDS and derives the score range [lo, hi] from the per-split extremes;
-//   2. scores a first round of items into registers and histograms them over 1024 equal-width score buckets; the
-//      bucket that holds the K-th best gives a score cut: everything below it is out for good;
+// Shape of pq_score_topk(): a scan launch with grid = (item blocks, B), then a small fold launch.  A scan workgroup
+//   1. requests its first codes, then copies its query's m x b table into LDS;
+//   2. scores a first round of items into registers and histograms them over 1024 equal-width buckets spanning
+//      their range; the bucket that holds the K-th best gives a score cut: everything below it is out for good;
 //   3. streams the rest of its share of G against that cut; survivors (a handful) go to small per-wave lists in
 //      LDS that are pruned exactly (by key) when they fill;
-//   4. selects its exact K best and writes them to the workspace; the workgroup that arrives last at the query's
-//      ticket folds all workgroups' lists into the final sorted K.
+//   4. selects its exact K best and writes them, sorted, to the workspace.
+// The fold launch (one workgroup per query) reduces the workgroups' lists to the final sorted K the same way.
 // The histogram only ever prunes; every decision that picks a winner compares full keys, so the result is exact
 // for any input, including heavy ties (which merely take slower paths).
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
-
-#include <atomic>
-#include <chrono>
 
 #include "pqtopk.h"
 
@@ -40,7 +37,7 @@ constexpr int kGenericItemsPerThread = 4;         // items a thread holds per ro
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
 constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace
-constexpr int kTicketBytes = 256;                 // one ticket per query, padded
+constexpr int kBlocksPerCU = 2;                   // scan workgroups per CU over the whole grid
 
 __device__ __forceinline__ uint32_t orderable_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -132,15 +129,14 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float
 // ---------------------------------------------------------------------------------------------------------------
 // Small per-workgroup control block in LDS.
 struct Ctl {
-    float lo;            // lower end of the score range
+    float lo;            // lower end of the score range the histogram covers
     float scale;         // buckets per unit of score (0: range degenerate, histogram off)
     float cut;           // scores <= cut cannot reach this workgroup's top K (valid after a histogram pass)
     int bstar;           // bucket of the K-th best in the histogrammed set
     int ncand;           // candidates collected for an exact selection
-    int is_last;         // this workgroup took the query's last ticket
     int wave_cnt[kWaves];
-    float smin[PQ_MAX_M];
-    float smax[PQ_MAX_M];
+    float wave_min[kWaves];
+    float wave_max[kWaves];
 };
 
 __device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
@@ -148,6 +144,33 @@ __device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
     float x = (score - lo) * scale;
     int bkt = (x > 0.0f) ? (int)x : 0;
     return bkt > kBins - 1 ? kBins - 1 : bkt;
+}
+
+// Range of the scores held by the workgroup -> bucket mapping.  Every thread passes the min / max of its own valid
+// scores (+inf / -inf if it has none); returns after a barrier with ctl->lo / ctl->scale set.
+__device__ void set_range(float mn, float mx, Ctl* ctl, int tid) {
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, off, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    }
+    if (lane == 0) { ctl->wave_min[wave] = mn; ctl->wave_max[wave] = mx; }
+    __syncthreads();
+    if (tid == 0) {
+        float lo = ctl->wave_min[0], hi = ctl->wave_max[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) { lo = fminf(lo, ctl->wave_min[w]); hi = fmaxf(hi, ctl->wave_max[w]); }
+        float range = hi - lo;
+        float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
+        if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
+        ctl->lo = lo;
+        ctl->scale = scale;
+        ctl->cut = -__builtin_inff();
+        ctl->bstar = 0;
+        ctl->ncand = 0;
+    }
+    __syncthreads();
 }
 
 // Wave 0: find the highest bucket b* such that buckets >= b* hold at least K entries (0 if there are fewer than K in
@@ -165,7 +188,6 @@ __device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
         if (lane + off < kWave) suffix += other;
     }
     uint64_t has = __ballot(suffix >= (uint32_t)K);
-    int bstar = 0;
     if (has != 0) {
         int owner = 63 - __builtin_clzll(has);               // highest lane whose suffix reaches K
         if (lane == owner) {
@@ -182,7 +204,7 @@ __device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
         ctl->bstar = 0;
     }
     wave_sync();
-    bstar = ctl->bstar;
+    const int bstar = ctl->bstar;
     if (lane == 0) {
         // a score cut with bucket_of(cut) < b*: by monotonicity every entry of a bucket >= b* is > cut
         float cut = -__builtin_inff();
@@ -231,10 +253,24 @@ struct WaveTopK {
     }
 };
 
+// Sorted exact K best of the C candidates in cand[] (C <= what one pass of the workgroup can rank), by counting:
+// the position of a key is the number of candidates that beat it.  dst[0..K) zero-filled where fewer exist.
+__device__ void rank_select(const uint64_t* cand, int C, int K, uint64_t* dst, int tid) {
+    for (int i = tid; i < K; i += kThreads) dst[i] = 0;
+    __syncthreads();
+    for (int t = tid; t < C; t += kThreads) {
+        uint64_t mine = cand[t];
+        int rank = 0;
+        for (int u = 0; u < C; ++u) rank += (cand[u] > mine) ? 1 : 0;
+        if (rank < K) dst[rank] = mine;
+    }
+    __syncthreads();
+}
+
 // Exact selection of the K best among the nonzero keys of src[0..n) (LDS, zeros allowed anywhere), written sorted
-// to dst[0..K) (zero-filled if fewer than K exist).  All kThreads threads call it.  `cand` holds candmax keys,
-// `hist` kBins counters.  If the histogram cannot narrow the set to candmax keys (ties, degenerate range), src is
-// sorted in place instead, which needs n to be a power of two.  dst may alias cand only if it does not alias src.
+// to dst[0..K) (zero-filled if fewer than K exist).  All kThreads threads call it, ctl->lo / scale / ncand = 0 set.
+// `cand` holds candmax keys, `hist` kBins counters.  If the histogram cannot narrow the set to candmax keys (ties,
+// degenerate range), src is sorted in place instead, which needs n to be a power of two.
 __device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_t* cand, int candmax, uint32_t* hist,
                              Ctl* ctl, int tid) {
     const int lane = tid & (kWave - 1);
@@ -260,16 +296,7 @@ __device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_
     __syncthreads();
     const int C = ctl->ncand;
     if (C <= candmax) {
-        // rank by counting: position of a key = number of candidates that beat it
-        for (int i = tid; i < K; i += kThreads) dst[i] = 0;
-        __syncthreads();
-        for (int t = tid; t < C; t += kThreads) {
-            uint64_t mine = cand[t];
-            int rank = 0;
-            for (int u = 0; u < C; ++u) rank += (cand[u] > mine) ? 1 : 0;
-            if (rank < K) dst[rank] = mine;
-        }
-        __syncthreads();
+        rank_select(cand, C, K, dst, tid);
     } else {
         bitonic_sort_desc<true>(src, n, tid, kThreads);
         for (int i = tid; i < K; i += kThreads) dst[i] = src[i];
@@ -277,73 +304,66 @@ __device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_
     }
 }
 
-// One arrival at a query's ticket.  The ticket holds (generation << 24 | arrivals); a ticket left by an earlier call
-// carries another generation and is restarted by whoever sees it first.  Returns this arrival's number, 1-based.
-__device__ uint32_t ticket_arrive(unsigned long long* ticket, unsigned long long gen) {
-    unsigned long long old = atomicAdd(ticket, 1ull);
-    if ((old >> 24) == gen) return (uint32_t)(old & 0xFFFFFFull) + 1u;
-    for (;;) {                                    // each failed exchange means another arrival succeeded: bounded
-        unsigned long long cur = atomicAdd(ticket, 0ull);
-        unsigned long long nxt = ((cur >> 24) == gen) ? cur + 1ull : ((gen << 24) | 1ull);
-        if (atomicCAS(ticket, cur, nxt) == cur) return (uint32_t)(nxt & 0xFFFFFFull);
-    }
-}
+__host__ __device__ inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
 // LDS layout of the scan kernel (dynamic): lut | hist | ctl | wave lists | cand | sorted
 struct ScanLds {
     float* lut;
     uint32_t* hist;
     Ctl* ctl;
-    uint64_t* lists;     // kWaves * cap, also the staging area of the grid-level fold
+    uint64_t* lists;     // kWaves * cap
     uint64_t* cand;      // candmax
-    uint64_t* sorted;    // K rounded up
+    uint64_t* sorted;    // K
 };
 
-__host__ __device__ inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
-
-__host__ __device__ inline size_t scan_lds_bytes(int m, int cap, int candmax, int K, int stage_keys) {
-    size_t lists = (size_t)kWaves * cap;
-    if (lists < (size_t)stage_keys) lists = stage_keys;
+__host__ __device__ inline size_t scan_lds_bytes(int m, int cap, int candmax, int K) {
     return align16((size_t)m * kLutStride * sizeof(float)) + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)) +
-           lists * sizeof(uint64_t) + (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
+           (size_t)kWaves * cap * sizeof(uint64_t) + (size_t)candmax * sizeof(uint64_t) +
+           align16((size_t)K * sizeof(uint64_t));
 }
 
-__device__ inline ScanLds carve(unsigned char* smem, int m, int cap, int candmax, int stage_keys) {
+__device__ inline ScanLds carve_scan(unsigned char* smem, int m, int cap, int candmax) {
     ScanLds L;
     size_t off = 0;
     L.lut = reinterpret_cast<float*>(smem + off);        off += align16((size_t)m * kLutStride * sizeof(float));
     L.hist = reinterpret_cast<uint32_t*>(smem + off);    off += kBins * sizeof(uint32_t);
     L.ctl = reinterpret_cast<Ctl*>(smem + off);          off += align16(sizeof(Ctl));
-    size_t lists = (size_t)kWaves * cap;
-    if (lists < (size_t)stage_keys) lists = stage_keys;
-    L.lists = reinterpret_cast<uint64_t*>(smem + off);   off += lists * sizeof(uint64_t);
+    L.lists = reinterpret_cast<uint64_t*>(smem + off);   off += (size_t)kWaves * cap * sizeof(uint64_t);
     L.cand = reinterpret_cast<uint64_t*>(smem + off);    off += (size_t)candmax * sizeof(uint64_t);
     L.sorted = reinterpret_cast<uint64_t*>(smem + off);
     return L;
 }
 
+// Optional phase timestamps for kernel tuning: built only with -DPQ_PHASE_TIMES, never in the shipped library.
+#ifdef PQ_PHASE_TIMES
+#define PQ_MARK(slot)                                                                                              \
+    do {                                                                                                           \
+        if (a.phase_times && threadIdx.x == 0)                                                                     \
+            a.phase_times[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64();           \
+    } while (0)
+#else
+#define PQ_MARK(slot) do {} while (0)
+#endif
+
 struct ScanArgs {
+    unsigned long long* phase_times;   // debug builds only
     const uint8_t* codes;
     const float* S;
     long long N;
     int m, b, K;
     int cap;             // keys per wave list (power of two >= K + 64)
     int candmax;         // keys of the exact-selection candidate array
-    int stage_keys;      // power of two: keys the fold stages per pass
-    unsigned long long* tickets;   // [B], kTicketBytes apart
     uint64_t* ws_keys;   // [B][nblk][K]
-    unsigned long long gen;
-    int* out_ids;
-    float* out_scores;
 };
 
-// Items a thread holds per round and how it loads / scores them.  M > 0: m is M and one 16-byte vector carries
-// 16/M items; M == 0: any m, one item per slot, row loads sized by m's alignment.
+// Items a thread holds per round.  M > 0: m is M and one 16-byte vector carries 16/M items; M == 0: any m, one item
+// per slot, row loads sized by m's alignment.
 template <int M>
 struct Round {
     static constexpr int kVecs = M ? vec_per_thread(M) : 0;
     static constexpr int kItems = M ? kVecs * (16 / M) : kGenericItemsPerThread;
     static constexpr int kUnitsPerThread = M ? kVecs : kGenericItemsPerThread;           // lane-sized units of work
+    static constexpr int kWords = M ? kVecs * 4 : 1;
 };
 
 template <int M>
@@ -389,39 +409,47 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
     return acc + 0.0f;
 }
 
-// Scores of the items this thread owns in round `r` of its workgroup.  item ids in id[], validity by id < N.
+// The code vectors this thread owns in the round that starts at unit `unit_base` (vector kernels only).
 template <int M>
-__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long unit_base, int tid,
-                                            float (&sc)[Round<M>::kItems], uint32_t (&id)[Round<M>::kItems]) {
+__device__ __forceinline__ void load_round(const ScanArgs& a, long long unit_base, int tid,
+                                           uint32_t (&w)[Round<M>::kWords]) {
     if constexpr (M > 0) {
-        constexpr int IPV = 16 / M;
         constexpr int kVecPerThread = Round<M>::kVecs;
         const long long total_bytes = a.N * M;
         const long long full_vecs = total_bytes / 16;
         const long long total_vecs = (total_bytes + 15) / 16;
         const uint4* cvec = reinterpret_cast<const uint4*>(a.codes);
-        uint32_t w[kVecPerThread][4];
 #pragma unroll
         for (int u = 0; u < kVecPerThread; ++u) {
             const long long v = unit_base + (long long)u * kThreads + tid;
-            w[u][0] = w[u][1] = w[u][2] = w[u][3] = 0u;
+            w[4 * u] = w[4 * u + 1] = w[4 * u + 2] = w[4 * u + 3] = 0u;
             if (v < full_vecs) {
                 uint4 x = cvec[v];
-                w[u][0] = x.x; w[u][1] = x.y; w[u][2] = x.z; w[u][3] = x.w;
+                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
             } else if (v < total_vecs) {              // ragged last vector: byte loads
                 for (long long p = v * 16; p < total_bytes; ++p) {
                     int o = (int)(p - v * 16);
-                    w[u][o >> 2] |= (uint32_t)a.codes[p] << ((o & 3) * 8);
+                    w[4 * u + (o >> 2)] |= (uint32_t)a.codes[p] << ((o & 3) * 8);
                 }
             }
         }
+    }
+}
+
+// Scores and ids of the items this thread owns in that round; an id >= N marks a slot past the catalogue's end.
+template <int M>
+__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long unit_base, int tid,
+                                            const uint32_t (&w)[Round<M>::kWords], float (&sc)[Round<M>::kItems],
+                                            uint32_t (&id)[Round<M>::kItems]) {
+    if constexpr (M > 0) {
+        constexpr int IPV = 16 / M;
 #pragma unroll
-        for (int u = 0; u < kVecPerThread; ++u) {
+        for (int u = 0; u < Round<M>::kVecs; ++u) {
             const long long v = unit_base + (long long)u * kThreads + tid;
 #pragma unroll
             for (int e = 0; e < IPV; ++e) {
                 id[u * IPV + e] = (uint32_t)(v * IPV + e);
-                sc[u * IPV + e] = score_packed<M>(lut, w[u], e * M);
+                sc[u * IPV + e] = score_packed<M>(lut, &w[4 * u], e * M);
             }
         }
     } else {
@@ -434,18 +462,27 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
     }
 }
 
+// Catalogue scan: grid = (item blocks, B).  Leaves each workgroup's exact, sorted K best keys in the workspace.
 template <int M>
 __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = M ? M : a.m;
-    const ScanLds L = carve(smem, m, a.cap, a.candmax, a.stage_keys);
+    const ScanLds L = carve_scan(smem, m, a.cap, a.candmax);
     Ctl* ctl = L.ctl;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q = blockIdx.y, nblk = gridDim.x, K = a.K, b = a.b;
     constexpr int kItems = Round<M>::kItems;
     constexpr int kUnits = Round<M>::kUnitsPerThread;
 
-    // ---- 1. table into LDS, score range from the per-split extremes
+    const long long total_units = M ? (a.N * M + 15) / 16 : a.N;
+    const long long round_units = (long long)kThreads * kUnits;
+    const long long rounds = (total_units + round_units - 1) / round_units;   // nblk <= rounds: every workgroup has one
+
+    PQ_MARK(0);
+    // ---- 1. first round's codes on their way, then the query's table into LDS
+    long long r = blockIdx.x;
+    uint32_t w[Round<M>::kWords];
+    load_round<M>(a, r * round_units, tid, w);
     const float* Sq = a.S + (size_t)q * m * b;
     for (int e = tid; e < m * kLutStride; e += kThreads) {
         int k = e / kLutStride, j = e % kLutStride;
@@ -453,46 +490,21 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     }
     for (int i = tid; i < kBins; i += kThreads) L.hist[i] = 0;
     __syncthreads();
-    for (int k = wave; k < m; k += kWaves) {              // one wave reduces one split
-        float mn = __builtin_inff(), mx = -__builtin_inff();
-        for (int j = lane; j < b; j += kWave) {
-            float v = L.lut[k * kLutStride + j];
-            mn = fminf(mn, v); mx = fmaxf(mx, v);
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            mn = fminf(mn, __shfl_xor(mn, off, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-        }
-        if (lane == 0) { ctl->smin[k] = mn; ctl->smax[k] = mx; }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        float lo = 0.0f, hi = 0.0f;
-        for (int k = 0; k < m; ++k) { lo += ctl->smin[k]; hi += ctl->smax[k]; }
-        float range = hi - lo;
-        float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
-        if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
-        ctl->lo = lo;
-        ctl->scale = scale;
-        ctl->cut = -__builtin_inff();
-        ctl->bstar = 0;
-    }
-    __syncthreads();
-    const float lo = ctl->lo, scale = ctl->scale;
+    PQ_MARK(1);
 
-    // ---- 2. first round: scores in registers, histogram, cut
-    const long long total_units = M ? (a.N * M + 15) / 16 : a.N;
-    const long long round_units = (long long)kThreads * kUnits;
-    const long long rounds = (total_units + round_units - 1) / round_units;
-
+    // ---- 2. first round: scores in registers, histogram over their range, cut
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, 0, 0ull};
-
-    long long r = blockIdx.x;
-    if (r < rounds) {
+    {
         float sc[kItems];
         uint32_t id[kItems];
-        score_round<M>(a, L.lut, r * round_units, tid, sc, id);
+        score_round<M>(a, L.lut, r * round_units, tid, w, sc, id);
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+        for (int e = 0; e < kItems; ++e)
+            if (id[e] < a.N) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
+        set_range(mn, mx, ctl, tid);
+        PQ_MARK(2);
+        const float lo = ctl->lo, scale = ctl->scale;
         int bk[kItems];
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
@@ -502,6 +514,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
         __syncthreads();
         if (tid < kWave) find_cut(L.hist, K, ctl, lane);
         __syncthreads();
+        PQ_MARK(3);
         const int bstar = ctl->bstar;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
@@ -510,13 +523,15 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
         }
         r += nblk;
     }
+    PQ_MARK(4);
 
     // ---- 3. stream the remaining rounds against the cut
     const float cut = ctl->cut;
     for (; r < rounds; r += nblk) {
         float sc[kItems];
         uint32_t id[kItems];
-        score_round<M>(a, L.lut, r * round_units, tid, sc, id);
+        load_round<M>(a, r * round_units, tid, w);
+        score_round<M>(a, L.lut, r * round_units, tid, w, sc, id);
         bool any = false;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) any = any || (sc[e] > cut && id[e] < a.N);
@@ -527,28 +542,21 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
             top.offer(key, lane);
         }
     }
+    PQ_MARK(5);
 
     // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
     if (lane == 0) ctl->wave_cnt[wave] = top.cnt;
     __syncthreads();
     int total = 0, before = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        int c = ctl->wave_cnt[w];
-        if (w < wave) before += c;
+    for (int wv = 0; wv < kWaves; ++wv) {
+        int c = ctl->wave_cnt[wv];
+        if (wv < wave) before += c;
         total += c;
     }
     if (total <= a.candmax) {
         for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
-        for (int i = tid; i < K; i += kThreads) L.sorted[i] = 0;
-        __syncthreads();
-        for (int t = tid; t < total; t += kThreads) {
-            uint64_t mine = L.cand[t];
-            int rank = 0;
-            for (int u = 0; u < total; ++u) rank += (L.cand[u] > mine) ? 1 : 0;
-            if (rank < K) L.sorted[rank] = mine;
-        }
-        __syncthreads();
+        rank_select(L.cand, total, K, L.sorted, tid);       // its first barrier orders the copies above
     } else {
         for (int t = top.cnt + lane; t < a.cap; t += kWave) top.buf[t] = 0;
         __syncthreads();
@@ -556,39 +564,60 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     }
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
     for (int t = tid; t < K; t += kThreads) mine_out[t] = L.sorted[t];
+    PQ_MARK(6);
+}
 
-    // ---- 5. ticket: the last workgroup of this query folds every workgroup's list
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        unsigned long long* ticket = a.tickets + (size_t)q * (kTicketBytes / sizeof(unsigned long long));
-        ctl->is_last = (ticket_arrive(ticket, a.gen) == (uint32_t)nblk) ? 1 : 0;
+// Grid-level fold: one workgroup per query turns the nblk sorted lists of K keys into the final K, sorted.
+// Dynamic LDS: hist | ctl | stage (stage_keys, a power of two >= 2K) | cand | sorted
+struct FoldArgs {
+    const uint64_t* ws_keys;   // [B][nblk][K]
+    int nblk, K;
+    int stage_keys, candmax;
+    int* out_ids;
+    float* out_scores;
+};
+
+__host__ __device__ inline size_t fold_lds_bytes(int stage_keys, int candmax, int K) {
+    return kBins * sizeof(uint32_t) + align16(sizeof(Ctl)) + (size_t)stage_keys * sizeof(uint64_t) +
+           (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
+}
+
+__global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+    Ctl* ctl = reinterpret_cast<Ctl*>(smem + kBins * sizeof(uint32_t));
+    uint64_t* stage = reinterpret_cast<uint64_t*>(smem + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)));
+    uint64_t* cand = stage + a.stage_keys;
+    uint64_t* sorted = cand + a.candmax;
+    const int tid = threadIdx.x, q = blockIdx.x, K = a.K;
+    const uint64_t* all = a.ws_keys + (size_t)q * a.nblk * K;
+    const long long nkeys = (long long)a.nblk * K;
+
+    // score range of all the keys (empty slots of short lists are 0)
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (long long i = tid; i < nkeys; i += kThreads) {
+        uint64_t key = all[i];
+        if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
     }
-    __syncthreads();
-    if (!ctl->is_last) return;
-    __threadfence();
+    set_range(mn, mx, ctl, tid);
 
-    const uint64_t* all = a.ws_keys + (size_t)q * nblk * K;
-    const long long nkeys = (long long)nblk * K;
-    uint64_t* stage = L.lists;                               // stage_keys slots, a power of two
     int keep = 0;                                            // best-so-far keys carried at the front of stage
     long long done = 0;
     while (done < nkeys) {
         long long take = nkeys - done;
         if (take > a.stage_keys - keep) take = a.stage_keys - keep;
-        for (int t = tid; t < a.stage_keys - keep; t += kThreads)
-            stage[keep + t] = (t < take) ? __builtin_nontemporal_load(all + done + t) : 0ull;
+        for (int t = tid; t < a.stage_keys - keep; t += kThreads) stage[keep + t] = (t < take) ? all[done + t] : 0ull;
         __syncthreads();
-        block_select(stage, a.stage_keys, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
+        block_select(stage, a.stage_keys, K, sorted, cand, a.candmax, hist, ctl, tid);
         done += take;
         keep = K;
         if (done < nkeys) {
-            for (int t = tid; t < K; t += kThreads) stage[t] = L.sorted[t];
+            for (int t = tid; t < K; t += kThreads) stage[t] = sorted[t];
             __syncthreads();
         }
     }
     for (int t = tid; t < K; t += kThreads) {
-        uint64_t key = L.sorted[t];
+        uint64_t key = sorted[t];
         a.out_ids[(size_t)q * K + t] = id_of_key(key);
         a.out_scores[(size_t)q * K + t] = score_of_key(key);
     }
@@ -596,6 +625,8 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
 
 // ---------------------------------------------------------------------------------------------------------------
 // host side
+
+unsigned long long* g_phase_times = nullptr;       // set only by the debug hook of -DPQ_PHASE_TIMES builds
 
 thread_local char g_hip_error[256] = "no HIP error recorded";
 
@@ -612,19 +643,12 @@ int next_pow2(int x) {
     return p;
 }
 
-// 40-bit call generation: starts from a per-process value derived from the clock, then counts calls.
-unsigned long long next_generation() {
-    static std::atomic<unsigned long long> gen{
-        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull >> 24};
-    return (gen.fetch_add(1, std::memory_order_relaxed) + 1) & ((1ull << 40) - 1);
-}
-
 struct ScanPlan {
     int nblk;        // item blocks per query
     int cap;         // keys per wave list
     int candmax;     // keys of the candidate array
-    int stage_keys;  // keys staged per fold pass
-    size_t lds;
+    int stage_keys;  // keys the fold stages per pass
+    size_t scan_lds, fold_lds;
     bool vec;
 };
 
@@ -636,7 +660,7 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     const long long units = p.vec ? (N * m + 15) / 16 : N;
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
-    long long most = (4LL * kAssumedCUs) / B;                 // about 4 workgroups per CU over the whole grid
+    long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
     if (most < 8) most = 8;
     long long nblk = rounds < most ? rounds : most;
     if (nblk < 1) nblk = 1;
@@ -648,12 +672,13 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     if (p.candmax < 512) p.candmax = 512;
     p.stage_keys = next_pow2(2 * K);
     if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
-    p.lds = scan_lds_bytes(m, p.cap, p.candmax, K, p.stage_keys);
+    p.scan_lds = scan_lds_bytes(m, p.cap, p.candmax, K);
+    p.fold_lds = fold_lds_bytes(p.stage_keys, p.candmax, K);
     return p;
 }
 
 size_t workspace_bytes(const ScanPlan& p, int B, int K) {
-    size_t bytes = (size_t)B * kTicketBytes + (size_t)B * p.nblk * K * sizeof(uint64_t);
+    size_t bytes = (size_t)B * p.nblk * K * sizeof(uint64_t);
     return (bytes + 255) & ~(size_t)255;
 }
 
@@ -663,7 +688,7 @@ int check_topk_args(const void* codes, const void* S, long long N, int B, int m,
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return PQ_ERR_SHAPE;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
     const ScanPlan p = make_plan(N, B, m, K);
-    if (p.lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)codes & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)S & 3) || ((uintptr_t)out_ids & 3) ||
         ((uintptr_t)out_scores & 3))
         return PQ_ERR_ALIGN;
@@ -681,28 +706,26 @@ hipError_t allow_lds(KernelT kernel, size_t bytes) {
 template <int M>
 hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st, hipEvent_t ev_start,
                        hipEvent_t ev_stop) {
-    hipError_t e = allow_lds(scan_topk_kernel<M>, p.lds);
+    hipError_t e = allow_lds(scan_topk_kernel<M>, p.scan_lds);
     if (e != hipSuccess) return e;
     dim3 grid(p.nblk, B), block(kThreads);
     if (ev_start || ev_stop) {
-        hipExtLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.lds, st, ev_start, ev_stop, 0, a);
+        hipExtLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.scan_lds, st, ev_start, ev_stop, 0, a);
     } else {
-        hipLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.lds, st, a);
+        hipLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.scan_lds, st, a);
     }
     return hipGetLastError();
 }
 
-// Enqueue the scan.  With events, they take the kernel's own start and end timestamps.
+// Enqueue scan + fold.  With events, they take the scan kernel's own start and end timestamps.
 int enqueue_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
                        float* out_scores, void* workspace, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     const ScanPlan p = make_plan(N, B, m, K);
     ScanArgs a;
+    a.phase_times = g_phase_times;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
-    a.cap = p.cap; a.candmax = p.candmax; a.stage_keys = p.stage_keys;
-    a.tickets = static_cast<unsigned long long*>(workspace);
-    a.ws_keys = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + (size_t)B * kTicketBytes);
-    a.gen = next_generation();
-    a.out_ids = out_ids; a.out_scores = out_scores;
+    a.cap = p.cap; a.candmax = p.candmax;
+    a.ws_keys = static_cast<uint64_t*>(workspace);
     hipError_t e;
     switch (p.vec ? m : 0) {
         case 1: e = launch_scan<1>(p, a, B, st, ev_start, ev_stop); break;
@@ -712,7 +735,14 @@ int enqueue_score_topk(const uint8_t* codes, const float* S, long long N, int B,
         case 16: e = launch_scan<16>(p, a, B, st, ev_start, ev_stop); break;
         default: e = launch_scan<0>(p, a, B, st, ev_start, ev_stop); break;
     }
-    return record_hip(e);
+    if (e != hipSuccess) return record_hip(e);
+    FoldArgs f;
+    f.ws_keys = a.ws_keys; f.nblk = p.nblk; f.K = K; f.stage_keys = p.stage_keys; f.candmax = p.candmax;
+    f.out_ids = out_ids; f.out_scores = out_scores;
+    e = allow_lds(fold_topk_kernel, p.fold_lds);
+    if (e != hipSuccess) return record_hip(e);
+    hipLaunchKernelGGL(fold_topk_kernel, dim3(B), dim3(kThreads), p.fold_lds, st, f);
+    return record_hip(hipGetLastError());
 }
 
 template <int S_ELEMS>
@@ -724,6 +754,11 @@ void launch_subitem(const float* queries, const float* centroids, float* S, int 
 }  // namespace
 
 extern "C" {
+
+#ifdef PQ_PHASE_TIMES
+// debug builds: device buffer of 16 timestamps (100 MHz ticks) per workgroup
+void pq_debug_set_phase_times(unsigned long long* device_buffer) { g_phase_times = device_buffer; }
+#endif
 
 int pq_subitem_scores(const float* queries, const float* centroids, float* S, int B, int d, int m, int b,
                       void* stream) {
@@ -745,7 +780,7 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K) {
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return 0;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return 0;
     const ScanPlan p = make_plan(N, B, m, K);
-    if (p.lds > kMaxLdsBytes) return 0;
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
     return workspace_bytes(p, B, K);
 }
 
