@@ -72,9 +72,12 @@ def main():
     ids = torch.empty((B, K), dtype=torch.int32, device="cuda")
     sc = torch.empty((B, K), dtype=torch.float32, device="cuda")
 
+    sub = pq.PreparedSubitemScores(Qd, Cd, out=Sd)
+    top = pq.PreparedScoreTopK(Gd, Sd, K, workspace=ws, out_ids=ids, out_scores=sc)
+
     def step():
-        pq.pq_subitem_scores(Qd, Cd, out=Sd)
-        pq.pq_score_topk(Gd, Sd, K, workspace=ws, out_ids=ids, out_scores=sc)
+        sub()
+        top()
 
     for _ in range(args.warmup):
         step()

@@ -127,3 +127,55 @@ def pq_score_topk_profile(codes: torch.Tensor, S: torch.Tensor, K: int, iters: i
     if rc != PQ_OK:
         raise PQError(rc, "pq_score_topk_profile")
     return float(ms.value)
+
+
+class PreparedSubitemScores:
+    """pq_subitem_scores with its arguments marshalled once; calling it only enqueues (for tight serving loops).
+    The tensors are kept alive by this object; `stream` is a raw hipStream_t handle (default: torch's current
+    stream at construction)."""
+
+    def __init__(self, queries: torch.Tensor, centroids: torch.Tensor, out: Optional[torch.Tensor] = None,
+                 stream: Optional[int] = None):
+        _dev(queries, torch.float32, "queries")
+        _dev(centroids, torch.float32, "centroids")
+        B, d = queries.shape
+        m, b, s = centroids.shape
+        if m * s != d:
+            raise PQError(PQ_ERR_SHAPE, "pq_subitem_scores")
+        self.S = out if out is not None else torch.empty((B, m, b), dtype=torch.float32, device=queries.device)
+        _dev(self.S, torch.float32, "S")
+        self._keep = (queries, centroids)
+        st = _stream() if stream is None else stream
+        c = ctypes
+        self._fn = lib().pq_subitem_scores
+        self._args = (c.c_void_p(queries.data_ptr()), c.c_void_p(centroids.data_ptr()), c.c_void_p(self.S.data_ptr()),
+                      c.c_int(B), c.c_int(d), c.c_int(m), c.c_int(b), c.c_void_p(st))
+
+    def __call__(self) -> torch.Tensor:
+        rc = self._fn(*self._args)
+        if rc != PQ_OK:
+            raise PQError(rc, "pq_subitem_scores")
+        return self.S
+
+
+class PreparedScoreTopK:
+    """pq_score_topk with its arguments marshalled once (workspace and outputs allocated here if not given)."""
+
+    def __init__(self, codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optional[torch.Tensor] = None,
+                 out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
+                 stream: Optional[int] = None):
+        N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores)
+        self.ids, self.scores, self.workspace = out_ids, out_scores, workspace
+        self._keep = (codes, S)
+        st = _stream() if stream is None else stream
+        c = ctypes
+        self._fn = lib().pq_score_topk
+        self._args = (c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_longlong(N), c.c_int(B), c.c_int(m),
+                      c.c_int(b), c.c_int(K), c.c_void_p(out_ids.data_ptr()), c.c_void_p(out_scores.data_ptr()),
+                      c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), c.c_void_p(st))
+
+    def __call__(self) -> Tuple[torch.Tensor, torch.Tensor]:
+        rc = self._fn(*self._args)
+        if rc != PQ_OK:
+            raise PQError(rc, "pq_score_topk")
+        return self.ids, self.scores

@@ -18,7 +18,6 @@
 // The histogram only ever prunes; every decision that picks a winner compares full keys, so the result is exact
 // for any input, including heavy ties (which merely take slower paths).
 #include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -32,12 +31,19 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kLutStride = 256;                   // table entries per split in LDS (a uint8 sub-id never runs past it)
 constexpr int kBins = 1024;                       // score buckets of the pruning histogram
 // 16-byte code vectors a thread holds per round: 4 for m >= 8, fewer for small m so a thread never holds > 16 items
-__host__ __device__ constexpr int vec_per_thread(int m) { return m >= 8 ? 4 : (m == 4 ? 2 : 1); }
+#ifndef PQ_VEC_PER_THREAD
+#define PQ_VEC_PER_THREAD 4
+#endif
+__host__ __device__ constexpr int vec_per_thread(int m) { return m >= 8 ? PQ_VEC_PER_THREAD : (m == 4 ? 2 : 1); }
 constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
+constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
 constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace
-constexpr int kBlocksPerCU = 2;                   // scan workgroups per CU over the whole grid
+#ifndef PQ_BLOCKS_PER_CU
+#define PQ_BLOCKS_PER_CU 2
+#endif
+constexpr int kBlocksPerCU = PQ_BLOCKS_PER_CU;    // scan workgroups per CU over the whole grid
 
 __device__ __forceinline__ uint32_t orderable_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -58,6 +64,54 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Cross-lane steps through the DPP data path (no LDS traffic).  Lanes whose source lies outside their row of 16
+// keep `identity`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f32(float identity, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t identity, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+constexpr int kDppRowShr = 0x110;        // + n
+constexpr int kDppBcast15 = 0x142;
+constexpr int kDppBcast31 = 0x143;
+
+// min and max over the wave, returned in every lane
+__device__ __forceinline__ void wave_minmax(float& mn, float& mx) {
+    mn = fminf(mn, dpp_f32<kDppQuadSwap1>(mn, mn));       mx = fmaxf(mx, dpp_f32<kDppQuadSwap1>(mx, mx));
+    mn = fminf(mn, dpp_f32<kDppQuadSwap2>(mn, mn));       mx = fmaxf(mx, dpp_f32<kDppQuadSwap2>(mx, mx));
+    mn = fminf(mn, dpp_f32<kDppRowHalfMirror>(mn, mn));   mx = fmaxf(mx, dpp_f32<kDppRowHalfMirror>(mx, mx));
+    mn = fminf(mn, dpp_f32<kDppRowMirror>(mn, mn));       mx = fmaxf(mx, dpp_f32<kDppRowMirror>(mx, mx));
+    // every row of 16 lanes now holds its own extremes; combine the four rows through scalar reads
+    float m0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 0));
+    float m1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 16));
+    float m2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 32));
+    float m3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 48));
+    float x0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 0));
+    float x1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 16));
+    float x2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 32));
+    float x3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 48));
+    mn = fminf(fminf(m0, m1), fminf(m2, m3));
+    mx = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+}
+
+// inclusive prefix sum over the lanes of the wave (lane i gets v[0] + .. + v[i])
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v) {
+    v += dpp_u32<kDppRowShr + 1>(0u, v);
+    v += dpp_u32<kDppRowShr + 2>(0u, v);
+    v += dpp_u32<kDppRowShr + 4>(0u, v);
+    v += dpp_u32<kDppRowShr + 8>(0u, v);
+    v += dpp_u32<kDppBcast15, 0xA>(0u, v);               // lane 15 -> lanes 16..31, lane 47 -> lanes 48..63
+    v += dpp_u32<kDppBcast31, 0xC>(0u, v);               // lane 31 -> lanes 32..63
+    return v;
 }
 
 // Bitonic sort of n (a power of two) keys in LDS, descending.  BLOCK: all threads of the workgroup take part and
@@ -147,58 +201,55 @@ __device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
 }
 
 // Range of the scores held by the workgroup -> bucket mapping.  Every thread passes the min / max of its own valid
-// scores (+inf / -inf if it has none); returns after a barrier with ctl->lo / ctl->scale set.
-__device__ void set_range(float mn, float mx, Ctl* ctl, int tid) {
+// scores (+inf / -inf if it has none).  One barrier; lo / scale come back in registers and in ctl.
+__device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid, float& lo_out, float& scale_out) {
     const int lane = tid & (kWave - 1), wave = tid / kWave;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        mn = fminf(mn, __shfl_xor(mn, off, kWave));
-        mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-    }
+    wave_minmax(mn, mx);
     if (lane == 0) { ctl->wave_min[wave] = mn; ctl->wave_max[wave] = mx; }
     __syncthreads();
-    if (tid == 0) {
-        float lo = ctl->wave_min[0], hi = ctl->wave_max[0];
+    float lo = ctl->wave_min[0], hi = ctl->wave_max[0];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) { lo = fminf(lo, ctl->wave_min[w]); hi = fmaxf(hi, ctl->wave_max[w]); }
-        float range = hi - lo;
-        float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
-        if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
+    for (int w = 1; w < kWaves; ++w) { lo = fminf(lo, ctl->wave_min[w]); hi = fmaxf(hi, ctl->wave_max[w]); }
+    float range = hi - lo;
+    float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
+    if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
+    if (tid == 0) {                                          // read by find_cut / block_select after a later barrier
         ctl->lo = lo;
         ctl->scale = scale;
         ctl->cut = -__builtin_inff();
         ctl->bstar = 0;
         ctl->ncand = 0;
     }
-    __syncthreads();
+    lo_out = lo;
+    scale_out = scale;
 }
 
 // Wave 0: find the highest bucket b* such that buckets >= b* hold at least K entries (0 if there are fewer than K in
 // all), and a score cut that every entry of a bucket >= b* exceeds.  hist has kBins counters.
 __device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
-    constexpr int per = kBins / kWave;                       // 16 buckets per lane, lane 63 owns the top ones
+    constexpr int per = kBins / kWave;                       // 16 buckets per lane; lane 0 owns the TOP ones
+    const int first = kBins - per * (lane + 1);              // this lane's lowest bucket
     uint32_t c[per];
     uint32_t mine = 0;
 #pragma unroll
-    for (int i = 0; i < per; ++i) { c[i] = hist[lane * per + i]; mine += c[i]; }
-    uint32_t suffix = mine;                                  // entries in this lane's buckets and above
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        uint32_t other = __shfl_down(suffix, off, kWave);
-        if (lane + off < kWave) suffix += other;
+    for (int i = 0; i < per; i += 4) {
+        uint4 v = *reinterpret_cast<const uint4*>(hist + first + i);
+        c[i] = v.x; c[i + 1] = v.y; c[i + 2] = v.z; c[i + 3] = v.w;
+        mine += v.x + v.y + v.z + v.w;
     }
-    uint64_t has = __ballot(suffix >= (uint32_t)K);
+    const uint32_t upto = wave_prefix_sum(mine);             // entries in this lane's buckets and all higher ones
+    const uint64_t has = __ballot(upto >= (uint32_t)K);
     if (has != 0) {
-        int owner = 63 - __builtin_clzll(has);               // highest lane whose suffix reaches K
+        const int owner = __builtin_ctzll(has);              // lane with the highest buckets that reaches K
         if (lane == owner) {
-            uint32_t above = suffix - mine;
+            uint32_t above = upto - mine;
             int found = -1;
 #pragma unroll
             for (int i = per - 1; i >= 0; --i) {
                 above += c[i];
                 if (found < 0 && above >= (uint32_t)K) found = i;
             }
-            ctl->bstar = lane * per + (found < 0 ? 0 : found);
+            ctl->bstar = first + (found < 0 ? 0 : found);
         }
     } else if (lane == 0) {
         ctl->bstar = 0;
@@ -218,50 +269,91 @@ __device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
     }
 }
 
-// Per-wave candidate list in LDS: `cap` keys, `cnt` of them in use, `thr` = K-th best key once K are known.
+// Sort a wave's candidate list (cnt of cap slots used) in place, best first.  Returns the K-th best key, or 0 if
+// the list holds fewer than K.  Out of line on purpose: it is rare and large.
+__device__ __noinline__ uint64_t sort_wave_list(uint64_t* buf, int cap, int cnt, int K, int lane) {
+    for (int t = cnt + lane; t < cap; t += kWave) buf[t] = 0;
+    wave_sync();
+    bitonic_sort_desc<false>(buf, cap, lane, kWave);
+    return cnt >= K ? buf[K - 1] : 0ull;
+}
+
+// Smallest float above x (x finite or -inf; -inf stays -inf): `s >= next_up(x)` is `s > x`.
+__device__ __forceinline__ float next_up(float x) {
+    if (x == -__builtin_inff()) return x;
+    if (x == 0.0f) return __uint_as_float(1u);
+    uint32_t u = __float_as_uint(x);
+    return __uint_as_float(x > 0.0f ? u + 1u : u - 1u);
+}
+
+// Per-wave candidate list in LDS.  A batch of at most one key per lane is appended by ballot compaction (no LDS
+// round trip: positions come from the ballot mask).  When the list passes `prune_at` it is cut back to its K best
+// and the wave's private score floor rises; when it would overflow it is sorted and pruned first.  Everything a
+// wave drops is beaten by K keys it still holds.
 struct WaveTopK {
-    uint64_t* buf;
-    int cap;
+    uint64_t* buf;       // cap keys
+    int cap;             // power of two, >= K + 64
     int K;
-    int cnt;
-    uint64_t thr;
+    int prune_at;        // list length that triggers a tightening (0: only when full)
+    int cnt;             // keys in the list (wave-uniform)
+    uint64_t thr;        // K-th best key of the list once known, else 0
+    float floor_ge;      // a score must be >= this to be worth appending
 
-    // sort the list, keep the K best, raise the threshold
-    __device__ void prune(int lane) {
-        for (int t = cnt + lane; t < cap; t += kWave) buf[t] = 0;
-        wave_sync();
-        bitonic_sort_desc<false>(buf, cap, lane, kWave);
-        if (cnt >= K) { cnt = K; thr = buf[K - 1]; }
-    }
-
-    // every lane offers one key (0 = nothing); keys above the threshold are appended
-    __device__ __forceinline__ void offer(uint64_t key, int lane) {
-        bool pass = key > thr;
-        uint64_t mask = __ballot(pass);
-        if (mask == 0) return;
+    // lanes in `mask` (non-empty, = ballot(take)) append the key of (score, id)
+    __device__ __forceinline__ void append(uint64_t mask, bool take, float score, uint32_t id, int lane) {
+        const uint64_t key = make_key(score + 0.0f, id);
         int n = __popcll(mask);
-        if (cnt + n > cap) {
-            prune(lane);
-            pass = key > thr;
-            mask = __ballot(pass);
+        if (cnt + n > cap) {                                  // rare: make room by sorting and keeping the K best
+            const uint64_t kth = sort_wave_list(buf, cap, cnt, K, lane);
+            if (cnt >= K) { cnt = K; thr = kth; floor_ge = fmaxf(floor_ge, score_of_key(thr)); }
+            take = take && key > thr;
+            mask = __ballot(take);
             if (mask == 0) return;
             n = __popcll(mask);
         }
-        int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-        if (pass) buf[pos] = key;
+        const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+        if (take) buf[pos] = key;
         cnt += n;
+    }
+
+    // cut the list back to its K best (sorted), raise thr and the floor
+    __device__ void tighten(int lane) {
+        wave_sync();
+        if (cnt <= kWave) {                                   // one key per lane: rank by counting
+            const uint64_t mine = lane < cnt ? buf[lane] : 0ull;
+            int rank = 0;
+            for (int u = 0; u < cnt; ++u) rank += (buf[u] > mine) ? 1 : 0;
+            wave_sync();
+            if (mine != 0ull && rank < K) buf[rank] = mine;
+            wave_sync();
+            if (cnt >= K) { cnt = K; thr = buf[K - 1]; }
+        } else {
+            const uint64_t kth = sort_wave_list(buf, cap, cnt, K, lane);
+            if (cnt >= K) { cnt = K; thr = kth; }
+        }
+        if (thr != 0ull) floor_ge = fmaxf(floor_ge, score_of_key(thr));
     }
 };
 
-// Sorted exact K best of the C candidates in cand[] (C <= what one pass of the workgroup can rank), by counting:
-// the position of a key is the number of candidates that beat it.  dst[0..K) zero-filled where fewer exist.
-__device__ void rank_select(const uint64_t* cand, int C, int K, uint64_t* dst, int tid) {
+// Sorted exact K best of the C candidates in cand[] by counting: the position of a key is the number of candidates
+// that beat it.  cand must have room for C rounded up to a multiple of 8 (the pad is zeroed here; a zero beats
+// nothing).  dst[0..K) is zero-filled where fewer than K exist.
+__device__ void rank_select(uint64_t* cand, int C, int K, uint64_t* dst, int tid) {
+    const int C8 = (C + 7) & ~7;
     for (int i = tid; i < K; i += kThreads) dst[i] = 0;
+    if (tid < C8 - C) cand[C + tid] = 0;
     __syncthreads();
     for (int t = tid; t < C; t += kThreads) {
-        uint64_t mine = cand[t];
+        const uint64_t mine = cand[t];
         int rank = 0;
-        for (int u = 0; u < C; ++u) rank += (cand[u] > mine) ? 1 : 0;
+        for (int u = 0; u < C8; u += 8) {
+            const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(cand + u);
+            const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(cand + u + 2);
+            const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(cand + u + 4);
+            const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(cand + u + 6);
+            rank += (p0.x > mine) + (p0.y > mine) + (p1.x > mine) + (p1.y > mine) + (p2.x > mine) + (p2.y > mine) +
+                    (p3.x > mine) + (p3.y > mine);
+        }
         if (rank < K) dst[rank] = mine;
     }
     __syncthreads();
@@ -353,6 +445,7 @@ struct ScanArgs {
     int m, b, K;
     int cap;             // keys per wave list (power of two >= K + 64)
     int candmax;         // keys of the exact-selection candidate array
+    int prune_at;        // wave list length that triggers a tightening (0: only when full)
     uint64_t* ws_keys;   // [B][nblk][K]
 };
 
@@ -361,22 +454,39 @@ struct ScanArgs {
 template <int M>
 struct Round {
     static constexpr int kVecs = M ? vec_per_thread(M) : 0;
-    static constexpr int kItems = M ? kVecs * (16 / M) : kGenericItemsPerThread;
+    static constexpr int kIPV = M ? 16 / M : 1;
+    static constexpr int kItems = M ? kVecs * kIPV : kGenericItemsPerThread;
     static constexpr int kUnitsPerThread = M ? kVecs : kGenericItemsPerThread;           // lane-sized units of work
     static constexpr int kWords = M ? kVecs * 4 : 1;
 };
 
+// Eq. 5 for the 16/M items packed in one 16-byte vector (words w[0..3], little-endian): all 16 table reads are
+// issued before any sum so they overlap in the LDS pipeline, then each item sums its m values left to right.
+// A sum of -0 is left as it is here; it is turned into +0 where a key is made.
 template <int M>
-__device__ __forceinline__ float score_packed(const float* lut, const uint32_t* words, int first_byte) {
-    float acc = 0.0f;
+__device__ __forceinline__ void score_vector(const float* lut, const uint32_t* w, float* sc) {
+    float v[16];
 #pragma unroll
-    for (int k = 0; k < M; ++k) {
-        int byte = first_byte + k;
-        uint32_t code = (words[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
-        float v = lut[k * kLutStride + code];
-        acc = (k == 0) ? v : acc + v;                 // Eq. 5, left to right
+    for (int byte = 0; byte < 16; ++byte) {
+        const uint32_t code = (w[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
+#ifdef PQ_DIAG_NOGATHER                              // tuning builds only: no table reads (results are wrong)
+        v[byte] = __uint_as_float(0x3f800000u | code);
+#else
+#ifdef PQ_DIAG_NOCONFLICT                             // tuning builds only: 32 consecutive words, no bank conflicts
+        v[byte] = lut[(byte % M) * kLutStride + (code & 31u)];
+#else
+        v[byte] = lut[(byte % M) * kLutStride + code];
+#endif
+#endif
     }
-    return acc + 0.0f;                                // -0 becomes +0
+    __builtin_amdgcn_sched_barrier(0);                // keep the 16 reads ahead of the sums
+#pragma unroll
+    for (int e = 0; e < 16 / M; ++e) {
+        float acc = v[e * M];
+#pragma unroll
+        for (int k = 1; k < M; ++k) acc = acc + v[e * M + k];
+        sc[e] = acc;
+    }
 }
 
 __device__ float score_row(const float* lut, const uint8_t* row, int m) {
@@ -406,141 +516,189 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
         acc = lut[row[0]];
         for (int k = 1; k < m; ++k) acc = acc + lut[k * kLutStride + row[k]];
     }
-    return acc + 0.0f;
+    return acc;
 }
 
-// The code vectors this thread owns in the round that starts at unit `unit_base` (vector kernels only).
+// One 16-byte code vector with bounds checks: zeros past the end, byte loads for a ragged last vector.
+__device__ __noinline__ uint4 load_vector_guarded(const uint8_t* codes, long long v, long long total_bytes) {
+    uint32_t x[4] = {0u, 0u, 0u, 0u};
+    if ((v + 1) * 16 <= total_bytes) {
+        const uint4 y = reinterpret_cast<const uint4*>(codes)[v];
+        x[0] = y.x; x[1] = y.y; x[2] = y.z; x[3] = y.w;
+    } else {
+        for (int o = 0; o < 16 && v * 16 + o < total_bytes; ++o) {
+            const uint32_t byte = (uint32_t)codes[v * 16 + o] << ((o & 3) * 8);
+            if ((o >> 2) == 0) x[0] |= byte; else if ((o >> 2) == 1) x[1] |= byte;
+            else if ((o >> 2) == 2) x[2] |= byte; else x[3] |= byte;
+        }
+    }
+    return make_uint4(x[0], x[1], x[2], x[3]);
+}
+
+// The code vectors this thread owns in the round that starts at unit `unit_base` (vector kernels only).  A round
+// that lies wholly inside the catalogue takes the branch-free path, so its loads stay in flight together.
 template <int M>
-__device__ __forceinline__ void load_round(const ScanArgs& a, long long unit_base, int tid,
+__device__ __forceinline__ void load_round(const ScanArgs& a, long long unit_base, bool inside, int tid,
                                            uint32_t (&w)[Round<M>::kWords]) {
     if constexpr (M > 0) {
         constexpr int kVecPerThread = Round<M>::kVecs;
-        const long long total_bytes = a.N * M;
-        const long long full_vecs = total_bytes / 16;
-        const long long total_vecs = (total_bytes + 15) / 16;
-        const uint4* cvec = reinterpret_cast<const uint4*>(a.codes);
+        if (inside) {
+#ifdef PQ_DIAG_NOLOAD                                 // tuning builds only: always the first round's codes
+            const uint4* base = reinterpret_cast<const uint4*>(a.codes);
+#else
+            const uint4* base = reinterpret_cast<const uint4*>(a.codes) + unit_base;
+#endif
 #pragma unroll
-        for (int u = 0; u < kVecPerThread; ++u) {
-            const long long v = unit_base + (long long)u * kThreads + tid;
-            w[4 * u] = w[4 * u + 1] = w[4 * u + 2] = w[4 * u + 3] = 0u;
-            if (v < full_vecs) {
-                uint4 x = cvec[v];
+            for (int u = 0; u < kVecPerThread; ++u) {
+                const uint4 x = base[u * kThreads + tid];
                 w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
-            } else if (v < total_vecs) {              // ragged last vector: byte loads
-                for (long long p = v * 16; p < total_bytes; ++p) {
-                    int o = (int)(p - v * 16);
-                    w[4 * u + (o >> 2)] |= (uint32_t)a.codes[p] << ((o & 3) * 8);
-                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kVecPerThread; ++u) {
+                const uint4 x = load_vector_guarded(a.codes, unit_base + (long long)u * kThreads + tid, a.N * M);
+                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
             }
         }
     }
 }
 
-// Scores and ids of the items this thread owns in that round; an id >= N marks a slot past the catalogue's end.
+// Scores of the items this thread owns in that round (slots past the catalogue's end get arbitrary finite values).
 template <int M>
 __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long unit_base, int tid,
-                                            const uint32_t (&w)[Round<M>::kWords], float (&sc)[Round<M>::kItems],
-                                            uint32_t (&id)[Round<M>::kItems]) {
+                                            const uint32_t (&w)[Round<M>::kWords], float (&sc)[Round<M>::kItems]) {
     if constexpr (M > 0) {
-        constexpr int IPV = 16 / M;
 #pragma unroll
-        for (int u = 0; u < Round<M>::kVecs; ++u) {
-            const long long v = unit_base + (long long)u * kThreads + tid;
-#pragma unroll
-            for (int e = 0; e < IPV; ++e) {
-                id[u * IPV + e] = (uint32_t)(v * IPV + e);
-                sc[u * IPV + e] = score_packed<M>(lut, &w[4 * u], e * M);
-            }
-        }
+        for (int u = 0; u < Round<M>::kVecs; ++u) score_vector<M>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
     } else {
 #pragma unroll
         for (int u = 0; u < kGenericItemsPerThread; ++u) {
             const long long item = unit_base + (long long)u * kThreads + tid;
-            id[u] = (uint32_t)item;
             sc[u] = (item < a.N) ? score_row(lut, a.codes + item * a.m, a.m) : 0.0f;
         }
     }
 }
 
+// Id of the item in slot e of this thread's round (may be >= N in the catalogue's last round).
+template <int M>
+__device__ __forceinline__ long long item_of_slot(long long unit_base, int tid, int e) {
+    constexpr int IPV = Round<M>::kIPV;
+    return (unit_base + (long long)(e / IPV) * kThreads + tid) * IPV + (e % IPV);
+}
+
 // Catalogue scan: grid = (item blocks, B).  Leaves each workgroup's exact, sorted K best keys in the workspace.
+// LDS: the score tables are a static array when m is a template value (their address is then a compile-time
+// constant, which lets sub-id extraction and address arithmetic fold into one instruction per lookup); the rest is
+// dynamic: [tables if M == 0] | hist | ctl | wave lists | cand | sorted.
 template <int M>
 __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
+    __shared__ __align__(16) float lut_static[M ? M * kLutStride : 4];
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = M ? M : a.m;
-    const ScanLds L = carve_scan(smem, m, a.cap, a.candmax);
+    const ScanLds L = carve_scan(smem, M ? 0 : m, a.cap, a.candmax);
+    float* const lut = M ? lut_static : L.lut;
     Ctl* ctl = L.ctl;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q = blockIdx.y, nblk = gridDim.x, K = a.K, b = a.b;
     constexpr int kItems = Round<M>::kItems;
     constexpr int kUnits = Round<M>::kUnitsPerThread;
+    constexpr int kWords = Round<M>::kWords;
 
     const long long total_units = M ? (a.N * M + 15) / 16 : a.N;
     const long long round_units = (long long)kThreads * kUnits;
     const long long rounds = (total_units + round_units - 1) / round_units;   // nblk <= rounds: every workgroup has one
+    const long long inside_rounds = M ? (a.N * M / 16) / round_units : a.N / round_units;   // rounds with no ragged end
 
     PQ_MARK(0);
-    // ---- 1. first round's codes on their way, then the query's table into LDS
+    // ---- 1. first two rounds' codes on their way, then the query's table into LDS
     long long r = blockIdx.x;
-    uint32_t w[Round<M>::kWords];
-    load_round<M>(a, r * round_units, tid, w);
+    uint32_t wa[kWords], wb[kWords];
     const float* Sq = a.S + (size_t)q * m * b;
-    for (int e = tid; e < m * kLutStride; e += kThreads) {
-        int k = e / kLutStride, j = e % kLutStride;
-        L.lut[e] = (j < b) ? Sq[k * b + j] : 0.0f;
+    if (b == kLutStride && m * kLutStride == 4 * kThreads) {  // m = 8, b = 256: one 16-byte load per thread
+        const float4 t4 = reinterpret_cast<const float4*>(Sq)[tid];
+        load_round<M>(a, r * round_units, r < inside_rounds, tid, wa);
+        if (r + nblk < rounds) load_round<M>(a, (r + nblk) * round_units, r + nblk < inside_rounds, tid, wb);
+        reinterpret_cast<float4*>(lut)[tid] = t4;
+    } else {
+        load_round<M>(a, r * round_units, r < inside_rounds, tid, wa);
+        if (r + nblk < rounds) load_round<M>(a, (r + nblk) * round_units, r + nblk < inside_rounds, tid, wb);
+        for (int e = tid; e < m * kLutStride; e += kThreads) {
+            int k = e / kLutStride, j = e % kLutStride;
+            lut[e] = (j < b) ? Sq[k * b + j] : 0.0f;
+        }
     }
     for (int i = tid; i < kBins; i += kThreads) L.hist[i] = 0;
     __syncthreads();
     PQ_MARK(1);
 
     // ---- 2. first round: scores in registers, histogram over their range, cut
-    WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, 0, 0ull};
+    WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
     {
         float sc[kItems];
-        uint32_t id[kItems];
-        score_round<M>(a, L.lut, r * round_units, tid, w, sc, id);
+        score_round<M>(a, lut, r * round_units, tid, wa, sc);
+        if (r + 2 * nblk < rounds)                             // wa is free again: third round on its way
+            load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wa);
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
-            if (id[e] < a.N) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
-        set_range(mn, mx, ctl, tid);
+            if (item_of_slot<M>(r * round_units, tid, e) < a.N) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
+        float lo, scale;
+        set_range(mn, mx, ctl, tid, lo, scale);
         PQ_MARK(2);
-        const float lo = ctl->lo, scale = ctl->scale;
         int bk[kItems];
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
             bk[e] = bucket_of(sc[e], lo, scale);
-            if (id[e] < a.N) atomicAdd(&L.hist[bk[e]], 1u);
+            if (item_of_slot<M>(r * round_units, tid, e) < a.N) atomicAdd(&L.hist[bk[e]], 1u);
         }
         __syncthreads();
         if (tid < kWave) find_cut(L.hist, K, ctl, lane);
         __syncthreads();
         PQ_MARK(3);
         const int bstar = ctl->bstar;
+        top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            uint64_t key = (id[e] < a.N && bk[e] >= bstar) ? make_key(sc[e], id[e]) : 0ull;
-            top.offer(key, lane);
+            const long long item = item_of_slot<M>(r * round_units, tid, e);
+            const bool take = item < a.N && bk[e] >= bstar;
+            const uint64_t mask = __ballot(take);
+            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
         }
+        if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
         r += nblk;
     }
     PQ_MARK(4);
 
-    // ---- 3. stream the remaining rounds against the cut
-    const float cut = ctl->cut;
-    for (; r < rounds; r += nblk) {
+    // ---- 3. stream the remaining rounds against the wave's floor, one round of loads always in flight
+    auto process = [&](const uint32_t (&w)[kWords], long long rr) {
         float sc[kItems];
-        uint32_t id[kItems];
-        load_round<M>(a, r * round_units, tid, w);
-        score_round<M>(a, L.lut, r * round_units, tid, w, sc, id);
-        bool any = false;
+        score_round<M>(a, lut, rr * round_units, tid, w, sc);
+        float best = sc[0];
 #pragma unroll
-        for (int e = 0; e < kItems; ++e) any = any || (sc[e] > cut && id[e] < a.N);
-        if (__ballot(any) == 0) continue;
+        for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
+#ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
+        if (__ballot(best >= 1.0e30f) == 0) return;
+#endif
+        if (__ballot(best >= top.floor_ge) == 0) return;      // nothing in this round can matter
+        const bool inside = rr < inside_rounds;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            uint64_t key = (sc[e] > cut && id[e] < a.N) ? make_key(sc[e], id[e]) : 0ull;
-            top.offer(key, lane);
+            const long long item = item_of_slot<M>(rr * round_units, tid, e);
+            const bool take = sc[e] >= top.floor_ge && (inside || item < a.N);
+            const uint64_t mask = __ballot(take);
+            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
         }
+        if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
+    };
+    // here wb holds round r and wa round r + nblk (where they exist)
+    while (r < rounds) {
+        process(wb, r);
+        if (r + 2 * nblk < rounds) load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wb);
+        r += nblk;
+        if (r >= rounds) break;
+        process(wa, r);
+        if (r + 2 * nblk < rounds) load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wa);
+        r += nblk;
     }
     PQ_MARK(5);
 
@@ -556,7 +714,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     }
     if (total <= a.candmax) {
         for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
-        rank_select(L.cand, total, K, L.sorted, tid);       // its first barrier orders the copies above
+        rank_select(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
     } else {
         for (int t = top.cnt + lane; t < a.cap; t += kWave) top.buf[t] = 0;
         __syncthreads();
@@ -593,13 +751,60 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     const uint64_t* all = a.ws_keys + (size_t)q * a.nblk * K;
     const long long nkeys = (long long)a.nblk * K;
 
-    // score range of all the keys (empty slots of short lists are 0)
+    // score range of all the keys (empty slots of short lists are 0); a modest number of keys stays in registers
+    const int lane = tid & (kWave - 1);
+    const bool in_regs = nkeys <= (long long)kThreads * kFoldRegs;
+    uint64_t keys[kFoldRegs];
     float mn = __builtin_inff(), mx = -__builtin_inff();
-    for (long long i = tid; i < nkeys; i += kThreads) {
-        uint64_t key = all[i];
-        if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
+    if (in_regs) {
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            const long long i = (long long)r * kThreads + tid;
+            keys[r] = (i < nkeys) ? all[i] : 0ull;
+            if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
+        }
+    } else {
+        for (long long i = tid; i < nkeys; i += kThreads) {
+            uint64_t key = all[i];
+            if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
+        }
     }
-    set_range(mn, mx, ctl, tid);
+    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+    float lo, scale;
+    set_range(mn, mx, ctl, tid, lo, scale);
+
+    if (in_regs) {
+        // one pass: histogram, cut, collect the few keys at or above the cut, rank them
+        int bk[kFoldRegs];
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            bk[r] = -1;
+            if (keys[r]) { bk[r] = bucket_of(score_of_key(keys[r]), lo, scale); atomicAdd(&hist[bk[r]], 1u); }
+        }
+        __syncthreads();
+        if (tid < kWave) find_cut(hist, K, ctl, lane);
+        __syncthreads();
+        const int bstar = ctl->bstar;
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            if (bk[r] >= bstar) {
+                int pos = atomicAdd(&ctl->ncand, 1);
+                if (pos < a.candmax) cand[pos] = keys[r];
+            }
+        }
+        __syncthreads();
+        const int C = ctl->ncand;
+        if (C <= a.candmax) {
+            rank_select(cand, C, K, sorted, tid);
+            for (int t = tid; t < K; t += kThreads) {
+                uint64_t key = sorted[t];
+                a.out_ids[(size_t)q * K + t] = id_of_key(key);
+                a.out_scores[(size_t)q * K + t] = score_of_key(key);
+            }
+            return;
+        }
+        // too many keys share the cut bucket (heavy ties): take the staged, sorting path below
+    }
 
     int keep = 0;                                            // best-so-far keys carried at the front of stage
     long long done = 0;
@@ -648,7 +853,9 @@ struct ScanPlan {
     int cap;         // keys per wave list
     int candmax;     // keys of the candidate array
     int stage_keys;  // keys the fold stages per pass
-    size_t scan_lds, fold_lds;
+    size_t scan_dyn_lds;     // dynamic LDS of the scan launch
+    size_t scan_lds;         // dynamic + the static score tables of the vector kernels
+    size_t fold_lds;
     bool vec;
 };
 
@@ -672,7 +879,8 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     if (p.candmax < 512) p.candmax = 512;
     p.stage_keys = next_pow2(2 * K);
     if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
-    p.scan_lds = scan_lds_bytes(m, p.cap, p.candmax, K);
+    p.scan_dyn_lds = scan_lds_bytes(p.vec ? 0 : m, p.cap, p.candmax, K);
+    p.scan_lds = p.scan_dyn_lds + (p.vec ? (size_t)m * kLutStride * sizeof(float) : 0);
     p.fold_lds = fold_lds_bytes(p.stage_keys, p.candmax, K);
     return p;
 }
@@ -704,42 +912,41 @@ hipError_t allow_lds(KernelT kernel, size_t bytes) {
 }
 
 template <int M>
-hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st, hipEvent_t ev_start,
-                       hipEvent_t ev_stop) {
-    hipError_t e = allow_lds(scan_topk_kernel<M>, p.scan_lds);
+hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    hipError_t e = allow_lds(scan_topk_kernel<M>, p.scan_dyn_lds);
     if (e != hipSuccess) return e;
-    dim3 grid(p.nblk, B), block(kThreads);
-    if (ev_start || ev_stop) {
-        hipExtLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.scan_lds, st, ev_start, ev_stop, 0, a);
-    } else {
-        hipLaunchKernelGGL(scan_topk_kernel<M>, grid, block, p.scan_lds, st, a);
-    }
+    hipLaunchKernelGGL(scan_topk_kernel<M>, dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
     return hipGetLastError();
 }
 
-// Enqueue scan + fold.  With events, they take the scan kernel's own start and end timestamps.
-int enqueue_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
-                       float* out_scores, void* workspace, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    const ScanPlan p = make_plan(N, B, m, K);
+// Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
+int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                 void* workspace, hipStream_t st) {
     ScanArgs a;
     a.phase_times = g_phase_times;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
     a.cap = p.cap; a.candmax = p.candmax;
+    a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
     a.ws_keys = static_cast<uint64_t*>(workspace);
     hipError_t e;
     switch (p.vec ? m : 0) {
-        case 1: e = launch_scan<1>(p, a, B, st, ev_start, ev_stop); break;
-        case 2: e = launch_scan<2>(p, a, B, st, ev_start, ev_stop); break;
-        case 4: e = launch_scan<4>(p, a, B, st, ev_start, ev_stop); break;
-        case 8: e = launch_scan<8>(p, a, B, st, ev_start, ev_stop); break;
-        case 16: e = launch_scan<16>(p, a, B, st, ev_start, ev_stop); break;
-        default: e = launch_scan<0>(p, a, B, st, ev_start, ev_stop); break;
+        case 1: e = launch_scan<1>(p, a, B, st); break;
+        case 2: e = launch_scan<2>(p, a, B, st); break;
+        case 4: e = launch_scan<4>(p, a, B, st); break;
+        case 8: e = launch_scan<8>(p, a, B, st); break;
+        case 16: e = launch_scan<16>(p, a, B, st); break;
+        default: e = launch_scan<0>(p, a, B, st); break;
     }
-    if (e != hipSuccess) return record_hip(e);
+    return record_hip(e);
+}
+
+// Enqueue the fold of the workspace's lists into the outputs.
+int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
     FoldArgs f;
-    f.ws_keys = a.ws_keys; f.nblk = p.nblk; f.K = K; f.stage_keys = p.stage_keys; f.candmax = p.candmax;
+    f.ws_keys = static_cast<const uint64_t*>(workspace);
+    f.nblk = p.nblk; f.K = K; f.stage_keys = p.stage_keys; f.candmax = p.candmax;
     f.out_ids = out_ids; f.out_scores = out_scores;
-    e = allow_lds(fold_topk_kernel, p.fold_lds);
+    hipError_t e = allow_lds(fold_topk_kernel, p.fold_lds);
     if (e != hipSuccess) return record_hip(e);
     hipLaunchKernelGGL(fold_topk_kernel, dim3(B), dim3(kThreads), p.fold_lds, st, f);
     return record_hip(hipGetLastError());
@@ -788,8 +995,11 @@ int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int 
                   float* out_scores, void* workspace, size_t workspace_bytes_given, void* stream) {
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
-    return enqueue_score_topk(codes, S, N, B, m, b, K, out_ids, out_scores, workspace,
-                              static_cast<hipStream_t>(stream), nullptr, nullptr);
+    const ScanPlan p = make_plan(N, B, m, K);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
+    if (rc != PQ_OK) return rc;
+    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
 }
 
 int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
@@ -799,25 +1009,24 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
     if (iters < 1) return PQ_ERR_SHAPE;
+    const ScanPlan p = make_plan(N, B, m, K);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipEvent_t a = nullptr, z = nullptr;
-    hipError_t e = hipEventCreate(&a);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    hipError_t e = hipEventCreate(&ev0);
     if (e != hipSuccess) return record_hip(e);
-    e = hipEventCreate(&z);
-    if (e != hipSuccess) { (void)hipEventDestroy(a); return record_hip(e); }
-    double sum = 0.0;
-    for (int it = 0; it < iters && rc == PQ_OK; ++it) {
-        rc = enqueue_score_topk(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, st, a, z);
-        if (rc != PQ_OK) break;
-        e = hipStreamSynchronize(st);
-        float ms = 0.0f;
-        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, z);
-        if (e != hipSuccess) { rc = record_hip(e); break; }
-        sum += ms;
-    }
-    (void)hipEventDestroy(a);
-    (void)hipEventDestroy(z);
-    if (rc == PQ_OK) *scan_ms = (float)(sum / iters);
+    e = hipEventCreate(&ev1);
+    if (e != hipSuccess) { (void)hipEventDestroy(ev0); return record_hip(e); }
+    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);           // untimed warm-up launch
+    if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev0, st));
+    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
+    if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev1, st));
+    if (rc == PQ_OK) rc = enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+    if (rc == PQ_OK) rc = record_hip(hipStreamSynchronize(st));
+    float ms = 0.0f;
+    if (rc == PQ_OK) rc = record_hip(hipEventElapsedTime(&ms, ev0, ev1));
+    (void)hipEventDestroy(ev0);
+    (void)hipEventDestroy(ev1);
+    if (rc == PQ_OK) *scan_ms = ms / (float)iters;
     return rc;
 }
 
