@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-iters", type=int, default=50)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of the code matrix (N*m bytes read, N*m written): "
+                         "the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -78,6 +81,10 @@ def main():
     def step():
         sub()
         top()
+
+    if args.calibrate_copy:
+        torch.empty_like(Gd).copy_(Gd)
+        torch.cuda.synchronize()
 
     for _ in range(args.warmup):
         step()
