@@ -40,6 +40,17 @@ def cpu_baseline(G, cent, Q, K, budget_s=12.0):
             "sample": f"{n} single-query passes of the oracle (Eq. 4, Eq. 5 over all {N} items, TopK) in {el:.2f} s"}
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per scan launch from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, each scaled by a
+    plain copy of known size), if this workload has been profiled; else None.  Counters cannot be read in-process."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +119,7 @@ def main():
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9
 
     ms_per_step = el / args.steps * 1e3
+    workload = f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch={B}, codes {cfg.codes}, seed {cfg.seed}"
     out = {
         "metric": "items scored/sec (PQTopK, whole path incl. top-K)",
         "value": N * B * args.steps / el,
@@ -116,10 +128,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch={B}, codes {cfg.codes}, seed {cfg.seed}"},
+        "config": {"workload": workload},
         "parity_vs_oracle": parity,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(workload),
                      "kernel": "catalogue scan (Eq. 5 + per-workgroup top-K)", "kernel_ms": scan_ms,
                      "algorithmic_bytes_per_launch": algo_bytes},
     }
