@@ -193,11 +193,12 @@ struct Ctl {
     float wave_max[kWaves];
 };
 
+template <int BINS = kBins>
 __device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
     // monotone non-decreasing in score: subtract, multiply by a non-negative, truncate (negative and NaN give 0)
     float x = (score - lo) * scale;
     int bkt = (x > 0.0f) ? (int)x : 0;
-    return bkt > kBins - 1 ? kBins - 1 : bkt;
+    return bkt > BINS - 1 ? BINS - 1 : bkt;
 }
 
 // Range of the scores held by the workgroup -> bucket mapping.  Every thread passes the min / max of its own valid
@@ -224,11 +225,12 @@ __device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid,
     scale_out = scale;
 }
 
-// Wave 0: find the highest bucket b* such that buckets >= b* hold at least K entries (0 if there are fewer than K in
-// all), and a score cut that every entry of a bucket >= b* exceeds.  hist has kBins counters.
+// One wave: find the highest bucket b* such that buckets >= b* hold at least K entries (0 if there are fewer than K
+// in all), and a score cut that every entry of a bucket >= b* exceeds.  hist has BINS counters (a multiple of 256).
+template <int BINS = kBins>
 __device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
-    constexpr int per = kBins / kWave;                       // 16 buckets per lane; lane 0 owns the TOP ones
-    const int first = kBins - per * (lane + 1);              // this lane's lowest bucket
+    constexpr int per = BINS / kWave;                        // buckets per lane; lane 0 owns the TOP ones
+    const int first = BINS - per * (lane + 1);               // this lane's lowest bucket
     uint32_t c[per];
     uint32_t mine = 0;
 #pragma unroll
@@ -262,8 +264,8 @@ __device__ void find_cut(const uint32_t* hist, int K, Ctl* ctl, int lane) {
         if (bstar > 0 && ctl->scale > 0.0f) {
             float width = 1.0f / ctl->scale;
             cut = ctl->lo + ((float)bstar - 0.5f) * width;
-            for (int guard = 0; guard < 64 && bucket_of(cut, ctl->lo, ctl->scale) >= bstar; ++guard) cut -= width;
-            if (bucket_of(cut, ctl->lo, ctl->scale) >= bstar) cut = -__builtin_inff();
+            for (int guard = 0; guard < 64 && bucket_of<BINS>(cut, ctl->lo, ctl->scale) >= bstar; ++guard) cut -= width;
+            if (bucket_of<BINS>(cut, ctl->lo, ctl->scale) >= bstar) cut = -__builtin_inff();
         }
         ctl->cut = cut;
     }
@@ -321,8 +323,18 @@ struct WaveTopK {
         wave_sync();
         if (cnt <= kWave) {                                   // one key per lane: rank by counting
             const uint64_t mine = lane < cnt ? buf[lane] : 0ull;
+            const int cnt8 = (cnt + 7) & ~7;                  // cap >= 128 > cnt8; pad with zeros (a zero beats nothing)
+            if (lane >= cnt && lane < cnt8) buf[lane] = 0ull;
+            wave_sync();
             int rank = 0;
-            for (int u = 0; u < cnt; ++u) rank += (buf[u] > mine) ? 1 : 0;
+            for (int u = 0; u < cnt8; u += 8) {               // eight keys per trip keeps the LDS latency off the path
+                const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(buf + u);
+                const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(buf + u + 2);
+                const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(buf + u + 4);
+                const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(buf + u + 6);
+                rank += (p0.x > mine) + (p0.y > mine) + (p1.x > mine) + (p1.y > mine) + (p2.x > mine) + (p2.y > mine) +
+                        (p3.x > mine) + (p3.y > mine);
+            }
             wave_sync();
             if (mine != 0ull && rank < K) buf[rank] = mine;
             wave_sync();
@@ -725,6 +737,288 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     PQ_MARK(6);
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Batched scan: one workgroup serves a tile of kQ queries with one pass over its share of G.  The tables of two
+// queries are interleaved ([pair][split][sub-id] -> float2), so one 8-byte LDS read returns the table values of
+// two queries for one sub-id: random 8-byte gathers run close to the LDS peak (128 B/clk/CU) where 4-byte ones reach
+// half of it, and sub-id extraction, address arithmetic and the code loads are shared by the whole tile.
+// grid = (item blocks, ceil(B / kQ)).  Static LDS: the tile's tables.  Dynamic LDS:
+// hist[kQ][kTiledBins] | ctl[kQ] | state[kWaves][kQ] | lists[kQ][kWaves][cap] | cand[candmax] | sorted[K].
+constexpr int kQ = 4;                // queries per tile
+constexpr int kTileVecs = 2;         // 16-byte code vectors a thread holds per round
+constexpr int kTiledBins = kBins / kQ;   // buckets per query; the kQ histograms together serve as one kBins histogram
+
+// One (wave, query) candidate list's state.  It lives in LDS so that the streaming loop keeps none of it in registers.
+struct WaveQ {
+    unsigned long long thr;
+    int cnt;
+    float floor_ge;
+};
+
+__host__ __device__ inline size_t tiled_lds_bytes(int cap, int candmax, int K) {
+    return (size_t)kBins * sizeof(uint32_t) + (size_t)kQ * align16(sizeof(Ctl)) +
+           (size_t)kWaves * kQ * sizeof(WaveQ) + (size_t)kQ * kWaves * cap * sizeof(uint64_t) +
+           (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
+}
+
+// Eq. 5 for the 16/M items of one code vector and the kQ queries of the tile; sc[q][e], sums left to right.
+template <int M>
+__device__ __forceinline__ void score_vector_tiled(const float2* lut2, const uint32_t* w, float (&sc)[kQ][16 / M]) {
+#pragma unroll
+    for (int p = 0; p < kQ / 2; ++p) {
+        float2 v[16];
+#pragma unroll
+        for (int byte = 0; byte < 16; ++byte) {
+            const uint32_t code = (w[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
+            v[byte] = lut2[(p * M + (byte % M)) * kLutStride + code];
+        }
+        __builtin_amdgcn_sched_barrier(0);                // keep the 16 reads ahead of the sums
+#pragma unroll
+        for (int e = 0; e < 16 / M; ++e) {
+            float a0 = v[e * M].x, a1 = v[e * M].y;
+#pragma unroll
+            for (int k = 1; k < M; ++k) { a0 = a0 + v[e * M + k].x; a1 = a1 + v[e * M + k].y; }
+            // the empty asm ties the finished sums to a point the next group's reads cannot cross, so at most one
+            // group's 16 values are live at a time (otherwise all reads get hoisted and registers triple)
+#ifdef PQ_TILED_PIN
+            asm volatile("" : "+v"(a0), "+v"(a1) : : "memory");
+#endif
+            sc[2 * p][e] = a0;
+            sc[2 * p + 1][e] = a1;
+        }
+    }
+}
+
+// What one thread offers to one query's list after a round: NI scores, their item ids, and whether each may enter.
+template <int NI>
+struct Slots {
+    float sc[NI];
+    uint32_t id[NI];
+    bool ok[NI];
+};
+
+// The uncommon half of a round for one query: some lane holds a score at or above the list's floor.  Out of line, with
+// the list's state loaded from and stored back to LDS, so the streaming loop stays small.
+template <int NI>
+__device__ __noinline__ void offer_slow(WaveQ* st, uint64_t* buf, int cap, int K, int prune_at, Slots<NI> s, int lane) {
+    WaveTopK top{buf, cap, K, prune_at, st->cnt, st->thr, st->floor_ge};
+#pragma unroll
+    for (int e = 0; e < NI; ++e) {
+        const bool take = s.ok[e] && s.sc[e] >= top.floor_ge;
+        const uint64_t mask = __ballot(take);
+        if (mask != 0) top.append(mask, take, s.sc[e], s.id[e], lane);
+    }
+    if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
+    if (lane == 0) { st->cnt = top.cnt; st->thr = top.thr; st->floor_ge = top.floor_ge; }
+    wave_sync();
+}
+
+template <int M>
+__global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, int B) {
+    constexpr int IPV = 16 / M, kItems = kTileVecs * IPV, kWords = kTileVecs * 4;
+    __shared__ __align__(16) float2 lut2[(kQ / 2) * M * kLutStride];
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+    unsigned char* pctl = smem + (size_t)kBins * sizeof(uint32_t);
+    WaveQ* states = reinterpret_cast<WaveQ*>(pctl + (size_t)kQ * align16(sizeof(Ctl)));
+    uint64_t* lists = reinterpret_cast<uint64_t*>(states + kWaves * kQ);
+    uint64_t* cand = lists + (size_t)kQ * kWaves * a.cap;
+    uint64_t* sorted = cand + a.candmax;
+    auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(pctl + (size_t)q * align16(sizeof(Ctl))); };
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int q0 = blockIdx.y * kQ, nblk = gridDim.x, K = a.K, b = a.b;
+    const int nq = (B - q0 < kQ) ? B - q0 : kQ;               // queries of this tile that exist
+    const long long total_units = (a.N * M + 15) / 16;
+    const long long round_units = (long long)kThreads * kTileVecs;
+    const long long rounds = (total_units + round_units - 1) / round_units;
+    const long long inside_rounds = (a.N * M / 16) / round_units;
+    WaveQ* const my_state = states + wave * kQ;
+    auto list_of = [&](int q) { return lists + ((size_t)q * kWaves + wave) * a.cap; };
+
+    auto load = [&](long long rr, uint32_t (&w)[kWords]) {
+        const long long unit_base = rr * round_units;
+        if (rr < inside_rounds) {
+            const uint4* base = reinterpret_cast<const uint4*>(a.codes) + unit_base;
+#pragma unroll
+            for (int u = 0; u < kTileVecs; ++u) {
+                const uint4 x = base[u * kThreads + tid];
+                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kTileVecs; ++u) {
+                const uint4 x = load_vector_guarded(a.codes, unit_base + (long long)u * kThreads + tid, a.N * M);
+                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
+            }
+        }
+    };
+    auto item_of = [&](long long rr, int e) {
+        return (rr * round_units + (long long)(e / IPV) * kThreads + tid) * IPV + (e % IPV);
+    };
+    auto score = [&](const uint32_t (&w)[kWords], float (&sc)[kQ][kItems]) {
+#pragma unroll
+        for (int u = 0; u < kTileVecs; ++u) {
+            float part[kQ][IPV];
+            score_vector_tiled<M>(lut2, &w[4 * u], part);
+#pragma unroll
+            for (int q = 0; q < kQ; ++q)
+#pragma unroll
+                for (int e = 0; e < IPV; ++e) sc[q][u * IPV + e] = part[q][e];
+        }
+    };
+
+    PQ_MARK(0);
+    // ---- 1. codes on their way, the tile's tables into LDS (queries past B get zero tables and are never scored)
+    long long r = blockIdx.x;
+    uint32_t wa[kWords], wb[kWords];
+    load(r, wa);
+    if (r + nblk < rounds) load(r + nblk, wb);
+    {
+        float* lutf = reinterpret_cast<float*>(lut2);
+        if (b == kLutStride) {                                // whole rows: 16-byte loads, four sub-ids at a time
+            for (int e4 = tid; e4 < kQ * M * kLutStride / 4; e4 += kThreads) {
+                const int q = e4 / (M * kLutStride / 4), kj4 = e4 % (M * kLutStride / 4);
+                float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (q < nq) v = reinterpret_cast<const float4*>(a.S + (size_t)(q0 + q) * M * kLutStride)[kj4];
+                float* dst = lutf + ((size_t)(q >> 1) * M * kLutStride + (size_t)kj4 * 4) * 2 + (q & 1);
+                dst[0] = v.x; dst[2] = v.y; dst[4] = v.z; dst[6] = v.w;
+            }
+        } else {
+            for (int e = tid; e < kQ * M * kLutStride; e += kThreads) {
+                const int q = e / (M * kLutStride), kj = e % (M * kLutStride), k = kj / kLutStride, j = kj % kLutStride;
+                const float v = (q < nq && j < b) ? a.S[((size_t)(q0 + q) * M + k) * b + j] : 0.0f;
+                lutf[(((q >> 1) * M + k) * kLutStride + j) * 2 + (q & 1)] = v;
+            }
+        }
+        for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+        if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
+    }
+    __syncthreads();
+    PQ_MARK(1);
+
+    // one round's scores against the kQ lists of this wave
+    auto offer_round = [&](const float (&sc)[kQ][kItems], long long rr, const int* bk, const int* bstar) {
+        const bool inside = rr < inside_rounds;
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            if (q >= nq) continue;
+            float best = sc[q][0];
+#pragma unroll
+            for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[q][e]);
+#ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
+            if (bk == nullptr && __ballot(best >= 1.0e30f) == 0) continue;
+#endif
+            if (__ballot(best >= my_state[q].floor_ge) == 0) continue;       // the usual case
+            Slots<kItems> s;
+#pragma unroll
+            for (int e = 0; e < kItems; ++e) {
+                const long long item = item_of(rr, e);
+                s.sc[e] = sc[q][e];
+                s.id[e] = (uint32_t)item;
+                s.ok[e] = (inside || item < a.N) && (bk == nullptr || bk[q * kItems + e] >= bstar[q]);
+            }
+            offer_slow<kItems>(&my_state[q], list_of(q), a.cap, K, a.prune_at, s, lane);
+        }
+    };
+
+    // ---- 2. first round: per query a histogram over its own score range gives that query's cut
+    {
+        float sc[kQ][kItems];
+        score(wa, sc);
+        if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+            for (int e = 0; e < kItems; ++e)
+                if (item_of(r, e) < a.N) { mn = fminf(mn, sc[q][e]); mx = fmaxf(mx, sc[q][e]); }
+            wave_minmax(mn, mx);
+            if (lane == 0) { ctl_of(q)->wave_min[wave] = mn; ctl_of(q)->wave_max[wave] = mx; }
+        }
+        __syncthreads();
+        int bk[kQ * kItems], bstar[kQ];
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            Ctl* c = ctl_of(q);
+            float lo = c->wave_min[0], hi = c->wave_max[0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) { lo = fminf(lo, c->wave_min[w]); hi = fmaxf(hi, c->wave_max[w]); }
+            const float range = hi - lo;
+            float scale = (range > 0.0f) ? (float)kTiledBins / range : 0.0f;
+            if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
+            if (tid == q) { c->lo = lo; c->scale = scale; c->cut = -__builtin_inff(); c->bstar = 0; c->ncand = 0; }
+#pragma unroll
+            for (int e = 0; e < kItems; ++e) {
+                bk[q * kItems + e] = bucket_of<kTiledBins>(sc[q][e], lo, scale);
+                if (q < nq && item_of(r, e) < a.N) atomicAdd(&hist[q * kTiledBins + bk[q * kItems + e]], 1u);
+            }
+        }
+        __syncthreads();
+        PQ_MARK(2);
+        if (wave < kQ) find_cut<kTiledBins>(hist + wave * kTiledBins, K, ctl_of(wave), lane);
+        __syncthreads();
+        PQ_MARK(3);
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            bstar[q] = ctl_of(q)->bstar;
+            if (lane == 0) my_state[q].floor_ge = next_up(ctl_of(q)->cut);
+        }
+        wave_sync();
+        offer_round(sc, r, bk, bstar);
+        r += nblk;
+    }
+    PQ_MARK(4);
+
+    // ---- 3. stream: wb holds round r, wa round r + nblk
+    while (r < rounds) {
+        {
+            float sc[kQ][kItems];
+            score(wb, sc);
+            if (r + 2 * nblk < rounds) load(r + 2 * nblk, wb);
+            offer_round(sc, r, nullptr, nullptr);
+        }
+        r += nblk;
+        if (r >= rounds) break;
+        {
+            float sc[kQ][kItems];
+            score(wa, sc);
+            if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+            offer_round(sc, r, nullptr, nullptr);
+        }
+        r += nblk;
+    }
+    PQ_MARK(5);
+
+    // ---- 4. per query: the waves' lists -> exact K best of this workgroup, sorted, to the workspace
+    __syncthreads();                                          // every wave's list state in LDS is final
+    for (int q = 0; q < nq; ++q) {
+        Ctl* c = ctl_of(q);
+        int total = 0, before = 0;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) {
+            const int n = states[wv * kQ + q].cnt;
+            if (wv < wave) before += n;
+            total += n;
+        }
+        const int mine = my_state[q].cnt;
+        uint64_t* buf = list_of(q);
+        if (total <= a.candmax) {
+            for (int t = lane; t < mine; t += kWave) cand[before + t] = buf[t];
+            rank_select(cand, total, K, sorted, tid);
+        } else {
+            for (int t = mine + lane; t < a.cap; t += kWave) buf[t] = 0;
+            if (tid == 0) { c->lo = ctl_of(q)->lo; }
+            __syncthreads();
+            block_select(lists + (size_t)q * kWaves * a.cap, kWaves * a.cap, K, sorted, cand, a.candmax, hist, c, tid);
+        }
+        uint64_t* mine_out = a.ws_keys + ((size_t)(q0 + q) * nblk + blockIdx.x) * K;
+        for (int t = tid; t < K; t += kThreads) mine_out[t] = sorted[t];
+        __syncthreads();                                      // sorted / cand are reused by the next query
+    }
+    PQ_MARK(6);
+}
+
 // Grid-level fold: one workgroup per query turns the nblk sorted lists of K keys into the final K, sorted.
 // Dynamic LDS: hist | ctl | stage (stage_keys, a power of two >= 2K) | cand | sorted
 struct FoldArgs {
@@ -849,6 +1143,7 @@ int next_pow2(int x) {
 }
 
 struct ScanPlan {
+    bool tiled;      // batched kernel: kQ queries per workgroup
     int nblk;        // item blocks per query
     int cap;         // keys per wave list
     int candmax;     // keys of the candidate array
@@ -881,6 +1176,32 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
     p.scan_dyn_lds = scan_lds_bytes(p.vec ? 0 : m, p.cap, p.candmax, K);
     p.scan_lds = p.scan_dyn_lds + (p.vec ? (size_t)m * kLutStride * sizeof(float) : 0);
+    p.tiled = false;
+#ifdef PQ_NO_TILED                                        // tuning builds only
+    if (false) {
+#else
+    if (B >= 2 && (m == 8 || m == 16)) {                      // batched kernel, if its tables and lists fit in LDS
+#endif
+        const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
+        const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
+        if (all <= kMaxLdsBytes) {
+            p.tiled = true;
+            p.scan_dyn_lds = dyn;
+            p.scan_lds = all;
+            const long long tiles = (B + kQ - 1) / kQ;
+            const long long t_round = (long long)kThreads * kTileVecs;
+            const long long t_rounds = (units + t_round - 1) / t_round;
+#ifndef PQ_TILED_BLOCKS_PER_CU
+#define PQ_TILED_BLOCKS_PER_CU 1
+#endif
+            long long want = ((long long)PQ_TILED_BLOCKS_PER_CU * kAssumedCUs) / tiles;
+            if (want < 8) want = 8;
+            long long nb = t_rounds < want ? t_rounds : want;
+            if (nb >= 8) nb &= ~7LL;                          // every tile's item block x lands on XCD x % 8
+            if (nb < 1) nb = 1;
+            p.nblk = (int)nb;
+        }
+    }
     p.fold_lds = fold_lds_bytes(p.stage_keys, p.candmax, K);
     return p;
 }
@@ -929,6 +1250,17 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
     a.ws_keys = static_cast<uint64_t*>(workspace);
     hipError_t e;
+    if (p.tiled) {
+        const dim3 grid(p.nblk, (B + kQ - 1) / kQ);
+        if (m == 8) {
+            e = allow_lds(scan_topk_tiled_kernel<8>, p.scan_dyn_lds);
+            if (e == hipSuccess) hipLaunchKernelGGL(scan_topk_tiled_kernel<8>, grid, dim3(kThreads), p.scan_dyn_lds, st, a, B);
+        } else {
+            e = allow_lds(scan_topk_tiled_kernel<16>, p.scan_dyn_lds);
+            if (e == hipSuccess) hipLaunchKernelGGL(scan_topk_tiled_kernel<16>, grid, dim3(kThreads), p.scan_dyn_lds, st, a, B);
+        }
+        return record_hip(e == hipSuccess ? hipGetLastError() : e);
+    }
     switch (p.vec ? m : 0) {
         case 1: e = launch_scan<1>(p, a, B, st); break;
         case 2: e = launch_scan<2>(p, a, B, st); break;
