@@ -19,6 +19,7 @@
 // for any input, including heavy ties (which merely take slower paths).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <string.h>
 
 #include "pqtopk.h"
@@ -188,6 +189,7 @@ struct Ctl {
     float cut;           // scores <= cut cannot reach this workgroup's top K (valid after a histogram pass)
     int bstar;           // bucket of the K-th best in the histogrammed set
     int ncand;           // candidates collected for an exact selection
+    int keep;            // batched kernel: keys currently held in the workgroup's best[] array of this query
     int wave_cnt[kWaves];
     float wave_min[kWaves];
     float wave_max[kWaves];
@@ -459,6 +461,9 @@ struct ScanArgs {
     int candmax;         // keys of the exact-selection candidate array
     int prune_at;        // wave list length that triggers a tightening (0: only when full)
     uint64_t* ws_keys;   // [B][nblk][K]
+    int checkpoint_factor;   // batched kernel: growth of the number of rounds between workgroup checkpoints (>= 2)
+    const uint64_t* carry;   // [B][K] sorted best keys of the items earlier stages scanned; nullptr in the first stage
+    uint32_t id_base;    // id of the first item of `codes` (a later stage scans a suffix of the catalogue)
 };
 
 // Items a thread holds per round.  M > 0: m is M and one 16-byte vector carries 16/M items; M == 0: any m, one item
@@ -643,9 +648,41 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     __syncthreads();
     PQ_MARK(1);
 
-    // ---- 2. first round: scores in registers, histogram over their range, cut
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
-    {
+
+    // one streamed round: score, and offer what reaches the wave's floor to its list
+    auto process = [&](const uint32_t (&w)[kWords], long long rr) {
+        float sc[kItems];
+        score_round<M>(a, lut, rr * round_units, tid, w, sc);
+        float best = sc[0];
+#pragma unroll
+        for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
+#ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
+        if (__ballot(best >= 1.0e30f) == 0) return;
+#endif
+        if (__ballot(best >= top.floor_ge) == 0) return;      // nothing in this round can matter
+        const bool inside = rr < inside_rounds;
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            const long long item = item_of_slot<M>(rr * round_units, tid, e);
+            const bool take = sc[e] >= top.floor_ge && (inside || item < a.N);
+            const uint64_t mask = __ballot(take);
+            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
+        }
+        if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
+    };
+
+    if (a.carry != nullptr) {
+        // ---- 2'. a later stage: the K-th best score of everything scanned before is a floor for the whole launch,
+        // so no histogram is needed and the first round is streamed like the others
+        const uint64_t kth = a.carry[(size_t)q * K + (K - 1)];
+        if (kth != 0ull) top.floor_ge = score_of_key(kth);
+        if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
+        process(wa, r);
+        if (r + 2 * nblk < rounds) load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wa);
+        r += nblk;
+    } else {
+        // ---- 2. first round: scores in registers, histogram over their range, cut
         float sc[kItems];
         score_round<M>(a, lut, r * round_units, tid, wa, sc);
         if (r + 2 * nblk < rounds)                             // wa is free again: third round on its way
@@ -674,34 +711,14 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
             const long long item = item_of_slot<M>(r * round_units, tid, e);
             const bool take = item < a.N && bk[e] >= bstar;
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
+            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
         r += nblk;
     }
     PQ_MARK(4);
 
-    // ---- 3. stream the remaining rounds against the wave's floor, one round of loads always in flight
-    auto process = [&](const uint32_t (&w)[kWords], long long rr) {
-        float sc[kItems];
-        score_round<M>(a, lut, rr * round_units, tid, w, sc);
-        float best = sc[0];
-#pragma unroll
-        for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
-#ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
-        if (__ballot(best >= 1.0e30f) == 0) return;
-#endif
-        if (__ballot(best >= top.floor_ge) == 0) return;      // nothing in this round can matter
-        const bool inside = rr < inside_rounds;
-#pragma unroll
-        for (int e = 0; e < kItems; ++e) {
-            const long long item = item_of_slot<M>(rr * round_units, tid, e);
-            const bool take = sc[e] >= top.floor_ge && (inside || item < a.N);
-            const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
-        }
-        if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
-    };
+    // ---- 3. stream the remaining rounds against the wave's floor, one round of loads always in flight:
     // here wb holds round r and wa round r + nblk (where they exist)
     while (r < rounds) {
         process(wb, r);
@@ -743,10 +760,13 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
 // two queries for one sub-id: random 8-byte gathers run close to the LDS peak (128 B/clk/CU) where 4-byte ones reach
 // half of it, and sub-id extraction, address arithmetic and the code loads are shared by the whole tile.
 // grid = (item blocks, ceil(B / kQ)).  Static LDS: the tile's tables.  Dynamic LDS:
-// hist[kQ][kTiledBins] | ctl[kQ] | state[kWaves][kQ] | lists[kQ][kWaves][cap] | cand[candmax] | sorted[K].
+// hist[kQ][kTiledBins] | ctl[kQ] | state[kWaves][kQ] | lists[kQ][kWaves][cap] | cand[candmax] | sorted[K] | best[kQ][K].
 constexpr int kQ = 4;                // queries per tile
 constexpr int kTileVecs = 2;         // 16-byte code vectors a thread holds per round
-constexpr int kTiledBins = kBins / kQ;   // buckets per query; the kQ histograms together serve as one kBins histogram
+constexpr int kTiledBins = kBins / kQ;
+#ifndef PQ_CHECKPOINT_FACTOR
+#define PQ_CHECKPOINT_FACTOR(K) ((K) > 28 ? 2 : 8)
+#endif   // buckets per query; the kQ histograms together serve as one kBins histogram
 
 // One (wave, query) candidate list's state.  It lives in LDS so that the streaming loop keeps none of it in registers.
 struct WaveQ {
@@ -755,10 +775,14 @@ struct WaveQ {
     float floor_ge;
 };
 
+// keys of room per query in the workgroup's best[] array (a checkpoint may keep a few more than K)
+__host__ __device__ inline int tiled_best_keys(int K) { return ((K > 128 ? K : 128) + 1) & ~1; }
+
 __host__ __device__ inline size_t tiled_lds_bytes(int cap, int candmax, int K) {
     return (size_t)kBins * sizeof(uint32_t) + (size_t)kQ * align16(sizeof(Ctl)) +
            (size_t)kWaves * kQ * sizeof(WaveQ) + (size_t)kQ * kWaves * cap * sizeof(uint64_t) +
-           (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
+           (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t)) +
+           (size_t)kQ * tiled_best_keys(K) * sizeof(uint64_t);
 }
 
 // Eq. 5 for the 16/M items of one code vector and the kQ queries of the tile; sc[q][e], sums left to right.
@@ -813,6 +837,185 @@ __device__ __noinline__ void offer_slow(WaveQ* st, uint64_t* buf, int cap, int K
     wave_sync();
 }
 
+// The batched kernel's dynamic LDS, carved.
+struct TileLds {
+    uint32_t* hist;
+    unsigned char* pctl;     // kQ control blocks
+    WaveQ* states;           // [kWaves][kQ]
+    uint64_t* lists;         // [kQ][kWaves][cap]
+    uint64_t* cand;          // candmax (>= kQ * kFastCand)
+    uint64_t* sorted;        // K
+    uint64_t* best;          // [kQ][kpad]: per query, a superset of the workgroup's K best so far (ctl->keep keys)
+    int kpad;
+};
+constexpr int kFastCand = 128;   // keys per query the cheap checkpoint paths handle (and best[] can hold)
+
+// Workgroup checkpoint of the batched kernel.  Per query it merges the waves' lists into best[q], empties the lists and
+// raises every wave's floor, so that the floors follow what the workgroup as a whole has scanned.  best[q] holds
+// ctl(q)->keep keys: a superset of the exact K best of everything scanned so far (exactly those, sorted, after a
+// `final` checkpoint).  Three paths, all exact in what they keep:
+//   - few keys everywhere: wave q ranks query q by counting, no workgroup barrier inside;
+//   - otherwise, while K leaves room in best[]: all queries at once, two waves each: a histogram over the keys' own
+//     score range gives a cut with at least K keys above it; those keys are kept and the cut becomes the floor;
+//   - a query that fits neither (or `final`): ranking / sorting by the whole workgroup, one query at a time.
+// Every thread of the workgroup calls it at the same round.  Out of line: the streaming loop stays small.
+__device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, int tid, bool final) {
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(L.pctl + (size_t)q * align16(sizeof(Ctl))); };
+    auto reset_lists = [&](int q, int wv, float floor_ge) {   // one thread per (query, wave)
+        WaveQ* st = L.states + wv * kQ + q;
+        st->cnt = 0;
+        st->thr = 0ull;
+        st->floor_ge = fmaxf(st->floor_ge, floor_ge);
+    };
+    __syncthreads();                                          // every wave's list state in LDS is final
+    int total[kQ], keep[kQ];
+    bool all_small = true;
+#pragma unroll
+    for (int q = 0; q < kQ; ++q) {
+        total[q] = 0;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) total[q] += L.states[wv * kQ + q].cnt;
+        keep[q] = ctl_of(q)->keep;
+        if (q < nq && total[q] + keep[q] > kFastCand) all_small = false;
+    }
+    bool exact_needed[kQ];
+#pragma unroll
+    for (int q = 0; q < kQ; ++q) exact_needed[q] = q < nq;
+
+    if (all_small) {
+        if (wave < nq) {
+            const int q = wave, T = total[q] + keep[q], T8 = (T + 7) & ~7;
+            uint64_t* c = L.cand + (size_t)q * kFastCand;
+            uint64_t* bq = L.best + (size_t)q * L.kpad;
+            int at = 0;
+            for (int wv = 0; wv < kWaves; ++wv) {
+                const int n = L.states[wv * kQ + q].cnt;
+                const uint64_t* src = L.lists + ((size_t)q * kWaves + wv) * cap;
+                for (int t = lane; t < n; t += kWave) c[at + t] = src[t];
+                at += n;
+            }
+            for (int t = lane; t < keep[q]; t += kWave) c[at + t] = bq[t];
+            for (int t = T + lane; t < T8; t += kWave) c[t] = 0ull;
+            wave_sync();
+            uint64_t mine[kFastCand / kWave];
+            int rank[kFastCand / kWave];
+#pragma unroll
+            for (int j = 0; j < kFastCand / kWave; ++j) {
+                mine[j] = (lane + j * kWave < T) ? c[lane + j * kWave] : 0ull;
+                rank[j] = 0;
+            }
+            for (int u = 0; u < T8; u += 8) {
+                const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(c + u);
+                const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(c + u + 2);
+                const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(c + u + 4);
+                const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(c + u + 6);
+#pragma unroll
+                for (int j = 0; j < kFastCand / kWave; ++j)
+                    rank[j] += (p0.x > mine[j]) + (p0.y > mine[j]) + (p1.x > mine[j]) + (p1.y > mine[j]) +
+                               (p2.x > mine[j]) + (p2.y > mine[j]) + (p3.x > mine[j]) + (p3.y > mine[j]);
+            }
+            for (int t = lane; t < K; t += kWave) bq[t] = 0ull;
+            wave_sync();
+#pragma unroll
+            for (int j = 0; j < kFastCand / kWave; ++j)
+                if (mine[j] != 0ull && rank[j] < K) bq[rank[j]] = mine[j];
+            wave_sync();
+            const uint64_t kth = bq[K - 1];
+            if (lane < kWaves) reset_lists(q, lane, kth != 0ull ? score_of_key(kth) : -__builtin_inff());
+            if (lane == 0) ctl_of(q)->keep = K;
+        }
+        __syncthreads();
+        return;
+    }
+
+    if (!final && K + 28 <= kFastCand) {
+        // all queries at once: waves 2q and 2q + 1 serve query q
+        const int q = wave >> 1, gt = tid & (2 * kWave - 1);
+        const bool active = q < nq;
+        Ctl* c = ctl_of(q);
+        uint32_t* h = L.hist + q * kTiledBins;
+        const uint64_t* bq = L.best + (size_t)q * L.kpad;
+        uint64_t* cq = L.cand + (size_t)q * kFastCand;
+        auto each_key = [&](auto&& f) {
+            for (int wv = 0; wv < kWaves; ++wv) {
+                const int n = L.states[wv * kQ + q].cnt;
+                const uint64_t* src = L.lists + ((size_t)q * kWaves + wv) * cap;
+                for (int t = gt; t < n; t += 2 * kWave) f(src[t]);
+            }
+            for (int t = gt; t < keep[q]; t += 2 * kWave) {
+                const uint64_t key = bq[t];
+                if (key != 0ull) f(key);
+            }
+        };
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        if (active) each_key([&](uint64_t key) { const float sc = score_of_key(key); mn = fminf(mn, sc); mx = fmaxf(mx, sc); });
+        wave_minmax(mn, mx);
+        if (lane == 0) { c->wave_min[wave] = mn; c->wave_max[wave] = mx; }
+        for (int i = gt; i < kTiledBins; i += 2 * kWave) h[i] = 0;
+        __syncthreads();
+        const float lo = fminf(c->wave_min[2 * q], c->wave_min[2 * q + 1]);
+        const float hi = fmaxf(c->wave_max[2 * q], c->wave_max[2 * q + 1]);
+        const float range = hi - lo;
+        float scale = (range > 0.0f) ? (float)kTiledBins / range : 0.0f;
+        if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
+        if (gt == 0) { c->lo = lo; c->scale = scale; c->ncand = 0; c->bstar = 0; c->cut = -__builtin_inff(); }
+        if (active) each_key([&](uint64_t key) { atomicAdd(&h[bucket_of<kTiledBins>(score_of_key(key), lo, scale)], 1u); });
+        __syncthreads();
+        if (active && (wave & 1) == 0) find_cut<kTiledBins>(h, K, c, lane);
+        __syncthreads();
+        const int bstar = c->bstar;
+        if (active)
+            each_key([&](uint64_t key) {
+                if (bucket_of<kTiledBins>(score_of_key(key), lo, scale) >= bstar) {
+                    const int pos = atomicAdd(&c->ncand, 1);
+                    if (pos < kFastCand) cq[pos] = key;
+                }
+            });
+        __syncthreads();
+        const int C = c->ncand;                               // kept keys: all those above the cut, at least min(K, all)
+        if (active && C <= kFastCand) {
+            uint64_t* bw = L.best + (size_t)q * L.kpad;
+            for (int t = gt; t < C; t += 2 * kWave) bw[t] = cq[t];
+            if (gt < kWaves) reset_lists(q, gt, next_up(c->cut));
+            if (gt == 0) c->keep = C;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int qq = 0; qq < kQ; ++qq) exact_needed[qq] = qq < nq && ctl_of(qq)->ncand > kFastCand;
+    }
+
+    for (int q = 0; q < nq; ++q) {
+        if (!exact_needed[q]) continue;
+        int before = 0;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv)
+            if (wv < wave) before += L.states[wv * kQ + q].cnt;
+        const int mine = L.states[wave * kQ + q].cnt;
+        uint64_t* qlists = L.lists + (size_t)q * kWaves * cap;
+        uint64_t* buf = qlists + (size_t)wave * cap;
+        uint64_t* bq = L.best + (size_t)q * L.kpad;
+        if (total[q] + keep[q] <= candmax) {                  // one ranking of lists and best together
+            for (int t = lane; t < mine; t += kWave) L.cand[before + t] = buf[t];
+            for (int t = tid; t < keep[q]; t += kThreads) L.cand[total[q] + t] = bq[t];
+            rank_select(L.cand, total[q] + keep[q], K, L.sorted, tid);
+        } else {                                              // lists first (histogram or sort), then with best
+            for (int t = mine + lane; t < cap; t += kWave) buf[t] = 0;
+            __syncthreads();
+            block_select(qlists, kWaves * cap, K, L.sorted, L.cand, candmax, L.hist, ctl_of(q), tid);
+            for (int t = tid; t < K; t += kThreads) L.cand[t] = L.sorted[t];
+            for (int t = tid; t < keep[q]; t += kThreads) L.cand[K + t] = bq[t];
+            __syncthreads();
+            rank_select(L.cand, K + keep[q], K, L.sorted, tid);
+        }
+        for (int t = tid; t < K; t += kThreads) bq[t] = L.sorted[t];
+        const uint64_t kth = L.sorted[K - 1];
+        if (tid < kWaves) reset_lists(q, tid, kth != 0ull ? score_of_key(kth) : -__builtin_inff());
+        if (tid == 0) ctl_of(q)->keep = K;
+        __syncthreads();                                      // sorted / cand are reused by the next query
+    }
+}
+
 template <int M>
 __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, int B) {
     constexpr int IPV = 16 / M, kItems = kTileVecs * IPV, kWords = kTileVecs * 4;
@@ -824,7 +1027,10 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     uint64_t* lists = reinterpret_cast<uint64_t*>(states + kWaves * kQ);
     uint64_t* cand = lists + (size_t)kQ * kWaves * a.cap;
     uint64_t* sorted = cand + a.candmax;
+    const int kpad = tiled_best_keys(a.K);
+    uint64_t* best = sorted + align16((size_t)a.K * sizeof(uint64_t)) / sizeof(uint64_t);   // [kQ][kpad]
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(pctl + (size_t)q * align16(sizeof(Ctl))); };
+    const TileLds tl{hist, pctl, states, lists, cand, sorted, best, kpad};
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q0 = blockIdx.y * kQ, nblk = gridDim.x, K = a.K, b = a.b;
@@ -892,12 +1098,37 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             }
         }
         for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
-        if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
+        for (int i = tid; i < kQ * kpad; i += kThreads) best[i] = 0;
+        if (tid < kQ) ctl_of(tid)->keep = 0;
+        if (lane < kQ) {
+            float floor0 = -__builtin_inff();                 // a later stage starts from the earlier stages' K-th best
+            if (a.carry != nullptr && lane < nq) {
+                const uint64_t kth = a.carry[(size_t)(q0 + lane) * K + (K - 1)];
+                if (kth != 0ull) floor0 = score_of_key(kth);
+            }
+            my_state[lane] = WaveQ{0ull, 0, floor0};
+        }
+        if (a.carry != nullptr && tid < kQ) {                 // no histogram in a later stage: exact selection sorts
+            Ctl* c = ctl_of(tid);
+            c->lo = 0.0f; c->scale = 0.0f; c->cut = -__builtin_inff(); c->bstar = 0; c->ncand = 0;
+        }
     }
     __syncthreads();
     PQ_MARK(1);
 
-    // one round's scores against the kQ lists of this wave
+    // One round's scores against the kQ lists of this wave.  The lists' lengths are cached in scalar registers
+    // (cnt[q]) while rounds stream: a survivor then costs one ballot-compacted LDS write and no LDS round trip.
+    // Anything else (a list that would overflow, or is due for tightening) goes through the out-of-line path, with
+    // the length synchronised through the list's state in LDS around the call.
+    int cnt[kQ];
+#pragma unroll
+    for (int q = 0; q < kQ; ++q) cnt[q] = 0;
+    auto publish_counts = [&]() {                             // before anything else reads the states
+        if (lane == 0) {
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) my_state[q].cnt = cnt[q];
+        }
+    };
     auto offer_round = [&](const float (&sc)[kQ][kItems], long long rr, const int* bk, const int* bstar) {
         const bool inside = rr < inside_rounds;
 #pragma unroll
@@ -909,21 +1140,50 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
             if (bk == nullptr && __ballot(best >= 1.0e30f) == 0) continue;
 #endif
-            if (__ballot(best >= my_state[q].floor_ge) == 0) continue;       // the usual case
-            Slots<kItems> s;
+            const float floor_ge = my_state[q].floor_ge;
+            if (__ballot(best >= floor_ge) == 0) continue;    // the usual case
+            uint64_t* const buf = list_of(q);
+            int stop = kItems;                                // first item the inline path had to leave
+            bool ok[kItems];
 #pragma unroll
             for (int e = 0; e < kItems; ++e) {
                 const long long item = item_of(rr, e);
-                s.sc[e] = sc[q][e];
-                s.id[e] = (uint32_t)item;
-                s.ok[e] = (inside || item < a.N) && (bk == nullptr || bk[q * kItems + e] >= bstar[q]);
+                ok[e] = (inside || item < a.N) && (bk == nullptr || bk[q * kItems + e] >= bstar[q]);
+                if (stop < kItems) continue;
+                const bool take = ok[e] && sc[q][e] >= floor_ge;
+                const uint64_t mask = __ballot(take);
+                if (mask == 0) continue;
+                const int n = __popcll(mask);
+                if (cnt[q] + n > a.cap) { stop = e; continue; }
+                const int pos = cnt[q] + __popcll(mask & ((1ull << lane) - 1ull));
+                if (take) buf[pos] = make_key(sc[q][e] + 0.0f, (uint32_t)item + a.id_base);
+                cnt[q] += n;
             }
-            offer_slow<kItems>(&my_state[q], list_of(q), a.cap, K, a.prune_at, s, lane);
+            if (stop < kItems || (a.prune_at != 0 && cnt[q] >= a.prune_at)) {
+                Slots<kItems> s;
+#pragma unroll
+                for (int e = 0; e < kItems; ++e) {
+                    s.sc[e] = sc[q][e];
+                    s.id[e] = (uint32_t)item_of(rr, e) + a.id_base;
+                    s.ok[e] = ok[e] && e >= stop;
+                }
+                if (lane == 0) my_state[q].cnt = cnt[q];
+                wave_sync();
+                offer_slow<kItems>(&my_state[q], buf, a.cap, K, a.prune_at, s, lane);
+                cnt[q] = __builtin_amdgcn_readfirstlane(my_state[q].cnt);
+            }
         }
     };
 
-    // ---- 2. first round: per query a histogram over its own score range gives that query's cut
-    {
+    if (a.carry != nullptr) {
+        // ---- 2'. a later stage streams its first round like the others
+        float sc[kQ][kItems];
+        score(wa, sc);
+        if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+        offer_round(sc, r, nullptr, nullptr);
+        r += nblk;
+    } else {
+        // ---- 2. first round: per query a histogram over its own score range gives that query's cut
         float sc[kQ][kItems];
         score(wa, sc);
         if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
@@ -970,51 +1230,45 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     }
     PQ_MARK(4);
 
-    // ---- 3. stream: wb holds round r, wa round r + nblk
+    // ---- 3. stream: wb holds round r, wa round r + nblk.  Segments of 2, 2 f, 2 f^2, ... rounds, a workgroup
+    // checkpoint between segments: the floors stay close to what the scanned part of the catalogue allows.
+    long long segment = 2;                                    // even, so that every segment starts with wb
     while (r < rounds) {
-        {
-            float sc[kQ][kItems];
-            score(wb, sc);
-            if (r + 2 * nblk < rounds) load(r + 2 * nblk, wb);
-            offer_round(sc, r, nullptr, nullptr);
+        long long left = segment;
+        while (r < rounds && left > 0) {
+            {
+                float sc[kQ][kItems];
+                score(wb, sc);
+                if (r + 2 * nblk < rounds) load(r + 2 * nblk, wb);
+                offer_round(sc, r, nullptr, nullptr);
+            }
+            r += nblk;
+            if (r >= rounds) break;
+            {
+                float sc[kQ][kItems];
+                score(wa, sc);
+                if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+                offer_round(sc, r, nullptr, nullptr);
+            }
+            r += nblk;
+            left -= 2;
         }
-        r += nblk;
-        if (r >= rounds) break;
-        {
-            float sc[kQ][kItems];
-            score(wa, sc);
-            if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
-            offer_round(sc, r, nullptr, nullptr);
+        if (r < rounds) {
+            publish_counts();
+            tile_checkpoint(tl, nq, K, a.cap, a.candmax, tid, false);
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) cnt[q] = 0;          // a checkpoint empties every list
+            segment *= a.checkpoint_factor;
         }
-        r += nblk;
     }
     PQ_MARK(5);
 
-    // ---- 4. per query: the waves' lists -> exact K best of this workgroup, sorted, to the workspace
-    __syncthreads();                                          // every wave's list state in LDS is final
-    for (int q = 0; q < nq; ++q) {
-        Ctl* c = ctl_of(q);
-        int total = 0, before = 0;
-#pragma unroll
-        for (int wv = 0; wv < kWaves; ++wv) {
-            const int n = states[wv * kQ + q].cnt;
-            if (wv < wave) before += n;
-            total += n;
-        }
-        const int mine = my_state[q].cnt;
-        uint64_t* buf = list_of(q);
-        if (total <= a.candmax) {
-            for (int t = lane; t < mine; t += kWave) cand[before + t] = buf[t];
-            rank_select(cand, total, K, sorted, tid);
-        } else {
-            for (int t = mine + lane; t < a.cap; t += kWave) buf[t] = 0;
-            if (tid == 0) { c->lo = ctl_of(q)->lo; }
-            __syncthreads();
-            block_select(lists + (size_t)q * kWaves * a.cap, kWaves * a.cap, K, sorted, cand, a.candmax, hist, c, tid);
-        }
-        uint64_t* mine_out = a.ws_keys + ((size_t)(q0 + q) * nblk + blockIdx.x) * K;
-        for (int t = tid; t < K; t += kThreads) mine_out[t] = sorted[t];
-        __syncthreads();                                      // sorted / cand are reused by the next query
+    // ---- 4. last checkpoint, then the workgroup's exact K best per query go to the workspace, sorted
+    publish_counts();
+    tile_checkpoint(tl, nq, K, a.cap, a.candmax, tid, true);
+    for (int i = tid; i < nq * K; i += kThreads) {
+        const int q = i / K, t = i % K;
+        a.ws_keys[((size_t)(q0 + q) * nblk + blockIdx.x) * K + t] = best[(size_t)q * kpad + t];
     }
     PQ_MARK(6);
 }
@@ -1023,9 +1277,11 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 // Dynamic LDS: hist | ctl | stage (stage_keys, a power of two >= 2K) | cand | sorted
 struct FoldArgs {
     const uint64_t* ws_keys;   // [B][nblk][K]
+    const uint64_t* carry_in;  // [B][K] best keys of earlier stages, folded in as one more list; nullptr: none
+    uint64_t* carry_out;       // [B][K] receives the sorted result as keys (may alias carry_in); nullptr: not wanted
     int nblk, K;
     int stage_keys, candmax;
-    int* out_ids;
+    int* out_ids;              // final stage only, else nullptr
     float* out_scores;
 };
 
@@ -1043,7 +1299,20 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     uint64_t* sorted = cand + a.candmax;
     const int tid = threadIdx.x, q = blockIdx.x, K = a.K;
     const uint64_t* all = a.ws_keys + (size_t)q * a.nblk * K;
-    const long long nkeys = (long long)a.nblk * K;
+    const long long nlist = (long long)a.nblk * K;
+    const long long nkeys = nlist + (a.carry_in ? K : 0);
+    const uint64_t* carry = a.carry_in ? a.carry_in + (size_t)q * K : nullptr;
+    auto key_at = [&](long long i) { return i < nlist ? all[i] : carry[i - nlist]; };
+    auto emit = [&](const uint64_t* sorted_keys) {            // every read of carry_in is done before this is called
+        for (int t = tid; t < K; t += kThreads) {
+            const uint64_t key = sorted_keys[t];
+            if (a.carry_out) a.carry_out[(size_t)q * K + t] = key;
+            if (a.out_ids) {
+                a.out_ids[(size_t)q * K + t] = id_of_key(key);
+                a.out_scores[(size_t)q * K + t] = score_of_key(key);
+            }
+        }
+    };
 
     // score range of all the keys (empty slots of short lists are 0); a modest number of keys stays in registers
     const int lane = tid & (kWave - 1);
@@ -1054,12 +1323,12 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
 #pragma unroll
         for (int r = 0; r < kFoldRegs; ++r) {
             const long long i = (long long)r * kThreads + tid;
-            keys[r] = (i < nkeys) ? all[i] : 0ull;
+            keys[r] = (i < nkeys) ? key_at(i) : 0ull;
             if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
     } else {
         for (long long i = tid; i < nkeys; i += kThreads) {
-            uint64_t key = all[i];
+            uint64_t key = key_at(i);
             if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
     }
@@ -1090,11 +1359,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
         const int C = ctl->ncand;
         if (C <= a.candmax) {
             rank_select(cand, C, K, sorted, tid);
-            for (int t = tid; t < K; t += kThreads) {
-                uint64_t key = sorted[t];
-                a.out_ids[(size_t)q * K + t] = id_of_key(key);
-                a.out_scores[(size_t)q * K + t] = score_of_key(key);
-            }
+            emit(sorted);
             return;
         }
         // too many keys share the cut bucket (heavy ties): take the staged, sorting path below
@@ -1105,7 +1370,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     while (done < nkeys) {
         long long take = nkeys - done;
         if (take > a.stage_keys - keep) take = a.stage_keys - keep;
-        for (int t = tid; t < a.stage_keys - keep; t += kThreads) stage[keep + t] = (t < take) ? all[done + t] : 0ull;
+        for (int t = tid; t < a.stage_keys - keep; t += kThreads) stage[keep + t] = (t < take) ? key_at(done + t) : 0ull;
         __syncthreads();
         block_select(stage, a.stage_keys, K, sorted, cand, a.candmax, hist, ctl, tid);
         done += take;
@@ -1115,11 +1380,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
             __syncthreads();
         }
     }
-    for (int t = tid; t < K; t += kThreads) {
-        uint64_t key = sorted[t];
-        a.out_ids[(size_t)q * K + t] = id_of_key(key);
-        a.out_scores[(size_t)q * K + t] = score_of_key(key);
-    }
+    emit(sorted);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -1195,7 +1456,7 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
 #define PQ_TILED_BLOCKS_PER_CU 1
 #endif
             long long want = ((long long)PQ_TILED_BLOCKS_PER_CU * kAssumedCUs) / tiles;
-            if (want < 8) want = 8;
+            if (want < 1) want = 1;                           // enough tiles to fill the machine: one workgroup each
             long long nb = t_rounds < want ? t_rounds : want;
             if (nb >= 8) nb &= ~7LL;                          // every tile's item block x lands on XCD x % 8
             if (nb < 1) nb = 1;
@@ -1206,9 +1467,65 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     return p;
 }
 
-size_t workspace_bytes(const ScanPlan& p, int B, int K) {
-    size_t bytes = (size_t)B * p.nblk * K * sizeof(uint64_t);
-    return (bytes + 255) & ~(size_t)255;
+// A call is cut into stages over consecutive item ranges.  Each stage is a scan launch plus a fold launch; the fold
+// leaves the best K keys of everything scanned so far in the workspace ("carry"), and the next stage's scan starts
+// from their K-th score as its floor instead of finding one by histogram.  With a floor that is already close to
+// final almost nothing reaches the candidate lists, which matters when a workgroup serves several queries or K is
+// large.  Small problems and single queries take one stage.
+constexpr int kMaxStages = 12;
+constexpr long long kStageAlign = 8192;            // items; a multiple of every kernel's round, and 16-byte aligned rows
+
+struct Stages {
+    int n;
+    long long begin[kMaxStages + 1];               // stage s scans items [begin[s], begin[s + 1])
+    ScanPlan plan[kMaxStages];
+    size_t lists_bytes;                            // per-workgroup lists: max over stages of B * nblk * K keys
+    size_t total_bytes;                            // lists + carry
+};
+
+Stages make_stages(long long N, int B, int m, int K) {
+    Stages st;
+    st.n = 1;
+    st.begin[0] = 0;
+#ifdef PQ_USE_STAGES
+    const long long kb = (long long)K * B;
+    long long rho = 1 + 100000 / kb;               // growth per stage: keeps a stage's expected survivors, K B (rho - 1), modest
+    if (rho < 2) rho = 2;
+    if (rho > 64) rho = 64;
+    long long first_min = (1LL << 20) / B;         // the first stage still has to fill the machine
+    if (first_min < 16384) first_min = 16384;
+    const ScanPlan whole = make_plan(N, B, m, K);
+    // (a workgroup that scans the whole catalogue for its queries tightens its own floors and needs no stages)
+    if (B >= 2 && whole.nblk > 1 && N * (long long)B >= (1LL << 24) && N >= 4 * first_min) {
+        int later = 0;                             // stages after the first: N / rho^later >= first_min
+        long long span = N;
+        while (later < kMaxStages - 1 && span / rho >= first_min) { span /= rho; ++later; }
+        if (later == 0) { later = 1; span = first_min; }
+        long long end = span;
+        for (int s = 0; s < later; ++s) {
+            long long e = (end + kStageAlign - 1) / kStageAlign * kStageAlign;
+            if (e <= st.begin[st.n - 1] || e >= N) break;
+            st.begin[st.n++] = e;
+            end *= rho;
+        }
+    }
+#endif
+    st.begin[st.n] = N;
+    st.lists_bytes = 0;
+    for (int s = 0; s < st.n; ++s) {
+        st.plan[s] = make_plan(st.begin[s + 1] - st.begin[s], B, m, K);
+        const size_t bytes = (size_t)B * st.plan[s].nblk * K * sizeof(uint64_t);
+        if (bytes > st.lists_bytes) st.lists_bytes = bytes;
+    }
+    st.lists_bytes = (st.lists_bytes + 255) & ~(size_t)255;
+    st.total_bytes = st.lists_bytes + (((size_t)B * K * sizeof(uint64_t) + 255) & ~(size_t)255);
+    return st;
+}
+
+bool stages_fit_lds(const Stages& st) {
+    for (int s = 0; s < st.n; ++s)
+        if (st.plan[s].scan_lds > kMaxLdsBytes || st.plan[s].fold_lds > kMaxLdsBytes) return false;
+    return true;
 }
 
 int check_topk_args(const void* codes, const void* S, long long N, int B, int m, int b, int K, const void* out_ids,
@@ -1216,12 +1533,12 @@ int check_topk_args(const void* codes, const void* S, long long N, int B, int m,
     if (!codes || !S || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return PQ_ERR_SHAPE;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
-    const ScanPlan p = make_plan(N, B, m, K);
-    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
+    const Stages st = make_stages(N, B, m, K);
+    if (!stages_fit_lds(st)) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)codes & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)S & 3) || ((uintptr_t)out_ids & 3) ||
         ((uintptr_t)out_scores & 3))
         return PQ_ERR_ALIGN;
-    if (workspace_bytes_given < workspace_bytes(p, B, K)) return PQ_ERR_WORKSPACE;
+    if (workspace_bytes_given < st.total_bytes) return PQ_ERR_WORKSPACE;
     return PQ_OK;
 }
 
@@ -1242,10 +1559,12 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
 
 // Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
 int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                 void* workspace, hipStream_t st) {
+                 void* workspace, const uint64_t* carry, uint32_t id_base, hipStream_t st) {
     ScanArgs a;
     a.phase_times = g_phase_times;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
+    a.carry = carry; a.id_base = id_base;
+    a.checkpoint_factor = PQ_CHECKPOINT_FACTOR(K);
     a.cap = p.cap; a.candmax = p.candmax;
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
     a.ws_keys = static_cast<uint64_t*>(workspace);
@@ -1272,16 +1591,41 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     return record_hip(e);
 }
 
-// Enqueue the fold of the workspace's lists into the outputs.
-int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
+// Enqueue the fold of the workspace's lists (and the carry of earlier stages) into the carry and / or the outputs.
+int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, const uint64_t* carry_in, uint64_t* carry_out,
+                 int* out_ids, float* out_scores, hipStream_t st) {
     FoldArgs f;
     f.ws_keys = static_cast<const uint64_t*>(workspace);
+    f.carry_in = carry_in; f.carry_out = carry_out;
     f.nblk = p.nblk; f.K = K; f.stage_keys = p.stage_keys; f.candmax = p.candmax;
     f.out_ids = out_ids; f.out_scores = out_scores;
     hipError_t e = allow_lds(fold_topk_kernel, p.fold_lds);
     if (e != hipSuccess) return record_hip(e);
     hipLaunchKernelGGL(fold_topk_kernel, dim3(B), dim3(kThreads), p.fold_lds, st, f);
     return record_hip(hipGetLastError());
+}
+
+// Enqueue every stage's scan and the folds between stages; the last stage's lists stay in the workspace for
+// enqueue_last_fold().
+int enqueue_scans(const Stages& sg, const uint8_t* codes, const float* S, int B, int m, int b, int K, void* workspace,
+                  hipStream_t st) {
+    uint64_t* carry = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + sg.lists_bytes);
+    for (int s = 0; s < sg.n; ++s) {
+        const long long begin = sg.begin[s], len = sg.begin[s + 1] - begin;
+        int rc = enqueue_scan(sg.plan[s], codes + (size_t)begin * m, S, len, B, m, b, K, workspace,
+                              s > 0 ? carry : nullptr, (uint32_t)begin, st);
+        if (rc != PQ_OK) return rc;
+        if (s + 1 < sg.n) {
+            rc = enqueue_fold(sg.plan[s], B, K, workspace, s > 0 ? carry : nullptr, carry, nullptr, nullptr, st);
+            if (rc != PQ_OK) return rc;
+        }
+    }
+    return PQ_OK;
+}
+
+int enqueue_last_fold(const Stages& sg, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
+    const uint64_t* carry = reinterpret_cast<const uint64_t*>(static_cast<unsigned char*>(workspace) + sg.lists_bytes);
+    return enqueue_fold(sg.plan[sg.n - 1], B, K, workspace, sg.n > 1 ? carry : nullptr, nullptr, out_ids, out_scores, st);
 }
 
 template <int S_ELEMS>
@@ -1318,20 +1662,25 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
 size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K) {
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return 0;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return 0;
-    const ScanPlan p = make_plan(N, B, m, K);
-    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
-    return workspace_bytes(p, B, K);
+    const Stages sg = make_stages(N, B, m, K);
+    if (!stages_fit_lds(sg)) return 0;
+#ifdef PQ_PLAN_DEBUG                                      // tuning builds only
+    for (int s = 0; s < sg.n; ++s)
+        fprintf(stderr, "stage %d: items [%lld, %lld) %s nblk %d\n", s, sg.begin[s], sg.begin[s + 1],
+                sg.plan[s].tiled ? "tiled" : "plain", sg.plan[s].nblk);
+#endif
+    return sg.total_bytes;
 }
 
 int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
                   float* out_scores, void* workspace, size_t workspace_bytes_given, void* stream) {
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
-    const ScanPlan p = make_plan(N, B, m, K);
+    const Stages sg = make_stages(N, B, m, K);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
+    rc = enqueue_scans(sg, codes, S, B, m, b, K, workspace, st);
     if (rc != PQ_OK) return rc;
-    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+    return enqueue_last_fold(sg, B, K, workspace, out_ids, out_scores, st);
 }
 
 int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
@@ -1341,18 +1690,18 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
     if (iters < 1) return PQ_ERR_SHAPE;
-    const ScanPlan p = make_plan(N, B, m, K);
+    const Stages sg = make_stages(N, B, m, K);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     hipError_t e = hipEventCreate(&ev0);
     if (e != hipSuccess) return record_hip(e);
     e = hipEventCreate(&ev1);
     if (e != hipSuccess) { (void)hipEventDestroy(ev0); return record_hip(e); }
-    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);           // untimed warm-up launch
+    rc = enqueue_scans(sg, codes, S, B, m, b, K, workspace, st);             // untimed warm-up pass
     if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev0, st));
-    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
+    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = enqueue_scans(sg, codes, S, B, m, b, K, workspace, st);
     if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev1, st));
-    if (rc == PQ_OK) rc = enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+    if (rc == PQ_OK) rc = enqueue_last_fold(sg, B, K, workspace, out_ids, out_scores, st);
     if (rc == PQ_OK) rc = record_hip(hipStreamSynchronize(st));
     float ms = 0.0f;
     if (rc == PQ_OK) rc = record_hip(hipEventElapsedTime(&ms, ev0, ev1));
