@@ -29,6 +29,14 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kThreads = 512;                     // scan workgroup: 8 waves
 constexpr int kWaves = kThreads / kWave;
+#ifndef PQ_BIG_THREADS
+#define PQ_BIG_THREADS 1024
+#endif
+#ifndef PQ_BIG_RING
+#define PQ_BIG_RING 2
+#endif
+constexpr int kBigThreads = PQ_BIG_THREADS;       // workgroup of the long single-query scan with replicated tables
+constexpr int kMaxWaves = kBigThreads / kWave;
 constexpr int kLutStride = 256;                   // table entries per split in LDS (a uint8 sub-id never runs past it)
 constexpr int kBins = 1024;                       // score buckets of the pruning histogram
 // 16-byte code vectors a thread holds per round: 4 for m >= 8, fewer for small m so a thread never holds > 16 items
@@ -45,6 +53,8 @@ constexpr int kAssumedCUs = 256;                  // MI355X; only used to size g
 #define PQ_BLOCKS_PER_CU 2
 #endif
 constexpr int kBlocksPerCU = PQ_BLOCKS_PER_CU;    // scan workgroups per CU over the whole grid
+constexpr int kTableCopies = 16;                  // copies of the score tables in the long single-query scan
+constexpr int kTableCopiesMinRounds = 8;          // rounds per workgroup from which the copies pay for themselves
 
 __device__ __forceinline__ uint32_t orderable_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -102,6 +112,22 @@ __device__ __forceinline__ void wave_minmax(float& mn, float& mx) {
     float x3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 48));
     mn = fminf(fminf(m0, m1), fminf(m2, m3));
     mx = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+}
+
+// A floor for a wave's top K (K in 1..64): a value that at least K of the lanes' values v reach, found by bisection
+// between the wave's extremes with one ballot per step (so close below the K-th largest, not exactly it).  Lanes
+// with nothing to offer pass -inf; if fewer than K lanes have a value the floor is -inf.  Same result in every lane.
+__device__ __forceinline__ float wave_floor_for_k(float v, int K) {
+    const float ninf = -__builtin_inff();
+    if (__popcll(__ballot(v > ninf)) < K) return ninf;
+    float lo = v > ninf ? v : __builtin_inff(), hi = v;
+    wave_minmax(lo, hi);                                      // at least K lanes reach lo
+#pragma unroll
+    for (int step = 0; step < 12; ++step) {
+        const float mid = lo + (hi - lo) * 0.5f;
+        if (__popcll(__ballot(v >= mid)) >= K) lo = mid; else hi = mid;
+    }
+    return lo;
 }
 
 // inclusive prefix sum over the lanes of the wave (lane i gets v[0] + .. + v[i])
@@ -190,9 +216,9 @@ struct Ctl {
     int bstar;           // bucket of the K-th best in the histogrammed set
     int ncand;           // candidates collected for an exact selection
     int keep;            // batched kernel: keys currently held in the workgroup's best[] array of this query
-    int wave_cnt[kWaves];
-    float wave_min[kWaves];
-    float wave_max[kWaves];
+    int wave_cnt[kMaxWaves];
+    float wave_min[kMaxWaves];
+    float wave_max[kMaxWaves];
 };
 
 template <int BINS = kBins>
@@ -205,6 +231,7 @@ __device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
 
 // Range of the scores held by the workgroup -> bucket mapping.  Every thread passes the min / max of its own valid
 // scores (+inf / -inf if it has none).  One barrier; lo / scale come back in registers and in ctl.
+template <int NW = kWaves>
 __device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid, float& lo_out, float& scale_out) {
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     wave_minmax(mn, mx);
@@ -212,7 +239,7 @@ __device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid,
     __syncthreads();
     float lo = ctl->wave_min[0], hi = ctl->wave_max[0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) { lo = fminf(lo, ctl->wave_min[w]); hi = fmaxf(hi, ctl->wave_max[w]); }
+    for (int w = 1; w < NW; ++w) { lo = fminf(lo, ctl->wave_min[w]); hi = fmaxf(hi, ctl->wave_max[w]); }
     float range = hi - lo;
     float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
     if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
@@ -352,12 +379,13 @@ struct WaveTopK {
 // Sorted exact K best of the C candidates in cand[] by counting: the position of a key is the number of candidates
 // that beat it.  cand must have room for C rounded up to a multiple of 8 (the pad is zeroed here; a zero beats
 // nothing).  dst[0..K) is zero-filled where fewer than K exist.
+template <int NT = kThreads>
 __device__ void rank_select(uint64_t* cand, int C, int K, uint64_t* dst, int tid) {
     const int C8 = (C + 7) & ~7;
-    for (int i = tid; i < K; i += kThreads) dst[i] = 0;
+    for (int i = tid; i < K; i += NT) dst[i] = 0;
     if (tid < C8 - C) cand[C + tid] = 0;
     __syncthreads();
-    for (int t = tid; t < C; t += kThreads) {
+    for (int t = tid; t < C; t += NT) {
         const uint64_t mine = cand[t];
         int rank = 0;
         for (int u = 0; u < C8; u += 8) {
@@ -374,17 +402,18 @@ __device__ void rank_select(uint64_t* cand, int C, int K, uint64_t* dst, int tid
 }
 
 // Exact selection of the K best among the nonzero keys of src[0..n) (LDS, zeros allowed anywhere), written sorted
-// to dst[0..K) (zero-filled if fewer than K exist).  All kThreads threads call it, ctl->lo / scale / ncand = 0 set.
+// to dst[0..K) (zero-filled if fewer than K exist).  All NT threads of the workgroup call it, ctl->lo / scale / ncand = 0 set.
 // `cand` holds candmax keys, `hist` kBins counters.  If the histogram cannot narrow the set to candmax keys (ties,
 // degenerate range), src is sorted in place instead, which needs n to be a power of two.
+template <int NT = kThreads>
 __device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_t* cand, int candmax, uint32_t* hist,
                              Ctl* ctl, int tid) {
     const int lane = tid & (kWave - 1);
-    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+    for (int i = tid; i < kBins; i += NT) hist[i] = 0;
     if (tid == 0) ctl->ncand = 0;
     __syncthreads();
     const float lo = ctl->lo, scale = ctl->scale;
-    for (int i = tid; i < n; i += kThreads) {
+    for (int i = tid; i < n; i += NT) {
         uint64_t key = src[i];
         if (key) atomicAdd(&hist[bucket_of(score_of_key(key), lo, scale)], 1u);
     }
@@ -392,7 +421,7 @@ __device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_
     if (tid < kWave) find_cut(hist, K, ctl, lane);
     __syncthreads();
     const int bstar = ctl->bstar;
-    for (int i = tid; i < n; i += kThreads) {
+    for (int i = tid; i < n; i += NT) {
         uint64_t key = src[i];
         if (key && bucket_of(score_of_key(key), lo, scale) >= bstar) {
             int pos = atomicAdd(&ctl->ncand, 1);
@@ -402,10 +431,10 @@ __device__ void block_select(uint64_t* src, int n, int K, uint64_t* dst, uint64_
     __syncthreads();
     const int C = ctl->ncand;
     if (C <= candmax) {
-        rank_select(cand, C, K, dst, tid);
+        rank_select<NT>(cand, C, K, dst, tid);
     } else {
-        bitonic_sort_desc<true>(src, n, tid, kThreads);
-        for (int i = tid; i < K; i += kThreads) dst[i] = src[i];
+        bitonic_sort_desc<true>(src, n, tid, NT);
+        for (int i = tid; i < K; i += NT) dst[i] = src[i];
         __syncthreads();
     }
 }
@@ -417,24 +446,24 @@ struct ScanLds {
     float* lut;
     uint32_t* hist;
     Ctl* ctl;
-    uint64_t* lists;     // kWaves * cap
+    uint64_t* lists;     // waves * cap
     uint64_t* cand;      // candmax
     uint64_t* sorted;    // K
 };
 
-__host__ __device__ inline size_t scan_lds_bytes(int m, int cap, int candmax, int K) {
-    return align16((size_t)m * kLutStride * sizeof(float)) + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)) +
-           (size_t)kWaves * cap * sizeof(uint64_t) + (size_t)candmax * sizeof(uint64_t) +
+__host__ __device__ inline size_t scan_lds_bytes(size_t lut_floats, int cap, int candmax, int K, int waves = kWaves) {
+    return align16(lut_floats * sizeof(float)) + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)) +
+           (size_t)waves * cap * sizeof(uint64_t) + (size_t)candmax * sizeof(uint64_t) +
            align16((size_t)K * sizeof(uint64_t));
 }
 
-__device__ inline ScanLds carve_scan(unsigned char* smem, int m, int cap, int candmax) {
+__device__ inline ScanLds carve_scan(unsigned char* smem, size_t lut_floats, int cap, int candmax, int waves = kWaves) {
     ScanLds L;
     size_t off = 0;
-    L.lut = reinterpret_cast<float*>(smem + off);        off += align16((size_t)m * kLutStride * sizeof(float));
+    L.lut = reinterpret_cast<float*>(smem + off);        off += align16(lut_floats * sizeof(float));
     L.hist = reinterpret_cast<uint32_t*>(smem + off);    off += kBins * sizeof(uint32_t);
     L.ctl = reinterpret_cast<Ctl*>(smem + off);          off += align16(sizeof(Ctl));
-    L.lists = reinterpret_cast<uint64_t*>(smem + off);   off += (size_t)kWaves * cap * sizeof(uint64_t);
+    L.lists = reinterpret_cast<uint64_t*>(smem + off);   off += (size_t)waves * cap * sizeof(uint64_t);
     L.cand = reinterpret_cast<uint64_t*>(smem + off);    off += (size_t)candmax * sizeof(uint64_t);
     L.sorted = reinterpret_cast<uint64_t*>(smem + off);
     return L;
@@ -480,7 +509,9 @@ struct Round {
 // Eq. 5 for the 16/M items packed in one 16-byte vector (words w[0..3], little-endian): all 16 table reads are
 // issued before any sum so they overlap in the LDS pipeline, then each item sums its m values left to right.
 // A sum of -0 is left as it is here; it is turned into +0 where a key is made.
-template <int M>
+// With C > 1 the tables are replicated: entry e of the table array has C copies at words e * C .. e * C + C - 1 and
+// `lut` already points at this lane's copy (lane % C), so lanes with different copies never share an LDS bank.
+template <int M, int C = 1>
 __device__ __forceinline__ void score_vector(const float* lut, const uint32_t* w, float* sc) {
     float v[16];
 #pragma unroll
@@ -492,7 +523,7 @@ __device__ __forceinline__ void score_vector(const float* lut, const uint32_t* w
 #ifdef PQ_DIAG_NOCONFLICT                             // tuning builds only: 32 consecutive words, no bank conflicts
         v[byte] = lut[(byte % M) * kLutStride + (code & 31u)];
 #else
-        v[byte] = lut[(byte % M) * kLutStride + code];
+        v[byte] = lut[((byte % M) * kLutStride + code) * C];
 #endif
 #endif
     }
@@ -552,68 +583,74 @@ __device__ __noinline__ uint4 load_vector_guarded(const uint8_t* codes, long lon
     return make_uint4(x[0], x[1], x[2], x[3]);
 }
 
-// The code vectors this thread owns in the round that starts at unit `unit_base` (vector kernels only).  A round
-// that lies wholly inside the catalogue takes the branch-free path, so its loads stay in flight together.
-template <int M>
-__device__ __forceinline__ void load_round(const ScanArgs& a, long long unit_base, bool inside, int tid,
+// Unit (code vector, or item in the generic kernel) that thread `tid` of workgroup `blk` owns in slot u of its
+// round rr: ((rr * kUnits + u) * nblk + blk) * NT + tid.  Slot u of one round of all workgroups together is one
+// contiguous stretch of the catalogue, so the grid sweeps memory front to back.
+template <int M, int NT>
+__device__ __forceinline__ long long unit_of(long long rr, int u, int nblk, int blk, int tid) {
+    return ((rr * Round<M>::kUnitsPerThread + u) * nblk + blk) * NT + tid;
+}
+
+// The code vectors this thread owns in round rr (vector kernels only).  Always the same number of plain 16-byte
+// loads, with the vector index clamped to `last_vec` (the last vector that lies wholly inside the catalogue): no
+// branch, so the compiler knows how many loads are outstanding at any point and lets several rounds stay in
+// flight.  A clamped vector's items are masked out by the caller.
+template <int M, int NT = kThreads>
+__device__ __forceinline__ void load_round(const ScanArgs& a, long long rr, int nblk, int blk, long long last_vec, int tid,
                                            uint32_t (&w)[Round<M>::kWords]) {
     if constexpr (M > 0) {
-        constexpr int kVecPerThread = Round<M>::kVecs;
-        if (inside) {
+        const uint4* base = reinterpret_cast<const uint4*>(a.codes);
+#pragma unroll
+        for (int u = 0; u < Round<M>::kVecs; ++u) {
 #ifdef PQ_DIAG_NOLOAD                                 // tuning builds only: always the first round's codes
-            const uint4* base = reinterpret_cast<const uint4*>(a.codes);
+            long long v = unit_of<M, NT>(0, u, nblk, blk, tid);
 #else
-            const uint4* base = reinterpret_cast<const uint4*>(a.codes) + unit_base;
+            long long v = unit_of<M, NT>(rr, u, nblk, blk, tid);
 #endif
-#pragma unroll
-            for (int u = 0; u < kVecPerThread; ++u) {
-                const uint4 x = base[u * kThreads + tid];
-                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kVecPerThread; ++u) {
-                const uint4 x = load_vector_guarded(a.codes, unit_base + (long long)u * kThreads + tid, a.N * M);
-                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
-            }
+            v = v < last_vec ? v : last_vec;
+            const uint4 x = base[v];
+            w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
         }
     }
 }
 
 // Scores of the items this thread owns in that round (slots past the catalogue's end get arbitrary finite values).
-template <int M>
-__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long unit_base, int tid,
+template <int M, int C = 1, int NT = kThreads>
+__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long rr, int nblk, int blk, int tid,
                                             const uint32_t (&w)[Round<M>::kWords], float (&sc)[Round<M>::kItems]) {
     if constexpr (M > 0) {
 #pragma unroll
-        for (int u = 0; u < Round<M>::kVecs; ++u) score_vector<M>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
+        for (int u = 0; u < Round<M>::kVecs; ++u) score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
     } else {
 #pragma unroll
         for (int u = 0; u < kGenericItemsPerThread; ++u) {
-            const long long item = unit_base + (long long)u * kThreads + tid;
+            const long long item = unit_of<M, NT>(rr, u, nblk, blk, tid);
             sc[u] = (item < a.N) ? score_row(lut, a.codes + item * a.m, a.m) : 0.0f;
         }
     }
 }
 
-// Id of the item in slot e of this thread's round (may be >= N in the catalogue's last round).
-template <int M>
-__device__ __forceinline__ long long item_of_slot(long long unit_base, int tid, int e) {
+// Id of the item in slot e of this thread's round (may lie past the scanned items in the last round).
+template <int M, int NT = kThreads>
+__device__ __forceinline__ long long item_of_slot(long long rr, int nblk, int blk, int tid, int e) {
     constexpr int IPV = Round<M>::kIPV;
-    return (unit_base + (long long)(e / IPV) * kThreads + tid) * IPV + (e % IPV);
+    return unit_of<M, NT>(rr, e / IPV, nblk, blk, tid) * IPV + (e % IPV);
 }
 
 // Catalogue scan: grid = (item blocks, B).  Leaves each workgroup's exact, sorted K best keys in the workspace.
 // LDS: the score tables are a static array when m is a template value (their address is then a compile-time
 // constant, which lets sub-id extraction and address arithmetic fold into one instruction per lookup); the rest is
 // dynamic: [tables if M == 0] | hist | ctl | wave lists | cand | sorted.
-template <int M>
-__global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
-    __shared__ __align__(16) float lut_static[M ? M * kLutStride : 4];
+// C > 1 (long single-query scans): C copies of the tables, in dynamic LDS, cut the bank conflicts of the lookups.
+template <int M, int C = 1, int NT = kThreads>
+__global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
+    constexpr int NW = NT / kWave;
+    static_assert(C == 1 || M > 0, "replicated tables need a compile-time m");
+    __shared__ __align__(16) float lut_static[(M && C == 1) ? M * kLutStride : 4];
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = M ? M : a.m;
-    const ScanLds L = carve_scan(smem, M ? 0 : m, a.cap, a.candmax);
-    float* const lut = M ? lut_static : L.lut;
+    const ScanLds L = carve_scan(smem, (M && C == 1) ? 0 : (size_t)m * kLutStride * C, a.cap, a.candmax, NW);
+    float* const lut_base = (M && C == 1) ? lut_static : L.lut;
     Ctl* ctl = L.ctl;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q = blockIdx.y, nblk = gridDim.x, K = a.K, b = a.b;
@@ -621,39 +658,69 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     constexpr int kUnits = Round<M>::kUnitsPerThread;
     constexpr int kWords = Round<M>::kWords;
 
-    const long long total_units = M ? (a.N * M + 15) / 16 : a.N;
-    const long long round_units = (long long)kThreads * kUnits;
-    const long long rounds = (total_units + round_units - 1) / round_units;   // nblk <= rounds: every workgroup has one
-    const long long inside_rounds = M ? (a.N * M / 16) / round_units : a.N / round_units;   // rounds with no ragged end
+    // Vector kernels scan the code vectors that lie wholly inside the catalogue; the fewer than 16 / M items after
+    // them (when N * M is not a multiple of 16) are scored one by one at the end.  The generic kernel scans items.
+    const long long total_units = M ? (a.N * M) / 16 : a.N;
+    const long long n_scan = M ? total_units * Round<M>::kIPV : a.N;          // items the rounds cover
+    const long long last_vec = total_units > 0 ? total_units - 1 : 0;
+    const long long round_units = (long long)NT * kUnits * nblk;              // units all workgroups take per round
+    const long long rounds = (total_units + round_units - 1) / round_units;   // every workgroup runs them all; 0 if N < 16 / M
+    const long long inside_rounds = total_units / round_units;                // rounds with no ragged end
 
     PQ_MARK(0);
-    // ---- 1. first two rounds' codes on their way, then the query's table into LDS
-    long long r = blockIdx.x;
-    uint32_t wa[kWords], wb[kWords];
+    // ---- 1. the first kRing rounds' codes on their way, then the query's table into LDS
+    constexpr int kRing = C > 1 ? PQ_BIG_RING : 2;            // rounds of codes in flight or in registers per thread
+    long long r = 0;
+    const int blk = blockIdx.x;
+    uint32_t w[kRing][kWords];
+    auto fetch = [&](long long rr, uint32_t (&buf)[kWords]) { load_round<M, NT>(a, rr, nblk, blk, last_vec, tid, buf); };
+    const bool has_rounds = rounds > 0;                       // false only when N < 16 / M: nothing but the tail items
+    auto fetch_first = [&]() {
+        if (has_rounds) fetch(r, w[0]);
+        if (r + 1 < rounds) {                                 // (with one round nothing is loaded twice)
+#pragma unroll
+            for (int i = 1; i < kRing; ++i) fetch(r + i, w[i]);
+        }
+    };
     const float* Sq = a.S + (size_t)q * m * b;
-    if (b == kLutStride && m * kLutStride == 4 * kThreads) {  // m = 8, b = 256: one 16-byte load per thread
+    if constexpr (C > 1) {
+        constexpr int kPer = (M * kLutStride + NT - 1) / NT;  // table entries per thread, requested before the codes
+        float tv[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = tid + i * NT, k = e / kLutStride, j = e % kLutStride;
+            tv[i] = (e < M * kLutStride && j < b) ? Sq[k * b + j] : 0.0f;
+        }
+        fetch_first();
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = tid + i * NT;
+            if (e < M * kLutStride) {
+                float4* dst = reinterpret_cast<float4*>(lut_base + (size_t)e * C);
+#pragma unroll
+                for (int c4 = 0; c4 < C / 4; ++c4) dst[c4] = make_float4(tv[i], tv[i], tv[i], tv[i]);
+            }
+        }
+    } else if (b == kLutStride && m * kLutStride == 4 * NT) {  // m = 8, b = 256: one 16-byte load per thread
         const float4 t4 = reinterpret_cast<const float4*>(Sq)[tid];
-        load_round<M>(a, r * round_units, r < inside_rounds, tid, wa);
-        if (r + nblk < rounds) load_round<M>(a, (r + nblk) * round_units, r + nblk < inside_rounds, tid, wb);
-        reinterpret_cast<float4*>(lut)[tid] = t4;
+        fetch_first();
+        reinterpret_cast<float4*>(lut_base)[tid] = t4;
     } else {
-        load_round<M>(a, r * round_units, r < inside_rounds, tid, wa);
-        if (r + nblk < rounds) load_round<M>(a, (r + nblk) * round_units, r + nblk < inside_rounds, tid, wb);
-        for (int e = tid; e < m * kLutStride; e += kThreads) {
+        fetch_first();
+        for (int e = tid; e < m * kLutStride; e += NT) {
             int k = e / kLutStride, j = e % kLutStride;
-            lut[e] = (j < b) ? Sq[k * b + j] : 0.0f;
+            lut_base[e] = (j < b) ? Sq[k * b + j] : 0.0f;
         }
     }
-    for (int i = tid; i < kBins; i += kThreads) L.hist[i] = 0;
+    for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
     __syncthreads();
     PQ_MARK(1);
+    const float* const lut = lut_base + (C > 1 ? lane % C : 0);   // this lane's copy
 
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
 
-    // one streamed round: score, and offer what reaches the wave's floor to its list
-    auto process = [&](const uint32_t (&w)[kWords], long long rr) {
-        float sc[kItems];
-        score_round<M>(a, lut, rr * round_units, tid, w, sc);
+    // what a round's scores offer to the wave's list: everything at or above its floor
+    auto offer = [&](const float (&sc)[kItems], long long rr) {
         float best = sc[0];
 #pragma unroll
         for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
@@ -664,41 +731,65 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
         const bool inside = rr < inside_rounds;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const long long item = item_of_slot<M>(rr * round_units, tid, e);
-            const bool take = sc[e] >= top.floor_ge && (inside || item < a.N);
+            const long long item = item_of_slot<M, NT>(rr, nblk, blk, tid, e);
+            const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
             if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
     };
+    // one streamed round
+    auto process = [&](const uint32_t (&w)[kWords], long long rr) {
+        float sc[kItems];
+        score_round<M, C, NT>(a, lut, rr, nblk, blk, tid, w, sc);
+        offer(sc, rr);
+    };
 
-    if (a.carry != nullptr) {
+    if (a.carry != nullptr || !has_rounds) {
         // ---- 2'. a later stage: the K-th best score of everything scanned before is a floor for the whole launch,
         // so no histogram is needed and the first round is streamed like the others
-        const uint64_t kth = a.carry[(size_t)q * K + (K - 1)];
-        if (kth != 0ull) top.floor_ge = score_of_key(kth);
+        if (a.carry != nullptr) {
+            const uint64_t kth = a.carry[(size_t)q * K + (K - 1)];
+            if (kth != 0ull) top.floor_ge = score_of_key(kth);
+        }
         if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
-        process(wa, r);
-        if (r + 2 * nblk < rounds) load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wa);
-        r += nblk;
-    } else {
-        // ---- 2. first round: scores in registers, histogram over their range, cut
+        if (has_rounds) {
+            process(w[0], r);
+            if (r + 1 < rounds) fetch(r + kRing, w[0]);
+            r += 1;
+        }
+    } else if (K <= kWave) {
+        // ---- 2a. first round, K <= 64: a floor that at least K of the lanes' best scores reach, so at least K of this
+        // wave's items do; it costs a dozen ballots and no workgroup barrier
+        if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
         float sc[kItems];
-        score_round<M>(a, lut, r * round_units, tid, wa, sc);
-        if (r + 2 * nblk < rounds)                             // wa is free again: third round on its way
-            load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wa);
+        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, w[0], sc);
+        if (r + 1 < rounds) fetch(r + kRing, w[0]);           // w[0] is free again
+        const bool inside = r < inside_rounds;
+        float best = -__builtin_inff();
+#pragma unroll
+        for (int e = 0; e < kItems; ++e)
+            if (inside || item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) best = fmaxf(best, sc[e]);
+        top.floor_ge = wave_floor_for_k(best, K);
+        offer(sc, r);
+        r += 1;
+    } else {
+        // ---- 2b. first round, larger K: scores in registers, histogram over their range, cut
+        float sc[kItems];
+        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, w[0], sc);
+        if (r + 1 < rounds) fetch(r + kRing, w[0]);           // w[0] is free again
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
-            if (item_of_slot<M>(r * round_units, tid, e) < a.N) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
+            if (item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
         float lo, scale;
-        set_range(mn, mx, ctl, tid, lo, scale);
+        set_range<NW>(mn, mx, ctl, tid, lo, scale);
         PQ_MARK(2);
         int bk[kItems];
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
             bk[e] = bucket_of(sc[e], lo, scale);
-            if (item_of_slot<M>(r * round_units, tid, e) < a.N) atomicAdd(&L.hist[bk[e]], 1u);
+            if (item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) atomicAdd(&L.hist[bk[e]], 1u);
         }
         __syncthreads();
         if (tid < kWave) find_cut(L.hist, K, ctl, lane);
@@ -708,26 +799,50 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
         top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const long long item = item_of_slot<M>(r * round_units, tid, e);
-            const bool take = item < a.N && bk[e] >= bstar;
+            const long long item = item_of_slot<M, NT>(r, nblk, blk, tid, e);
+            const bool take = item < n_scan && bk[e] >= bstar;
             const uint64_t mask = __ballot(take);
             if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
-        r += nblk;
+        r += 1;
     }
     PQ_MARK(4);
 
-    // ---- 3. stream the remaining rounds against the wave's floor, one round of loads always in flight:
-    // here wb holds round r and wa round r + nblk (where they exist)
-    while (r < rounds) {
-        process(wb, r);
-        if (r + 2 * nblk < rounds) load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wb);
-        r += nblk;
-        if (r >= rounds) break;
-        process(wa, r);
-        if (r + 2 * nblk < rounds) load_round<M>(a, (r + 2 * nblk) * round_units, r + 2 * nblk < inside_rounds, tid, wa);
-        r += nblk;
+    // ---- 3. stream the remaining rounds against the wave's floor, kRing - 1 rounds of loads always in flight:
+    // here w[i] holds round r + i - 1 for i = 1 .. kRing - 1 and w[0] round r + kRing - 1.  Loads past the last
+    // round are clamped re-reads of the last vector (their data is never used).
+    while (r + (kRing - 1) < rounds) {                        // kRing rounds at a time: no branch between their loads
+#pragma unroll
+        for (int i = 1; i <= kRing; ++i) {
+            process(w[i % kRing], r);
+            fetch(r + kRing, w[i % kRing]);
+            r += 1;
+        }
+    }
+#pragma unroll
+    for (int i = 1; i < kRing; ++i) {                         // the last rounds, fewer than kRing, already loaded
+        if (r < rounds) {
+            process(w[i], r);
+            r += 1;
+        }
+    }
+    if constexpr (M > 0) {
+        // the fewer than 16 / M items after the last whole code vector, one per lane of one wave
+        if (blockIdx.x == 0 && wave == 0) {
+            const long long item = n_scan + lane;
+            float sc = 0.0f;
+            bool take = false;
+            if (item < a.N) {
+                const uint8_t* row = a.codes + item * M;
+                sc = lut[(size_t)row[0] * C];
+#pragma unroll
+                for (int k = 1; k < M; ++k) sc = sc + lut[((size_t)k * kLutStride + row[k]) * C];
+                take = sc >= top.floor_ge;
+            }
+            const uint64_t mask = __ballot(take);
+            if (mask != 0) top.append(mask, take, sc, (uint32_t)item + a.id_base, lane);
+        }
     }
     PQ_MARK(5);
 
@@ -736,21 +851,21 @@ __global__ __launch_bounds__(kThreads) void scan_topk_kernel(ScanArgs a) {
     __syncthreads();
     int total = 0, before = 0;
 #pragma unroll
-    for (int wv = 0; wv < kWaves; ++wv) {
+    for (int wv = 0; wv < NW; ++wv) {
         int c = ctl->wave_cnt[wv];
         if (wv < wave) before += c;
         total += c;
     }
     if (total <= a.candmax) {
         for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
-        rank_select(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
+        rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
     } else {
         for (int t = top.cnt + lane; t < a.cap; t += kWave) top.buf[t] = 0;
         __syncthreads();
-        block_select(L.lists, kWaves * a.cap, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
+        block_select<NT>(L.lists, NW * a.cap, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
     }
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
-    for (int t = tid; t < K; t += kThreads) mine_out[t] = L.sorted[t];
+    for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
     PQ_MARK(6);
 }
 
@@ -1404,6 +1519,7 @@ int next_pow2(int x) {
 }
 
 struct ScanPlan {
+    int copies;      // single-query kernel: copies of the score tables in LDS (1 or kTableCopies)
     bool tiled;      // batched kernel: kQ queries per workgroup
     int nblk;        // item blocks per query
     int cap;         // keys per wave list
@@ -1420,7 +1536,7 @@ bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16; }
 ScanPlan make_plan(long long N, int B, int m, int K) {
     ScanPlan p;
     p.vec = is_vec_m(m);
-    const long long units = p.vec ? (N * m + 15) / 16 : N;
+    const long long units = p.vec ? (N * m) / 16 : N;          // whole code vectors (the few items after them are extra)
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
@@ -1435,8 +1551,26 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     if (p.candmax < 512) p.candmax = 512;
     p.stage_keys = next_pow2(2 * K);
     if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
-    p.scan_dyn_lds = scan_lds_bytes(p.vec ? 0 : m, p.cap, p.candmax, K);
-    p.scan_lds = p.scan_dyn_lds + (p.vec ? (size_t)m * kLutStride * sizeof(float) : 0);
+    p.copies = 1;
+#ifndef PQ_NO_TABLE_COPIES
+    // A long scan for few queries is bound by LDS bank conflicts of the random lookups: with kTableCopies copies of
+    // the tables, lanes l and l' collide only if l % kTableCopies == l' % kTableCopies.  Worth its LDS and fill time
+    // only when every workgroup streams many rounds; one workgroup per CU then (the tables take 128 KB at m = 8).
+    if (p.vec && m <= 8) {
+        long long nb = kAssumedCUs / B;                        // one workgroup (of kBigThreads) per CU over the whole grid
+        if (nb < 8) nb = 8;
+        const long long big_round = (long long)kBigThreads * vec_per_thread(m);
+        const long long big_rounds = (units + big_round - 1) / big_round;
+        const size_t dyn = scan_lds_bytes((size_t)m * kLutStride * kTableCopies, p.cap, p.candmax, K, kMaxWaves);
+        if (big_rounds >= kTableCopiesMinRounds * nb && dyn <= kMaxLdsBytes) {
+            p.copies = kTableCopies;
+            p.nblk = (int)nb;
+        }
+    }
+#endif
+    const size_t lut_dyn = p.copies > 1 ? (size_t)m * kLutStride * p.copies : (p.vec ? 0 : (size_t)m * kLutStride);
+    p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.copies > 1 ? kMaxWaves : kWaves);
+    p.scan_lds = p.scan_dyn_lds + ((p.vec && p.copies == 1) ? (size_t)m * kLutStride * sizeof(float) : 0);
     p.tiled = false;
 #ifdef PQ_NO_TILED                                        // tuning builds only
     if (false) {
@@ -1551,6 +1685,15 @@ hipError_t allow_lds(KernelT kernel, size_t bytes) {
 
 template <int M>
 hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    if constexpr (M >= 1 && M <= 8) {
+        if (p.copies == kTableCopies) {
+            hipError_t e = allow_lds(scan_topk_kernel<M, kTableCopies, kBigThreads>, p.scan_dyn_lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((scan_topk_kernel<M, kTableCopies, kBigThreads>), dim3(p.nblk, B), dim3(kBigThreads),
+                               p.scan_dyn_lds, st, a);
+            return hipGetLastError();
+        }
+    }
     hipError_t e = allow_lds(scan_topk_kernel<M>, p.scan_dyn_lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(scan_topk_kernel<M>, dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
