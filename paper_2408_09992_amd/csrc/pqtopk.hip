@@ -216,6 +216,7 @@ struct Ctl {
     int bstar;           // bucket of the K-th best in the histogrammed set
     int ncand;           // candidates collected for an exact selection
     int keep;            // batched kernel: keys currently held in the workgroup's best[] array of this query
+    int next_unit;       // single-query kernel: next unit of work to hand to a wave
     int wave_cnt[kMaxWaves];
     float wave_min[kMaxWaves];
     float wave_max[kMaxWaves];
@@ -375,6 +376,64 @@ struct WaveTopK {
         if (thr != 0ull) floor_ge = fmaxf(floor_ge, score_of_key(thr));
     }
 };
+
+constexpr int kFastCand = 128;   // keys one wave can rank on its own (two per lane)
+
+// One wave: sorted exact K best of the T <= MAXT keys in c[] (LDS; c has room for T rounded up to a multiple of 8,
+// zeros allowed anywhere and ignored), written to dst[0..K) (LDS, zero where fewer than K exist).  More than 64 keys
+// are first cut down to those that reach a floor at least K of them reach (about K keys, compacted in place); what
+// is left is ranked by counting: the position of a key is the number of keys that beat it.  No workgroup barrier;
+// every lane of the wave calls it.  wave_floor_for_k() must be declared above.
+template <int MAXT = kFastCand>
+__device__ __forceinline__ void wave_rank_select(uint64_t* c, int T, int K, uint64_t* dst, int lane) {
+    constexpr int PER = MAXT / kWave;
+    uint64_t mine[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) mine[j] = (lane + j * kWave < T) ? c[lane + j * kWave] : 0ull;
+    for (int t = lane; t < K; t += kWave) dst[t] = 0ull;
+    if (T > kWave && K <= kWave) {
+        float best = -__builtin_inff();
+#pragma unroll
+        for (int j = 0; j < PER; ++j)
+            if (mine[j] != 0ull) best = fmaxf(best, score_of_key(mine[j]));
+        const float floor_ge = wave_floor_for_k(best, K);
+        wave_sync();                                          // every lane holds its keys: c can be rewritten
+        int kept = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const bool take = mine[j] != 0ull && score_of_key(mine[j]) >= floor_ge;
+            const uint64_t mask = __ballot(take);
+            if (take) c[kept + __popcll(mask & ((1ull << lane) - 1ull))] = mine[j];
+            kept += __popcll(mask);
+        }
+        T = kept;
+        wave_sync();
+#pragma unroll
+        for (int j = 0; j < PER; ++j) mine[j] = (lane + j * kWave < T) ? c[lane + j * kWave] : 0ull;
+    }
+    const int T8 = (T + 7) & ~7;
+    wave_sync();                                              // (the pad below must not overtake the reads above)
+    for (int t = T + lane; t < T8; t += kWave) c[t] = 0ull;
+    wave_sync();
+    int rank[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) rank[j] = 0;
+    for (int u = 0; u < T8; u += 8) {
+        const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(c + u);
+        const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(c + u + 2);
+        const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(c + u + 4);
+        const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(c + u + 6);
+#pragma unroll
+        for (int j = 0; j < PER; ++j)
+            if (j * kWave < T)
+                rank[j] += (p0.x > mine[j]) + (p0.y > mine[j]) + (p1.x > mine[j]) + (p1.y > mine[j]) +
+                           (p2.x > mine[j]) + (p2.y > mine[j]) + (p3.x > mine[j]) + (p3.y > mine[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+        if (mine[j] != 0ull && rank[j] < K) dst[rank[j]] = mine[j];
+    wave_sync();
+}
 
 // Sorted exact K best of the C candidates in cand[] by counting: the position of a key is the number of candidates
 // that beat it.  cand must have room for C rounded up to a multiple of 8 (the pad is zeroed here; a zero beats
@@ -567,22 +626,6 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
     return acc;
 }
 
-// One 16-byte code vector with bounds checks: zeros past the end, byte loads for a ragged last vector.
-__device__ __noinline__ uint4 load_vector_guarded(const uint8_t* codes, long long v, long long total_bytes) {
-    uint32_t x[4] = {0u, 0u, 0u, 0u};
-    if ((v + 1) * 16 <= total_bytes) {
-        const uint4 y = reinterpret_cast<const uint4*>(codes)[v];
-        x[0] = y.x; x[1] = y.y; x[2] = y.z; x[3] = y.w;
-    } else {
-        for (int o = 0; o < 16 && v * 16 + o < total_bytes; ++o) {
-            const uint32_t byte = (uint32_t)codes[v * 16 + o] << ((o & 3) * 8);
-            if ((o >> 2) == 0) x[0] |= byte; else if ((o >> 2) == 1) x[1] |= byte;
-            else if ((o >> 2) == 2) x[2] |= byte; else x[3] |= byte;
-        }
-    }
-    return make_uint4(x[0], x[1], x[2], x[3]);
-}
-
 // Unit (code vector, or item in the generic kernel) that thread `tid` of workgroup `blk` owns in slot u of its
 // round rr: ((rr * kUnits + u) * nblk + blk) * NT + tid.  Slot u of one round of all workgroups together is one
 // contiguous stretch of the catalogue, so the grid sweeps memory front to back.
@@ -615,12 +658,22 @@ __device__ __forceinline__ void load_round(const ScanArgs& a, long long rr, int 
 }
 
 // Scores of the items this thread owns in that round (slots past the catalogue's end get arbitrary finite values).
+// `inside`: the round lies wholly inside the scanned units (n_units of them); otherwise vectors past the end are not
+// looked up at all (a wave whose lanes are all past the end skips the vector's table reads).
 template <int M, int C = 1, int NT = kThreads>
 __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long rr, int nblk, int blk, int tid,
-                                            const uint32_t (&w)[Round<M>::kWords], float (&sc)[Round<M>::kItems]) {
+                                            bool inside, long long n_units, const uint32_t (&w)[Round<M>::kWords],
+                                            float (&sc)[Round<M>::kItems]) {
     if constexpr (M > 0) {
 #pragma unroll
-        for (int u = 0; u < Round<M>::kVecs; ++u) score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
+        for (int u = 0; u < Round<M>::kVecs; ++u) {
+            if (inside || unit_of<M, NT>(rr, u, nblk, blk, tid) < n_units) {
+                score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < Round<M>::kIPV; ++e) sc[u * Round<M>::kIPV + e] = 0.0f;
+            }
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < kGenericItemsPerThread; ++u) {
@@ -664,7 +717,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     const long long n_scan = M ? total_units * Round<M>::kIPV : a.N;          // items the rounds cover
     const long long last_vec = total_units > 0 ? total_units - 1 : 0;
     const long long round_units = (long long)NT * kUnits * nblk;              // units all workgroups take per round
-    const long long rounds = (total_units + round_units - 1) / round_units;   // every workgroup runs them all; 0 if N < 16 / M
+    const long long rounds = (total_units + round_units - 1) / round_units;   // every workgroup runs them all
     const long long inside_rounds = total_units / round_units;                // rounds with no ragged end
 
     PQ_MARK(0);
@@ -673,33 +726,30 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     long long r = 0;
     const int blk = blockIdx.x;
     uint32_t w[kRing][kWords];
-    auto fetch = [&](long long rr, uint32_t (&buf)[kWords]) { load_round<M, NT>(a, rr, nblk, blk, last_vec, tid, buf); };
-    const bool has_rounds = rounds > 0;                       // false only when N < 16 / M: nothing but the tail items
-    auto fetch_first = [&]() {
-        if (has_rounds) fetch(r, w[0]);
-        if (r + 1 < rounds) {                                 // (with one round nothing is loaded twice)
-#pragma unroll
-            for (int i = 1; i < kRing; ++i) fetch(r + i, w[i]);
-        }
+    // (vt: the thread index whose share of round rr is meant; a wave may take over another wave's share)
+    auto fetch = [&](long long rr, int vt, uint32_t (&buf)[kWords]) { load_round<M, NT>(a, rr, nblk, blk, last_vec, vt, buf); };
+    // (the host sends catalogues with no whole code vector, N * M < 16, to the generic kernel: rounds >= 1 here)
+    auto fetch_first = [&]() {                                // no branch: the loads can be counted, so what follows
+#pragma unroll                                                // waits for exactly what it needs
+        for (int i = 0; i < kRing; ++i) fetch(r + i, tid, w[i]);
     };
     const float* Sq = a.S + (size_t)q * m * b;
     if constexpr (C > 1) {
-        constexpr int kPer = (M * kLutStride + NT - 1) / NT;  // table entries per thread, requested before the codes
+        // thread t writes the 16-byte pieces t, t + NT, ... of the replicated tables (piece p is a quarter of the C
+        // copies of entry p / (C / 4)): consecutive lanes write consecutive LDS addresses.  Values requested first.
+        constexpr int kPieces = M * kLutStride * (C / 4);
+        constexpr int kPer = (kPieces + NT - 1) / NT;
         float tv[kPer];
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int e = tid + i * NT, k = e / kLutStride, j = e % kLutStride;
+            const int e = (tid + i * NT) / (C / 4), k = e / kLutStride, j = e % kLutStride;
             tv[i] = (e < M * kLutStride && j < b) ? Sq[k * b + j] : 0.0f;
         }
         fetch_first();
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int e = tid + i * NT;
-            if (e < M * kLutStride) {
-                float4* dst = reinterpret_cast<float4*>(lut_base + (size_t)e * C);
-#pragma unroll
-                for (int c4 = 0; c4 < C / 4; ++c4) dst[c4] = make_float4(tv[i], tv[i], tv[i], tv[i]);
-            }
+            const int piece = tid + i * NT;
+            if (piece < kPieces) reinterpret_cast<float4*>(lut_base)[piece] = make_float4(tv[i], tv[i], tv[i], tv[i]);
         }
     } else if (b == kLutStride && m * kLutStride == 4 * NT) {  // m = 8, b = 256: one 16-byte load per thread
         const float4 t4 = reinterpret_cast<const float4*>(Sq)[tid];
@@ -713,6 +763,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         }
     }
     for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
+    if (tid == 0) ctl->next_unit = kRing * NW;
     __syncthreads();
     PQ_MARK(1);
     const float* const lut = lut_base + (C > 1 ? lane % C : 0);   // this lane's copy
@@ -720,7 +771,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
 
     // what a round's scores offer to the wave's list: everything at or above its floor
-    auto offer = [&](const float (&sc)[kItems], long long rr) {
+    auto offer = [&](const float (&sc)[kItems], long long rr, int vt) {
         float best = sc[0];
 #pragma unroll
         for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
@@ -731,7 +782,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         const bool inside = rr < inside_rounds;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const long long item = item_of_slot<M, NT>(rr, nblk, blk, tid, e);
+            const long long item = item_of_slot<M, NT>(rr, nblk, blk, vt, e);
             const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
             if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
@@ -739,45 +790,40 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
     };
     // one streamed round
-    auto process = [&](const uint32_t (&w)[kWords], long long rr) {
+    auto process = [&](const uint32_t (&w)[kWords], long long rr, int vt) {
         float sc[kItems];
-        score_round<M, C, NT>(a, lut, rr, nblk, blk, tid, w, sc);
-        offer(sc, rr);
+        score_round<M, C, NT>(a, lut, rr, nblk, blk, vt, rr < inside_rounds, total_units, w, sc);
+        offer(sc, rr, vt);
     };
 
-    if (a.carry != nullptr || !has_rounds) {
+    if (a.carry != nullptr) {
         // ---- 2'. a later stage: the K-th best score of everything scanned before is a floor for the whole launch,
         // so no histogram is needed and the first round is streamed like the others
-        if (a.carry != nullptr) {
-            const uint64_t kth = a.carry[(size_t)q * K + (K - 1)];
-            if (kth != 0ull) top.floor_ge = score_of_key(kth);
-        }
+        const uint64_t kth = a.carry[(size_t)q * K + (K - 1)];
+        if (kth != 0ull) top.floor_ge = score_of_key(kth);
         if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
-        if (has_rounds) {
-            process(w[0], r);
-            if (r + 1 < rounds) fetch(r + kRing, w[0]);
-            r += 1;
-        }
+        process(w[0], r, tid);
+        r += 1;
     } else if (K <= kWave) {
         // ---- 2a. first round, K <= 64: a floor that at least K of the lanes' best scores reach, so at least K of this
         // wave's items do; it costs a dozen ballots and no workgroup barrier
         if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
         float sc[kItems];
-        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, w[0], sc);
-        if (r + 1 < rounds) fetch(r + kRing, w[0]);           // w[0] is free again
+        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
         const bool inside = r < inside_rounds;
         float best = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
             if (inside || item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) best = fmaxf(best, sc[e]);
+        PQ_MARK(2);
         top.floor_ge = wave_floor_for_k(best, K);
-        offer(sc, r);
+        PQ_MARK(3);
+        offer(sc, r, tid);
         r += 1;
     } else {
         // ---- 2b. first round, larger K: scores in registers, histogram over their range, cut
         float sc[kItems];
-        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, w[0], sc);
-        if (r + 1 < rounds) fetch(r + kRing, w[0]);           // w[0] is free again
+        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
@@ -809,22 +855,34 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     }
     PQ_MARK(4);
 
-    // ---- 3. stream the remaining rounds against the wave's floor, kRing - 1 rounds of loads always in flight:
-    // here w[i] holds round r + i - 1 for i = 1 .. kRing - 1 and w[0] round r + kRing - 1.  Loads past the last
-    // round are clamped re-reads of the last vector (their data is never used).
-    while (r + (kRing - 1) < rounds) {                        // kRing rounds at a time: no branch between their loads
+    // ---- 3. stream the remaining rounds against the wave's floor.  Work is handed out in units of one wave's share
+    // of a round: unit j is the share of wave j % NW in round j / NW.  A wave's first kRing units are its own share
+    // of the first kRing rounds (already loaded or on their way); after that it takes the next free unit from a
+    // counter in LDS, so a wave that falls behind (LDS arbitration, candidate handling) does not hold the workgroup
+    // up at the end.  The counter's atomic is issued one step before its result is used, and a unit's loads are
+    // unconditional (past the last unit they are clamped re-reads whose data is never used): no wait in the loop
+    // is longer than it has to be.
+    if (rounds > 1) {
+        const long long units = rounds * NW;
+        int pending = 0;                                      // lane 0: result of the last counter request
+        auto request_unit = [&]() { if (lane == 0) pending = atomicAdd(&ctl->next_unit, 1); };
+        auto requested_unit = [&]() -> long long { return (long long)__builtin_amdgcn_readfirstlane(pending); };
+        long long unit[kRing];                                // unit held by w[i]
 #pragma unroll
-        for (int i = 1; i <= kRing; ++i) {
-            process(w[i % kRing], r);
-            fetch(r + kRing, w[i % kRing]);
-            r += 1;
-        }
-    }
+        for (int i = 1; i < kRing; ++i) unit[i] = (long long)i * NW + wave;
+        request_unit();
+        unit[0] = requested_unit();
+        request_unit();
+        fetch(unit[0] / NW, (int)(unit[0] % NW) * kWave + lane, w[0]);
+        while (unit[1 % kRing] < units) {                     // the oldest unit held; a younger one past the end scores nothing
 #pragma unroll
-    for (int i = 1; i < kRing; ++i) {                         // the last rounds, fewer than kRing, already loaded
-        if (r < rounds) {
-            process(w[i], r);
-            r += 1;
+            for (int i = 1; i <= kRing; ++i) {
+                const int s = i % kRing;
+                process(w[s], unit[s] / NW, (int)(unit[s] % NW) * kWave + lane);
+                unit[s] = requested_unit();
+                request_unit();
+                fetch(unit[s] / NW, (int)(unit[s] % NW) * kWave + lane, w[s]);
+            }
         }
     }
     if constexpr (M > 0) {
@@ -856,6 +914,23 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         if (wv < wave) before += c;
         total += c;
     }
+    uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
+    if (total <= kFastCand) {                                 // the usual case: wave 0 ranks them alone and stores
+        if (wave == 0) {
+            int at = 0;
+            for (int wv = 0; wv < NW; ++wv) {
+                const int n = ctl->wave_cnt[wv];
+                const uint64_t* src = L.lists + (size_t)wv * a.cap;
+                for (int t = lane; t < n; t += kWave) L.cand[at + t] = src[t];
+                at += n;
+            }
+            wave_sync();
+            wave_rank_select(L.cand, total, K, L.sorted, lane);
+            for (int t = lane; t < K; t += kWave) mine_out[t] = L.sorted[t];
+        }
+        PQ_MARK(6);
+        return;
+    }
     if (total <= a.candmax) {
         for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
         rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
@@ -864,7 +939,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         __syncthreads();
         block_select<NT>(L.lists, NW * a.cap, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
     }
-    uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
     for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
     PQ_MARK(6);
 }
@@ -963,7 +1037,6 @@ struct TileLds {
     uint64_t* best;          // [kQ][kpad]: per query, a superset of the workgroup's K best so far (ctl->keep keys)
     int kpad;
 };
-constexpr int kFastCand = 128;   // keys per query the cheap checkpoint paths handle (and best[] can hold)
 
 // Workgroup checkpoint of the batched kernel.  Per query it merges the waves' lists into best[q], empties the lists and
 // raises every wave's floor, so that the floors follow what the workgroup as a whole has scanned.  best[q] holds
@@ -1000,7 +1073,7 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
 
     if (all_small) {
         if (wave < nq) {
-            const int q = wave, T = total[q] + keep[q], T8 = (T + 7) & ~7;
+            const int q = wave, T = total[q] + keep[q];
             uint64_t* c = L.cand + (size_t)q * kFastCand;
             uint64_t* bq = L.best + (size_t)q * L.kpad;
             int at = 0;
@@ -1011,31 +1084,8 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
                 at += n;
             }
             for (int t = lane; t < keep[q]; t += kWave) c[at + t] = bq[t];
-            for (int t = T + lane; t < T8; t += kWave) c[t] = 0ull;
             wave_sync();
-            uint64_t mine[kFastCand / kWave];
-            int rank[kFastCand / kWave];
-#pragma unroll
-            for (int j = 0; j < kFastCand / kWave; ++j) {
-                mine[j] = (lane + j * kWave < T) ? c[lane + j * kWave] : 0ull;
-                rank[j] = 0;
-            }
-            for (int u = 0; u < T8; u += 8) {
-                const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(c + u);
-                const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(c + u + 2);
-                const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(c + u + 4);
-                const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(c + u + 6);
-#pragma unroll
-                for (int j = 0; j < kFastCand / kWave; ++j)
-                    rank[j] += (p0.x > mine[j]) + (p0.y > mine[j]) + (p1.x > mine[j]) + (p1.y > mine[j]) +
-                               (p2.x > mine[j]) + (p2.y > mine[j]) + (p3.x > mine[j]) + (p3.y > mine[j]);
-            }
-            for (int t = lane; t < K; t += kWave) bq[t] = 0ull;
-            wave_sync();
-#pragma unroll
-            for (int j = 0; j < kFastCand / kWave; ++j)
-                if (mine[j] != 0ull && rank[j] < K) bq[rank[j]] = mine[j];
-            wave_sync();
+            wave_rank_select(c, T, K, bq, lane);
             const uint64_t kth = bq[K - 1];
             if (lane < kWaves) reset_lists(q, lane, kth != 0ull ? score_of_key(kth) : -__builtin_inff());
             if (lane == 0) ctl_of(q)->keep = K;
@@ -1150,28 +1200,27 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q0 = blockIdx.y * kQ, nblk = gridDim.x, K = a.K, b = a.b;
     const int nq = (B - q0 < kQ) ? B - q0 : kQ;               // queries of this tile that exist
-    const long long total_units = (a.N * M + 15) / 16;
+    // The rounds cover the code vectors that lie wholly inside the catalogue (at least one: the host sends smaller
+    // catalogues elsewhere); the fewer than 16 / M items after them are scored one by one at the end.
+    const long long total_units = (a.N * M) / 16;
+    const long long n_scan = total_units * IPV;
+    const long long last_vec = total_units - 1;
     const long long round_units = (long long)kThreads * kTileVecs;
     const long long rounds = (total_units + round_units - 1) / round_units;
-    const long long inside_rounds = (a.N * M / 16) / round_units;
+    const long long inside_rounds = total_units / round_units;
     WaveQ* const my_state = states + wave * kQ;
     auto list_of = [&](int q) { return lists + ((size_t)q * kWaves + wave) * a.cap; };
 
+    // a round's code vectors: always kTileVecs plain 16-byte loads, the index clamped to the last whole vector (no
+    // branch, so the loads can be counted and a second round stays in flight); clamped items are masked out later
     auto load = [&](long long rr, uint32_t (&w)[kWords]) {
-        const long long unit_base = rr * round_units;
-        if (rr < inside_rounds) {
-            const uint4* base = reinterpret_cast<const uint4*>(a.codes) + unit_base;
+        const uint4* base = reinterpret_cast<const uint4*>(a.codes);
 #pragma unroll
-            for (int u = 0; u < kTileVecs; ++u) {
-                const uint4 x = base[u * kThreads + tid];
-                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kTileVecs; ++u) {
-                const uint4 x = load_vector_guarded(a.codes, unit_base + (long long)u * kThreads + tid, a.N * M);
-                w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
-            }
+        for (int u = 0; u < kTileVecs; ++u) {
+            long long v = rr * round_units + (long long)u * kThreads + tid;
+            v = v < last_vec ? v : last_vec;
+            const uint4 x = base[v];
+            w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
         }
     };
     auto item_of = [&](long long rr, int e) {
@@ -1194,7 +1243,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     long long r = blockIdx.x;
     uint32_t wa[kWords], wb[kWords];
     load(r, wa);
-    if (r + nblk < rounds) load(r + nblk, wb);
+    load(r + nblk, wb);
     {
         float* lutf = reinterpret_cast<float*>(lut2);
         if (b == kLutStride) {                                // whole rows: 16-byte loads, four sub-ids at a time
@@ -1263,7 +1312,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
             for (int e = 0; e < kItems; ++e) {
                 const long long item = item_of(rr, e);
-                ok[e] = (inside || item < a.N) && (bk == nullptr || bk[q * kItems + e] >= bstar[q]);
+                ok[e] = (inside || item < n_scan) && (bk == nullptr || bk[q * kItems + e] >= bstar[q]);
                 if (stop < kItems) continue;
                 const bool take = ok[e] && sc[q][e] >= floor_ge;
                 const uint64_t mask = __ballot(take);
@@ -1294,20 +1343,20 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         // ---- 2'. a later stage streams its first round like the others
         float sc[kQ][kItems];
         score(wa, sc);
-        if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+        load(r + 2 * nblk, wa);
         offer_round(sc, r, nullptr, nullptr);
         r += nblk;
     } else {
         // ---- 2. first round: per query a histogram over its own score range gives that query's cut
         float sc[kQ][kItems];
         score(wa, sc);
-        if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+        load(r + 2 * nblk, wa);
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
             for (int e = 0; e < kItems; ++e)
-                if (item_of(r, e) < a.N) { mn = fminf(mn, sc[q][e]); mx = fmaxf(mx, sc[q][e]); }
+                if (item_of(r, e) < n_scan) { mn = fminf(mn, sc[q][e]); mx = fmaxf(mx, sc[q][e]); }
             wave_minmax(mn, mx);
             if (lane == 0) { ctl_of(q)->wave_min[wave] = mn; ctl_of(q)->wave_max[wave] = mx; }
         }
@@ -1326,7 +1375,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
             for (int e = 0; e < kItems; ++e) {
                 bk[q * kItems + e] = bucket_of<kTiledBins>(sc[q][e], lo, scale);
-                if (q < nq && item_of(r, e) < a.N) atomicAdd(&hist[q * kTiledBins + bk[q * kItems + e]], 1u);
+                if (q < nq && item_of(r, e) < n_scan) atomicAdd(&hist[q * kTiledBins + bk[q * kItems + e]], 1u);
             }
         }
         __syncthreads();
@@ -1350,23 +1399,28 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     long long segment = 2;                                    // even, so that every segment starts with wb
     while (r < rounds) {
         long long left = segment;
-        while (r < rounds && left > 0) {
+        while (left > 0 && r + nblk < rounds) {               // two rounds at a time, no branch between their loads
             {
                 float sc[kQ][kItems];
                 score(wb, sc);
-                if (r + 2 * nblk < rounds) load(r + 2 * nblk, wb);
+                load(r + 2 * nblk, wb);
                 offer_round(sc, r, nullptr, nullptr);
             }
             r += nblk;
-            if (r >= rounds) break;
             {
                 float sc[kQ][kItems];
                 score(wa, sc);
-                if (r + 2 * nblk < rounds) load(r + 2 * nblk, wa);
+                load(r + 2 * nblk, wa);
                 offer_round(sc, r, nullptr, nullptr);
             }
             r += nblk;
             left -= 2;
+        }
+        if (left > 0 && r < rounds) {                         // a last single round
+            float sc[kQ][kItems];
+            score(wb, sc);
+            offer_round(sc, r, nullptr, nullptr);
+            r += nblk;
         }
         if (r < rounds) {
             publish_counts();
@@ -1374,6 +1428,39 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
             for (int q = 0; q < kQ; ++q) cnt[q] = 0;          // a checkpoint empties every list
             segment *= a.checkpoint_factor;
+        }
+    }
+    // the fewer than 16 / M items after the last whole code vector: one per lane of one wave, per query
+    if (blockIdx.x == 0 && wave == 0 && n_scan < a.N) {
+        const long long item = n_scan + lane;
+        float tsc[kQ];
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) tsc[q] = 0.0f;
+        if (item < a.N) {
+            const uint8_t* row = a.codes + item * M;
+#pragma unroll
+            for (int p = 0; p < kQ / 2; ++p) {
+                float2 acc = lut2[(p * M) * kLutStride + row[0]];
+#pragma unroll
+                for (int k = 1; k < M; ++k) {
+                    const float2 v = lut2[(p * M + k) * kLutStride + row[k]];
+                    acc.x = acc.x + v.x;
+                    acc.y = acc.y + v.y;
+                }
+                tsc[2 * p] = acc.x;
+                tsc[2 * p + 1] = acc.y;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            if (q >= nq) continue;
+            Slots<kItems> s;
+#pragma unroll
+            for (int e = 0; e < kItems; ++e) { s.sc[e] = tsc[q]; s.id[e] = (uint32_t)item + a.id_base; s.ok[e] = e == 0 && item < a.N; }
+            if (lane == 0) my_state[q].cnt = cnt[q];
+            wave_sync();
+            offer_slow<kItems>(&my_state[q], list_of(q), a.cap, K, a.prune_at, s, lane);
+            cnt[q] = __builtin_amdgcn_readfirstlane(my_state[q].cnt);
         }
     }
     PQ_MARK(5);
@@ -1446,6 +1533,62 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
             uint64_t key = key_at(i);
             if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
+    }
+    if (in_regs && K <= kWave) {
+        // Small K: every wave finds a floor that at least K of its lanes' best keys reach, keeps the keys at or above
+        // it (about K of them), and if the waves together kept few enough, wave 0 ranks those and writes the result.
+        // One barrier.  Otherwise the general path below starts over from the keys in registers.
+        constexpr int kWaveKeep = 64, kFoldFast = 256;        // keys a wave may keep here; keys wave 0 ranks alone
+        float best = -__builtin_inff();
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r)
+            if (keys[r]) best = fmaxf(best, score_of_key(keys[r]));
+        const float floor_ge = wave_floor_for_k(best, K);
+        const int wave = tid / kWave;
+        uint64_t* kept = stage + wave * kWaveKeep;            // stage has room for 2048 keys at least
+        int cnt = 0;
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            const bool take = keys[r] != 0ull && score_of_key(keys[r]) >= floor_ge;
+            const uint64_t mask = __ballot(take);
+            if (mask != 0) {
+                const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+                if (take && pos < kWaveKeep) kept[pos] = keys[r];
+                cnt += __popcll(mask);
+            }
+        }
+        if (lane == 0) ctl->wave_cnt[wave] = cnt;
+        __syncthreads();
+        int total = 0;
+        bool fits = true;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) {
+            const int n = ctl->wave_cnt[wv];
+            total += n;
+            fits = fits && n <= kWaveKeep;
+        }
+        if (fits && total <= kFoldFast) {
+            if (wave == 0) {
+                int at = 0;
+                for (int wv = 0; wv < kWaves; ++wv) {
+                    const int n = ctl->wave_cnt[wv];
+                    for (int t = lane; t < n; t += kWave) cand[at + t] = stage[wv * kWaveKeep + t];
+                    at += n;
+                }
+                wave_sync();
+                wave_rank_select<kFoldFast>(cand, total, K, sorted, lane);
+                for (int t = lane; t < K; t += kWave) {
+                    const uint64_t key = sorted[t];
+                    if (a.carry_out) a.carry_out[(size_t)q * K + t] = key;
+                    if (a.out_ids) {
+                        a.out_ids[(size_t)q * K + t] = id_of_key(key);
+                        a.out_scores[(size_t)q * K + t] = score_of_key(key);
+                    }
+                }
+            }
+            return;
+        }
+        __syncthreads();                                      // everyone has read the counts before they are reused
     }
     for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
     float lo, scale;
@@ -1535,13 +1678,19 @@ bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16; }
 
 ScanPlan make_plan(long long N, int B, int m, int K) {
     ScanPlan p;
-    p.vec = is_vec_m(m);
+    p.vec = is_vec_m(m) && N * m >= 16;                        // (the vector kernels need one whole code vector at least)
     const long long units = p.vec ? (N * m) / 16 : N;          // whole code vectors (the few items after them are extra)
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
     if (most < 8) most = 8;
     long long nblk = rounds < most ? rounds : most;
+#ifndef PQ_SHORT_BLOCKS_PER_CU
+#define PQ_SHORT_BLOCKS_PER_CU 1
+#endif
+    long long one_per_cu = PQ_SHORT_BLOCKS_PER_CU * kAssumedCUs / B;   // a short scan is spread evenly: one workgroup per CU, which
+    if (one_per_cu < 8) one_per_cu = 8;                        // then takes two or three (possibly ragged) rounds
+    if (rounds > one_per_cu && (rounds <= most || PQ_SHORT_BLOCKS_PER_CU > 1) && rounds <= 4 * most) nblk = one_per_cu;
     if (nblk < 1) nblk = 1;
     if (B > 1 && nblk >= 8) nblk &= ~7LL;                      // same item block of every query on the same XCD
     p.nblk = (int)nblk;
@@ -1575,7 +1724,7 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
 #ifdef PQ_NO_TILED                                        // tuning builds only
     if (false) {
 #else
-    if (B >= 2 && (m == 8 || m == 16)) {                      // batched kernel, if its tables and lists fit in LDS
+    if (B >= 2 && (m == 8 || m == 16) && N * m >= 16) {       // batched kernel, if its tables and lists fit in LDS
 #endif
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
