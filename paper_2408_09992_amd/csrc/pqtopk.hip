@@ -550,8 +550,6 @@ struct ScanArgs {
     int prune_at;        // wave list length that triggers a tightening (0: only when full)
     uint64_t* ws_keys;   // [B][nblk][K]
     int checkpoint_factor;   // batched kernel: growth of the number of rounds between workgroup checkpoints (>= 2)
-    const uint64_t* carry;   // [B][K] sorted best keys of the items earlier stages scanned; nullptr in the first stage
-    uint32_t id_base;    // id of the first item of `codes` (a later stage scans a suffix of the catalogue)
 };
 
 // Items a thread holds per round.  M > 0: m is M and one 16-byte vector carries 16/M items; M == 0: any m, one item
@@ -785,7 +783,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             const long long item = item_of_slot<M, NT>(rr, nblk, blk, vt, e);
             const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
+            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
     };
@@ -796,15 +794,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         offer(sc, rr, vt);
     };
 
-    if (a.carry != nullptr) {
-        // ---- 2'. a later stage: the K-th best score of everything scanned before is a floor for the whole launch,
-        // so no histogram is needed and the first round is streamed like the others
-        const uint64_t kth = a.carry[(size_t)q * K + (K - 1)];
-        if (kth != 0ull) top.floor_ge = score_of_key(kth);
-        if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
-        process(w[0], r, tid);
-        r += 1;
-    } else if (K <= kWave) {
+    if (K <= kWave) {
         // ---- 2a. first round, K <= 64: a floor that at least K of the lanes' best scores reach, so at least K of this
         // wave's items do; it costs a dozen ballots and no workgroup barrier
         if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
@@ -848,7 +838,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             const long long item = item_of_slot<M, NT>(r, nblk, blk, tid, e);
             const bool take = item < n_scan && bk[e] >= bstar;
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item + a.id_base, lane);
+            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
         r += 1;
@@ -899,7 +889,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
                 take = sc >= top.floor_ge;
             }
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc, (uint32_t)item + a.id_base, lane);
+            if (mask != 0) top.append(mask, take, sc, (uint32_t)item, lane);
         }
     }
     PQ_MARK(5);
@@ -1264,18 +1254,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
         for (int i = tid; i < kQ * kpad; i += kThreads) best[i] = 0;
         if (tid < kQ) ctl_of(tid)->keep = 0;
-        if (lane < kQ) {
-            float floor0 = -__builtin_inff();                 // a later stage starts from the earlier stages' K-th best
-            if (a.carry != nullptr && lane < nq) {
-                const uint64_t kth = a.carry[(size_t)(q0 + lane) * K + (K - 1)];
-                if (kth != 0ull) floor0 = score_of_key(kth);
-            }
-            my_state[lane] = WaveQ{0ull, 0, floor0};
-        }
-        if (a.carry != nullptr && tid < kQ) {                 // no histogram in a later stage: exact selection sorts
-            Ctl* c = ctl_of(tid);
-            c->lo = 0.0f; c->scale = 0.0f; c->cut = -__builtin_inff(); c->bstar = 0; c->ncand = 0;
-        }
+        if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
     }
     __syncthreads();
     PQ_MARK(1);
@@ -1320,7 +1299,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
                 const int n = __popcll(mask);
                 if (cnt[q] + n > a.cap) { stop = e; continue; }
                 const int pos = cnt[q] + __popcll(mask & ((1ull << lane) - 1ull));
-                if (take) buf[pos] = make_key(sc[q][e] + 0.0f, (uint32_t)item + a.id_base);
+                if (take) buf[pos] = make_key(sc[q][e] + 0.0f, (uint32_t)item);
                 cnt[q] += n;
             }
             if (stop < kItems || (a.prune_at != 0 && cnt[q] >= a.prune_at)) {
@@ -1328,7 +1307,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
                 for (int e = 0; e < kItems; ++e) {
                     s.sc[e] = sc[q][e];
-                    s.id[e] = (uint32_t)item_of(rr, e) + a.id_base;
+                    s.id[e] = (uint32_t)item_of(rr, e);
                     s.ok[e] = ok[e] && e >= stop;
                 }
                 if (lane == 0) my_state[q].cnt = cnt[q];
@@ -1339,14 +1318,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         }
     };
 
-    if (a.carry != nullptr) {
-        // ---- 2'. a later stage streams its first round like the others
-        float sc[kQ][kItems];
-        score(wa, sc);
-        load(r + 2 * nblk, wa);
-        offer_round(sc, r, nullptr, nullptr);
-        r += nblk;
-    } else {
+    {
         // ---- 2. first round: per query a histogram over its own score range gives that query's cut
         float sc[kQ][kItems];
         score(wa, sc);
@@ -1456,7 +1428,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             if (q >= nq) continue;
             Slots<kItems> s;
 #pragma unroll
-            for (int e = 0; e < kItems; ++e) { s.sc[e] = tsc[q]; s.id[e] = (uint32_t)item + a.id_base; s.ok[e] = e == 0 && item < a.N; }
+            for (int e = 0; e < kItems; ++e) { s.sc[e] = tsc[q]; s.id[e] = (uint32_t)item; s.ok[e] = e == 0 && item < a.N; }
             if (lane == 0) my_state[q].cnt = cnt[q];
             wave_sync();
             offer_slow<kItems>(&my_state[q], list_of(q), a.cap, K, a.prune_at, s, lane);
@@ -1479,11 +1451,9 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 // Dynamic LDS: hist | ctl | stage (stage_keys, a power of two >= 2K) | cand | sorted
 struct FoldArgs {
     const uint64_t* ws_keys;   // [B][nblk][K]
-    const uint64_t* carry_in;  // [B][K] best keys of earlier stages, folded in as one more list; nullptr: none
-    uint64_t* carry_out;       // [B][K] receives the sorted result as keys (may alias carry_in); nullptr: not wanted
     int nblk, K;
     int stage_keys, candmax;
-    int* out_ids;              // final stage only, else nullptr
+    int* out_ids;
     float* out_scores;
 };
 
@@ -1501,18 +1471,13 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     uint64_t* sorted = cand + a.candmax;
     const int tid = threadIdx.x, q = blockIdx.x, K = a.K;
     const uint64_t* all = a.ws_keys + (size_t)q * a.nblk * K;
-    const long long nlist = (long long)a.nblk * K;
-    const long long nkeys = nlist + (a.carry_in ? K : 0);
-    const uint64_t* carry = a.carry_in ? a.carry_in + (size_t)q * K : nullptr;
-    auto key_at = [&](long long i) { return i < nlist ? all[i] : carry[i - nlist]; };
-    auto emit = [&](const uint64_t* sorted_keys) {            // every read of carry_in is done before this is called
+    const long long nkeys = (long long)a.nblk * K;
+    auto key_at = [&](long long i) { return all[i]; };
+    auto emit = [&](const uint64_t* sorted_keys) {
         for (int t = tid; t < K; t += kThreads) {
             const uint64_t key = sorted_keys[t];
-            if (a.carry_out) a.carry_out[(size_t)q * K + t] = key;
-            if (a.out_ids) {
-                a.out_ids[(size_t)q * K + t] = id_of_key(key);
-                a.out_scores[(size_t)q * K + t] = score_of_key(key);
-            }
+            a.out_ids[(size_t)q * K + t] = id_of_key(key);
+            a.out_scores[(size_t)q * K + t] = score_of_key(key);
         }
     };
 
@@ -1579,11 +1544,8 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
                 wave_rank_select<kFoldFast>(cand, total, K, sorted, lane);
                 for (int t = lane; t < K; t += kWave) {
                     const uint64_t key = sorted[t];
-                    if (a.carry_out) a.carry_out[(size_t)q * K + t] = key;
-                    if (a.out_ids) {
-                        a.out_ids[(size_t)q * K + t] = id_of_key(key);
-                        a.out_scores[(size_t)q * K + t] = score_of_key(key);
-                    }
+                    a.out_ids[(size_t)q * K + t] = id_of_key(key);
+                    a.out_scores[(size_t)q * K + t] = score_of_key(key);
                 }
             }
             return;
@@ -1750,65 +1712,9 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     return p;
 }
 
-// A call is cut into stages over consecutive item ranges.  Each stage is a scan launch plus a fold launch; the fold
-// leaves the best K keys of everything scanned so far in the workspace ("carry"), and the next stage's scan starts
-// from their K-th score as its floor instead of finding one by histogram.  With a floor that is already close to
-// final almost nothing reaches the candidate lists, which matters when a workgroup serves several queries or K is
-// large.  Small problems and single queries take one stage.
-constexpr int kMaxStages = 12;
-constexpr long long kStageAlign = 8192;            // items; a multiple of every kernel's round, and 16-byte aligned rows
-
-struct Stages {
-    int n;
-    long long begin[kMaxStages + 1];               // stage s scans items [begin[s], begin[s + 1])
-    ScanPlan plan[kMaxStages];
-    size_t lists_bytes;                            // per-workgroup lists: max over stages of B * nblk * K keys
-    size_t total_bytes;                            // lists + carry
-};
-
-Stages make_stages(long long N, int B, int m, int K) {
-    Stages st;
-    st.n = 1;
-    st.begin[0] = 0;
-#ifdef PQ_USE_STAGES
-    const long long kb = (long long)K * B;
-    long long rho = 1 + 100000 / kb;               // growth per stage: keeps a stage's expected survivors, K B (rho - 1), modest
-    if (rho < 2) rho = 2;
-    if (rho > 64) rho = 64;
-    long long first_min = (1LL << 20) / B;         // the first stage still has to fill the machine
-    if (first_min < 16384) first_min = 16384;
-    const ScanPlan whole = make_plan(N, B, m, K);
-    // (a workgroup that scans the whole catalogue for its queries tightens its own floors and needs no stages)
-    if (B >= 2 && whole.nblk > 1 && N * (long long)B >= (1LL << 24) && N >= 4 * first_min) {
-        int later = 0;                             // stages after the first: N / rho^later >= first_min
-        long long span = N;
-        while (later < kMaxStages - 1 && span / rho >= first_min) { span /= rho; ++later; }
-        if (later == 0) { later = 1; span = first_min; }
-        long long end = span;
-        for (int s = 0; s < later; ++s) {
-            long long e = (end + kStageAlign - 1) / kStageAlign * kStageAlign;
-            if (e <= st.begin[st.n - 1] || e >= N) break;
-            st.begin[st.n++] = e;
-            end *= rho;
-        }
-    }
-#endif
-    st.begin[st.n] = N;
-    st.lists_bytes = 0;
-    for (int s = 0; s < st.n; ++s) {
-        st.plan[s] = make_plan(st.begin[s + 1] - st.begin[s], B, m, K);
-        const size_t bytes = (size_t)B * st.plan[s].nblk * K * sizeof(uint64_t);
-        if (bytes > st.lists_bytes) st.lists_bytes = bytes;
-    }
-    st.lists_bytes = (st.lists_bytes + 255) & ~(size_t)255;
-    st.total_bytes = st.lists_bytes + (((size_t)B * K * sizeof(uint64_t) + 255) & ~(size_t)255);
-    return st;
-}
-
-bool stages_fit_lds(const Stages& st) {
-    for (int s = 0; s < st.n; ++s)
-        if (st.plan[s].scan_lds > kMaxLdsBytes || st.plan[s].fold_lds > kMaxLdsBytes) return false;
-    return true;
+size_t workspace_bytes(const ScanPlan& p, int B, int K) {
+    const size_t bytes = (size_t)B * p.nblk * K * sizeof(uint64_t);
+    return (bytes + 255) & ~(size_t)255;
 }
 
 int check_topk_args(const void* codes, const void* S, long long N, int B, int m, int b, int K, const void* out_ids,
@@ -1816,12 +1722,12 @@ int check_topk_args(const void* codes, const void* S, long long N, int B, int m,
     if (!codes || !S || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return PQ_ERR_SHAPE;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
-    const Stages st = make_stages(N, B, m, K);
-    if (!stages_fit_lds(st)) return PQ_ERR_UNSUPPORTED;
+    const ScanPlan p = make_plan(N, B, m, K);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)codes & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)S & 3) || ((uintptr_t)out_ids & 3) ||
         ((uintptr_t)out_scores & 3))
         return PQ_ERR_ALIGN;
-    if (workspace_bytes_given < st.total_bytes) return PQ_ERR_WORKSPACE;
+    if (workspace_bytes_given < workspace_bytes(p, B, K)) return PQ_ERR_WORKSPACE;
     return PQ_OK;
 }
 
@@ -1851,11 +1757,10 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
 
 // Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
 int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                 void* workspace, const uint64_t* carry, uint32_t id_base, hipStream_t st) {
+                 void* workspace, hipStream_t st) {
     ScanArgs a;
     a.phase_times = g_phase_times;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
-    a.carry = carry; a.id_base = id_base;
     a.checkpoint_factor = PQ_CHECKPOINT_FACTOR(K);
     a.cap = p.cap; a.candmax = p.candmax;
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
@@ -1883,41 +1788,16 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     return record_hip(e);
 }
 
-// Enqueue the fold of the workspace's lists (and the carry of earlier stages) into the carry and / or the outputs.
-int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, const uint64_t* carry_in, uint64_t* carry_out,
-                 int* out_ids, float* out_scores, hipStream_t st) {
+// Enqueue the fold of the workspace's lists into the outputs.
+int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
     FoldArgs f;
     f.ws_keys = static_cast<const uint64_t*>(workspace);
-    f.carry_in = carry_in; f.carry_out = carry_out;
     f.nblk = p.nblk; f.K = K; f.stage_keys = p.stage_keys; f.candmax = p.candmax;
     f.out_ids = out_ids; f.out_scores = out_scores;
     hipError_t e = allow_lds(fold_topk_kernel, p.fold_lds);
     if (e != hipSuccess) return record_hip(e);
     hipLaunchKernelGGL(fold_topk_kernel, dim3(B), dim3(kThreads), p.fold_lds, st, f);
     return record_hip(hipGetLastError());
-}
-
-// Enqueue every stage's scan and the folds between stages; the last stage's lists stay in the workspace for
-// enqueue_last_fold().
-int enqueue_scans(const Stages& sg, const uint8_t* codes, const float* S, int B, int m, int b, int K, void* workspace,
-                  hipStream_t st) {
-    uint64_t* carry = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + sg.lists_bytes);
-    for (int s = 0; s < sg.n; ++s) {
-        const long long begin = sg.begin[s], len = sg.begin[s + 1] - begin;
-        int rc = enqueue_scan(sg.plan[s], codes + (size_t)begin * m, S, len, B, m, b, K, workspace,
-                              s > 0 ? carry : nullptr, (uint32_t)begin, st);
-        if (rc != PQ_OK) return rc;
-        if (s + 1 < sg.n) {
-            rc = enqueue_fold(sg.plan[s], B, K, workspace, s > 0 ? carry : nullptr, carry, nullptr, nullptr, st);
-            if (rc != PQ_OK) return rc;
-        }
-    }
-    return PQ_OK;
-}
-
-int enqueue_last_fold(const Stages& sg, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
-    const uint64_t* carry = reinterpret_cast<const uint64_t*>(static_cast<unsigned char*>(workspace) + sg.lists_bytes);
-    return enqueue_fold(sg.plan[sg.n - 1], B, K, workspace, sg.n > 1 ? carry : nullptr, nullptr, out_ids, out_scores, st);
 }
 
 template <int S_ELEMS>
@@ -1954,25 +1834,20 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
 size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K) {
     if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return 0;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return 0;
-    const Stages sg = make_stages(N, B, m, K);
-    if (!stages_fit_lds(sg)) return 0;
-#ifdef PQ_PLAN_DEBUG                                      // tuning builds only
-    for (int s = 0; s < sg.n; ++s)
-        fprintf(stderr, "stage %d: items [%lld, %lld) %s nblk %d\n", s, sg.begin[s], sg.begin[s + 1],
-                sg.plan[s].tiled ? "tiled" : "plain", sg.plan[s].nblk);
-#endif
-    return sg.total_bytes;
+    const ScanPlan p = make_plan(N, B, m, K);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
+    return workspace_bytes(p, B, K);
 }
 
 int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
                   float* out_scores, void* workspace, size_t workspace_bytes_given, void* stream) {
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
-    const Stages sg = make_stages(N, B, m, K);
+    const ScanPlan p = make_plan(N, B, m, K);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = enqueue_scans(sg, codes, S, B, m, b, K, workspace, st);
+    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
     if (rc != PQ_OK) return rc;
-    return enqueue_last_fold(sg, B, K, workspace, out_ids, out_scores, st);
+    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
 }
 
 int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
@@ -1982,18 +1857,18 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
     if (iters < 1) return PQ_ERR_SHAPE;
-    const Stages sg = make_stages(N, B, m, K);
+    const ScanPlan p = make_plan(N, B, m, K);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     hipError_t e = hipEventCreate(&ev0);
     if (e != hipSuccess) return record_hip(e);
     e = hipEventCreate(&ev1);
     if (e != hipSuccess) { (void)hipEventDestroy(ev0); return record_hip(e); }
-    rc = enqueue_scans(sg, codes, S, B, m, b, K, workspace, st);             // untimed warm-up pass
+    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);           // untimed warm-up launch
     if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev0, st));
-    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = enqueue_scans(sg, codes, S, B, m, b, K, workspace, st);
+    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
     if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev1, st));
-    if (rc == PQ_OK) rc = enqueue_last_fold(sg, B, K, workspace, out_ids, out_scores, st);
+    if (rc == PQ_OK) rc = enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
     if (rc == PQ_OK) rc = record_hip(hipStreamSynchronize(st));
     float ms = 0.0f;
     if (rc == PQ_OK) rc = record_hip(hipEventElapsedTime(&ms, ev0, ev1));
