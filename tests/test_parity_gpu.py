@@ -74,6 +74,31 @@ def test_score_topk_large_k(pq, oracle):
         assert_same_topk(pq, oracle, G, S, K, "largeK")
 
 
+def test_score_topk_single_query_mid_k(pq, oracle):
+    """K between the sizes the wave-level paths treat differently (pruned lists up to K = 28, floors by bisection
+    up to K = 64, histogram cut above), one query, several rounds per workgroup and a ragged tail."""
+    for N, m in ((1_500_001, 8), (700_003, 4), (300_001, 16)):
+        G = W.codes_uniform(N, m, 256, seed=N)
+        S = W.normal_f32(W.stream_key(N, W.STREAM_QUERIES), m * 256).reshape(1, m, 256)
+        for K in (28, 29, 50, 64, 65):
+            assert_same_topk(pq, oracle, G, S, K, "midK")
+
+
+@pytest.mark.parametrize("N,m,B", [(17_000_003, 4, 1), (17_000_001, 2, 1), (34_000_001, 1, 1), (6_000_001, 4, 3)])
+def test_score_topk_long_scans_replicated_tables(pq, oracle, N, m, B):
+    """Catalogues long enough for the single-query kernel that keeps several copies of the score tables in LDS
+    (1024-thread workgroups, work handed to waves from a counter), for every m it is built for; N leaves a tail
+    of items after the last whole 16-byte code vector.  m = 8 is covered by the 50M-item configuration."""
+    G = W.codes_uniform(N, m, 256, seed=m)
+    S = W.normal_f32(W.stream_key(m, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    ids, sc = assert_same_topk(pq, oracle, G, S, 10, "long")
+    # the last item wins when it is given the best row: the tail after the last whole vector is really scanned
+    G[N - 1] = S[0].argmax(axis=1)
+    ids, sc = assert_same_topk(pq, oracle, G, S, 10, "long+tail")
+    if m >= 4:                                     # (with fewer splits thousands of items share the best row: lower ids win)
+        assert ids[0, 0] == N - 1
+
+
 # ---------------------------------------------------------------- ties and adversarial orders
 
 def test_all_items_equal(pq, oracle):
