@@ -7,19 +7,25 @@
 // Total order used everywhere: a 64-bit key  (orderable(score) << 32) | ~id.  A larger key is a better item:
 // higher score first, lower id between equal scores.  Keys of distinct items are distinct, key 0 means "empty".
 //
-// Shape of pq_score_topk(): a scan launch with grid = (item blocks, B), then a small fold launch.  A scan workgroup
-//   1. requests its first codes, then copies its query's m x b table into LDS;
-//   2. scores a first round of items into registers and histograms them over 1024 equal-width buckets spanning
-//      their range; the bucket that holds the K-th best gives a score cut: everything below it is out for good;
-//   3. streams the rest of its share of G against that cut; survivors (a handful) go to small per-wave lists in
-//      LDS that are pruned exactly (by key) when they fill;
-//   4. selects its exact K best and writes them, sorted, to the workspace.
-// The fold launch (one workgroup per query) reduces the workgroups' lists to the final sorted K the same way.
-// The histogram only ever prunes; every decision that picks a winner compares full keys, so the result is exact
-// for any input, including heavy ties (which merely take slower paths).
+// Shape of pq_score_topk(): one scan launch, then a small fold launch.
+//   scan_topk_kernel<M, C, NT> (one query per workgroup; grid = (item blocks, B)):
+//     1. requests its query's table values and its first rounds of codes, then fills the m x b table into LDS
+//        (C copies of it for long scans, so that lanes with different copies never collide on an LDS bank);
+//     2. scores a first round of items into registers and derives a floor that at least K of them reach (per wave
+//        by bisection with ballots for K <= 64; from a 1024-bucket histogram over the workgroup for larger K):
+//        everything below it is out for good;
+//     3. streams the rest of its share of G against the floor; code loads are branch-free and counted, so the next
+//        round's loads stay in flight; waves take their work units from a counter in LDS; survivors (a handful)
+//        go to small per-wave lists in LDS that are pruned exactly (by key) when they fill, which raises the floor;
+//     4. selects its exact K best and writes them, sorted, to the workspace.
+//   scan_topk_tiled_kernel<M> (m = 8 or 16, B >= 2; a tile of four queries per workgroup, tables interleaved as
+//     float4 so one 16-byte LDS read serves the four queries and sub-id extraction is shared): same steps, plus
+//     workgroup checkpoints at geometrically spaced rounds that merge the waves' lists and raise all floors.
+//   fold_topk_kernel (one workgroup per query) reduces the workgroups' lists to the final sorted K.
+// Floors and histograms only ever prune; every decision that picks a winner compares full keys, so the result is
+// exact for any input, including heavy ties (which merely take slower paths).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdio.h>
 #include <string.h>
 
 #include "pqtopk.h"
@@ -29,30 +35,19 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kThreads = 512;                     // scan workgroup: 8 waves
 constexpr int kWaves = kThreads / kWave;
-#ifndef PQ_BIG_THREADS
-#define PQ_BIG_THREADS 1024
-#endif
-#ifndef PQ_BIG_RING
-#define PQ_BIG_RING 2
-#endif
-constexpr int kBigThreads = PQ_BIG_THREADS;       // workgroup of the long single-query scan with replicated tables
+constexpr int kBigThreads = 1024;                 // workgroup of the long single-query scan with replicated tables
 constexpr int kMaxWaves = kBigThreads / kWave;
 constexpr int kLutStride = 256;                   // table entries per split in LDS (a uint8 sub-id never runs past it)
 constexpr int kBins = 1024;                       // score buckets of the pruning histogram
 // 16-byte code vectors a thread holds per round: 4 for m >= 8, fewer for small m so a thread never holds > 16 items
-#ifndef PQ_VEC_PER_THREAD
-#define PQ_VEC_PER_THREAD 4
-#endif
-__host__ __device__ constexpr int vec_per_thread(int m) { return m >= 8 ? PQ_VEC_PER_THREAD : (m == 4 ? 2 : 1); }
+__host__ __device__ constexpr int vec_per_thread(int m) { return m >= 8 ? 4 : (m == 4 ? 2 : 1); }
 constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
+constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
 constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace
-#ifndef PQ_BLOCKS_PER_CU
-#define PQ_BLOCKS_PER_CU 2
-#endif
-constexpr int kBlocksPerCU = PQ_BLOCKS_PER_CU;    // scan workgroups per CU over the whole grid
+constexpr int kBlocksPerCU = 2;                   // single-query scan workgroups per CU over the whole grid
 constexpr int kTableCopies = 16;                  // copies of the score tables in the long single-query scan
 constexpr int kTableCopiesMinRounds = 8;          // rounds per workgroup from which the copies pay for themselves
 
@@ -528,19 +523,7 @@ __device__ inline ScanLds carve_scan(unsigned char* smem, size_t lut_floats, int
     return L;
 }
 
-// Optional phase timestamps for kernel tuning: built only with -DPQ_PHASE_TIMES, never in the shipped library.
-#ifdef PQ_PHASE_TIMES
-#define PQ_MARK(slot)                                                                                              \
-    do {                                                                                                           \
-        if (a.phase_times && threadIdx.x == 0)                                                                     \
-            a.phase_times[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64();           \
-    } while (0)
-#else
-#define PQ_MARK(slot) do {} while (0)
-#endif
-
 struct ScanArgs {
-    unsigned long long* phase_times;   // debug builds only
     const uint8_t* codes;
     const float* S;
     long long N;
@@ -574,15 +557,7 @@ __device__ __forceinline__ void score_vector(const float* lut, const uint32_t* w
 #pragma unroll
     for (int byte = 0; byte < 16; ++byte) {
         const uint32_t code = (w[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
-#ifdef PQ_DIAG_NOGATHER                              // tuning builds only: no table reads (results are wrong)
-        v[byte] = __uint_as_float(0x3f800000u | code);
-#else
-#ifdef PQ_DIAG_NOCONFLICT                             // tuning builds only: 32 consecutive words, no bank conflicts
-        v[byte] = lut[(byte % M) * kLutStride + (code & 31u)];
-#else
         v[byte] = lut[((byte % M) * kLutStride + code) * C];
-#endif
-#endif
     }
     __builtin_amdgcn_sched_barrier(0);                // keep the 16 reads ahead of the sums
 #pragma unroll
@@ -643,11 +618,7 @@ __device__ __forceinline__ void load_round(const ScanArgs& a, long long rr, int 
         const uint4* base = reinterpret_cast<const uint4*>(a.codes);
 #pragma unroll
         for (int u = 0; u < Round<M>::kVecs; ++u) {
-#ifdef PQ_DIAG_NOLOAD                                 // tuning builds only: always the first round's codes
-            long long v = unit_of<M, NT>(0, u, nblk, blk, tid);
-#else
             long long v = unit_of<M, NT>(rr, u, nblk, blk, tid);
-#endif
             v = v < last_vec ? v : last_vec;
             const uint4 x = base[v];
             w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
@@ -718,9 +689,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     const long long rounds = (total_units + round_units - 1) / round_units;   // every workgroup runs them all
     const long long inside_rounds = total_units / round_units;                // rounds with no ragged end
 
-    PQ_MARK(0);
     // ---- 1. the first kRing rounds' codes on their way, then the query's table into LDS
-    constexpr int kRing = C > 1 ? PQ_BIG_RING : 2;            // rounds of codes in flight or in registers per thread
     long long r = 0;
     const int blk = blockIdx.x;
     uint32_t w[kRing][kWords];
@@ -763,7 +732,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
     if (tid == 0) ctl->next_unit = kRing * NW;
     __syncthreads();
-    PQ_MARK(1);
     const float* const lut = lut_base + (C > 1 ? lane % C : 0);   // this lane's copy
 
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
@@ -773,9 +741,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         float best = sc[0];
 #pragma unroll
         for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
-#ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
-        if (__ballot(best >= 1.0e30f) == 0) return;
-#endif
         if (__ballot(best >= top.floor_ge) == 0) return;      // nothing in this round can matter
         const bool inside = rr < inside_rounds;
 #pragma unroll
@@ -805,9 +770,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
             if (inside || item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) best = fmaxf(best, sc[e]);
-        PQ_MARK(2);
         top.floor_ge = wave_floor_for_k(best, K);
-        PQ_MARK(3);
         offer(sc, r, tid);
         r += 1;
     } else {
@@ -820,7 +783,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             if (item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
         float lo, scale;
         set_range<NW>(mn, mx, ctl, tid, lo, scale);
-        PQ_MARK(2);
         int bk[kItems];
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
@@ -830,7 +792,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         __syncthreads();
         if (tid < kWave) find_cut(L.hist, K, ctl, lane);
         __syncthreads();
-        PQ_MARK(3);
         const int bstar = ctl->bstar;
         top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut
 #pragma unroll
@@ -843,7 +804,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
         r += 1;
     }
-    PQ_MARK(4);
 
     // ---- 3. stream the remaining rounds against the wave's floor.  Work is handed out in units of one wave's share
     // of a round: unit j is the share of wave j % NW in round j / NW.  A wave's first kRing units are its own share
@@ -892,7 +852,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             if (mask != 0) top.append(mask, take, sc, (uint32_t)item, lane);
         }
     }
-    PQ_MARK(5);
 
     // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
     if (lane == 0) ctl->wave_cnt[wave] = top.cnt;
@@ -918,7 +877,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             wave_rank_select(L.cand, total, K, L.sorted, lane);
             for (int t = lane; t < K; t += kWave) mine_out[t] = L.sorted[t];
         }
-        PQ_MARK(6);
         return;
     }
     if (total <= a.candmax) {
@@ -930,22 +888,18 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         block_select<NT>(L.lists, NW * a.cap, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
     }
     for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
-    PQ_MARK(6);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Batched scan: one workgroup serves a tile of kQ queries with one pass over its share of G.  The tables of two
-// queries are interleaved ([pair][split][sub-id] -> float2), so one 8-byte LDS read returns the table values of
-// two queries for one sub-id: random 8-byte gathers run close to the LDS peak (128 B/clk/CU) where 4-byte ones reach
-// half of it, and sub-id extraction, address arithmetic and the code loads are shared by the whole tile.
+// Batched scan: one workgroup serves a tile of kQ = 4 queries with one pass over its share of G.  The four queries'
+// tables are interleaved ([split][sub-id] -> float4), so one 16-byte LDS read returns the table values of the four
+// queries for one sub-id: random 16-byte gathers move about twice the bytes per clock that 4-byte ones do, and
+// sub-id extraction, address arithmetic and the code loads are shared by the whole tile.
 // grid = (item blocks, ceil(B / kQ)).  Static LDS: the tile's tables.  Dynamic LDS:
-// hist[kQ][kTiledBins] | ctl[kQ] | state[kWaves][kQ] | lists[kQ][kWaves][cap] | cand[candmax] | sorted[K] | best[kQ][K].
-constexpr int kQ = 4;                // queries per tile
-constexpr int kTileVecs = 2;         // 16-byte code vectors a thread holds per round
-constexpr int kTiledBins = kBins / kQ;
-#ifndef PQ_CHECKPOINT_FACTOR
-#define PQ_CHECKPOINT_FACTOR(K) ((K) > 28 ? 2 : 8)
-#endif   // buckets per query; the kQ histograms together serve as one kBins histogram
+// hist[kQ][kTiledBins] | ctl[kQ] | state[kWaves][kQ] | lists[kQ][kWaves][cap] | cand[candmax] | sorted[K] | best[kQ][kpad].
+constexpr int kQ = 4;                    // queries per tile
+constexpr int kTileVecs = 2;             // 16-byte code vectors a thread holds per round
+constexpr int kTiledBins = kBins / kQ;   // buckets per query; the kQ histograms together serve as one kBins histogram
 
 // One (wave, query) candidate list's state.  It lives in LDS so that the streaming loop keeps none of it in registers.
 struct WaveQ {
@@ -964,31 +918,27 @@ __host__ __device__ inline size_t tiled_lds_bytes(int cap, int candmax, int K) {
            (size_t)kQ * tiled_best_keys(K) * sizeof(uint64_t);
 }
 
-// Eq. 5 for the 16/M items of one code vector and the kQ queries of the tile; sc[q][e], sums left to right.
+// Eq. 5 for the 16/M items of one code vector and the kQ = 4 queries of the tile; sc[q][e], sums left to right.
+// The four queries' tables are interleaved ([split][sub-id] -> float4): one 16-byte LDS read per sub-id.
 template <int M>
-__device__ __forceinline__ void score_vector_tiled(const float2* lut2, const uint32_t* w, float (&sc)[kQ][16 / M]) {
+__device__ __forceinline__ void score_vector_quad(const float4* lut4, const uint32_t* w, float (&sc)[kQ][16 / M]) {
+    static_assert(kQ == 4, "one float4 per table entry");
+    float4 v[16];
 #pragma unroll
-    for (int p = 0; p < kQ / 2; ++p) {
-        float2 v[16];
+    for (int byte = 0; byte < 16; ++byte) {
+        const uint32_t code = (w[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
+        v[byte] = lut4[(byte % M) * kLutStride + code];
+    }
+    __builtin_amdgcn_sched_barrier(0);                    // keep the 16 reads ahead of the sums
 #pragma unroll
-        for (int byte = 0; byte < 16; ++byte) {
-            const uint32_t code = (w[byte >> 2] >> ((byte & 3) * 8)) & 0xFFu;
-            v[byte] = lut2[(p * M + (byte % M)) * kLutStride + code];
+    for (int e = 0; e < 16 / M; ++e) {
+        float4 acc = v[e * M];
+#pragma unroll
+        for (int k = 1; k < M; ++k) {
+            acc.x = acc.x + v[e * M + k].x; acc.y = acc.y + v[e * M + k].y;
+            acc.z = acc.z + v[e * M + k].z; acc.w = acc.w + v[e * M + k].w;
         }
-        __builtin_amdgcn_sched_barrier(0);                // keep the 16 reads ahead of the sums
-#pragma unroll
-        for (int e = 0; e < 16 / M; ++e) {
-            float a0 = v[e * M].x, a1 = v[e * M].y;
-#pragma unroll
-            for (int k = 1; k < M; ++k) { a0 = a0 + v[e * M + k].x; a1 = a1 + v[e * M + k].y; }
-            // the empty asm ties the finished sums to a point the next group's reads cannot cross, so at most one
-            // group's 16 values are live at a time (otherwise all reads get hoisted and registers triple)
-#ifdef PQ_TILED_PIN
-            asm volatile("" : "+v"(a0), "+v"(a1) : : "memory");
-#endif
-            sc[2 * p][e] = a0;
-            sc[2 * p + 1][e] = a1;
-        }
+        sc[0][e] = acc.x; sc[1][e] = acc.y; sc[2][e] = acc.z; sc[3][e] = acc.w;
     }
 }
 
@@ -1174,7 +1124,7 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
 template <int M>
 __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, int B) {
     constexpr int IPV = 16 / M, kItems = kTileVecs * IPV, kWords = kTileVecs * 4;
-    __shared__ __align__(16) float2 lut2[(kQ / 2) * M * kLutStride];
+    __shared__ __align__(16) float4 lut4[M * kLutStride];
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
     unsigned char* pctl = smem + (size_t)kBins * sizeof(uint32_t);
@@ -1220,7 +1170,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
         for (int u = 0; u < kTileVecs; ++u) {
             float part[kQ][IPV];
-            score_vector_tiled<M>(lut2, &w[4 * u], part);
+            score_vector_quad<M>(lut4, &w[4 * u], part);
 #pragma unroll
             for (int q = 0; q < kQ; ++q)
 #pragma unroll
@@ -1228,27 +1178,26 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         }
     };
 
-    PQ_MARK(0);
     // ---- 1. codes on their way, the tile's tables into LDS (queries past B get zero tables and are never scored)
     long long r = blockIdx.x;
     uint32_t wa[kWords], wb[kWords];
     load(r, wa);
     load(r + nblk, wb);
     {
-        float* lutf = reinterpret_cast<float*>(lut2);
+        float* lutf = reinterpret_cast<float*>(lut4);
         if (b == kLutStride) {                                // whole rows: 16-byte loads, four sub-ids at a time
             for (int e4 = tid; e4 < kQ * M * kLutStride / 4; e4 += kThreads) {
                 const int q = e4 / (M * kLutStride / 4), kj4 = e4 % (M * kLutStride / 4);
                 float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
                 if (q < nq) v = reinterpret_cast<const float4*>(a.S + (size_t)(q0 + q) * M * kLutStride)[kj4];
-                float* dst = lutf + ((size_t)(q >> 1) * M * kLutStride + (size_t)kj4 * 4) * 2 + (q & 1);
-                dst[0] = v.x; dst[2] = v.y; dst[4] = v.z; dst[6] = v.w;
+                float* dst = lutf + (size_t)kj4 * 4 * kQ + q;
+                dst[0] = v.x; dst[kQ] = v.y; dst[2 * kQ] = v.z; dst[3 * kQ] = v.w;
             }
         } else {
             for (int e = tid; e < kQ * M * kLutStride; e += kThreads) {
                 const int q = e / (M * kLutStride), kj = e % (M * kLutStride), k = kj / kLutStride, j = kj % kLutStride;
                 const float v = (q < nq && j < b) ? a.S[((size_t)(q0 + q) * M + k) * b + j] : 0.0f;
-                lutf[(((q >> 1) * M + k) * kLutStride + j) * 2 + (q & 1)] = v;
+                lutf[((size_t)k * kLutStride + j) * kQ + q] = v;
             }
         }
         for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
@@ -1257,7 +1206,6 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
     }
     __syncthreads();
-    PQ_MARK(1);
 
     // One round's scores against the kQ lists of this wave.  The lists' lengths are cached in scalar registers
     // (cnt[q]) while rounds stream: a survivor then costs one ballot-compacted LDS write and no LDS round trip.
@@ -1280,9 +1228,6 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             float best = sc[q][0];
 #pragma unroll
             for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[q][e]);
-#ifdef PQ_DIAG_STREAMONLY                             // tuning builds only: nothing ever passes (results are wrong)
-            if (bk == nullptr && __ballot(best >= 1.0e30f) == 0) continue;
-#endif
             const float floor_ge = my_state[q].floor_ge;
             if (__ballot(best >= floor_ge) == 0) continue;    // the usual case
             uint64_t* const buf = list_of(q);
@@ -1351,10 +1296,8 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             }
         }
         __syncthreads();
-        PQ_MARK(2);
         if (wave < kQ) find_cut<kTiledBins>(hist + wave * kTiledBins, K, ctl_of(wave), lane);
         __syncthreads();
-        PQ_MARK(3);
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             bstar[q] = ctl_of(q)->bstar;
@@ -1364,7 +1307,6 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         offer_round(sc, r, bk, bstar);
         r += nblk;
     }
-    PQ_MARK(4);
 
     // ---- 3. stream: wb holds round r, wa round r + nblk.  Segments of 2, 2 f, 2 f^2, ... rounds, a workgroup
     // checkpoint between segments: the floors stay close to what the scanned part of the catalogue allows.
@@ -1412,12 +1354,13 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             const uint8_t* row = a.codes + item * M;
 #pragma unroll
             for (int p = 0; p < kQ / 2; ++p) {
-                float2 acc = lut2[(p * M) * kLutStride + row[0]];
+                const float* lf = reinterpret_cast<const float*>(lut4);
+                float2 acc = make_float2(lf[(size_t)row[0] * kQ + 2 * p], lf[(size_t)row[0] * kQ + 2 * p + 1]);
 #pragma unroll
                 for (int k = 1; k < M; ++k) {
-                    const float2 v = lut2[(p * M + k) * kLutStride + row[k]];
-                    acc.x = acc.x + v.x;
-                    acc.y = acc.y + v.y;
+                    const size_t at = ((size_t)k * kLutStride + row[k]) * kQ + 2 * p;
+                    acc.x = acc.x + lf[at];
+                    acc.y = acc.y + lf[at + 1];
                 }
                 tsc[2 * p] = acc.x;
                 tsc[2 * p + 1] = acc.y;
@@ -1435,7 +1378,6 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             cnt[q] = __builtin_amdgcn_readfirstlane(my_state[q].cnt);
         }
     }
-    PQ_MARK(5);
 
     // ---- 4. last checkpoint, then the workgroup's exact K best per query go to the workspace, sorted
     publish_counts();
@@ -1444,7 +1386,6 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         const int q = i / K, t = i % K;
         a.ws_keys[((size_t)(q0 + q) * nblk + blockIdx.x) * K + t] = best[(size_t)q * kpad + t];
     }
-    PQ_MARK(6);
 }
 
 // Grid-level fold: one workgroup per query turns the nblk sorted lists of K keys into the final K, sorted.
@@ -1606,8 +1547,6 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
 // ---------------------------------------------------------------------------------------------------------------
 // host side
 
-unsigned long long* g_phase_times = nullptr;       // set only by the debug hook of -DPQ_PHASE_TIMES builds
-
 thread_local char g_hip_error[256] = "no HIP error recorded";
 
 int record_hip(hipError_t e) {
@@ -1647,12 +1586,9 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
     if (most < 8) most = 8;
     long long nblk = rounds < most ? rounds : most;
-#ifndef PQ_SHORT_BLOCKS_PER_CU
-#define PQ_SHORT_BLOCKS_PER_CU 1
-#endif
-    long long one_per_cu = PQ_SHORT_BLOCKS_PER_CU * kAssumedCUs / B;   // a short scan is spread evenly: one workgroup per CU, which
+    long long one_per_cu = kAssumedCUs / B;                    // a short scan is spread evenly: one workgroup per CU, which
     if (one_per_cu < 8) one_per_cu = 8;                        // then takes two or three (possibly ragged) rounds
-    if (rounds > one_per_cu && (rounds <= most || PQ_SHORT_BLOCKS_PER_CU > 1) && rounds <= 4 * most) nblk = one_per_cu;
+    if (rounds > one_per_cu && rounds <= most) nblk = one_per_cu;
     if (nblk < 1) nblk = 1;
     if (B > 1 && nblk >= 8) nblk &= ~7LL;                      // same item block of every query on the same XCD
     p.nblk = (int)nblk;
@@ -1663,7 +1599,6 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     p.stage_keys = next_pow2(2 * K);
     if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
     p.copies = 1;
-#ifndef PQ_NO_TABLE_COPIES
     // A long scan for few queries is bound by LDS bank conflicts of the random lookups: with kTableCopies copies of
     // the tables, lanes l and l' collide only if l % kTableCopies == l' % kTableCopies.  Worth its LDS and fill time
     // only when every workgroup streams many rounds; one workgroup per CU then (the tables take 128 KB at m = 8).
@@ -1678,16 +1613,11 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
             p.nblk = (int)nb;
         }
     }
-#endif
     const size_t lut_dyn = p.copies > 1 ? (size_t)m * kLutStride * p.copies : (p.vec ? 0 : (size_t)m * kLutStride);
     p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.copies > 1 ? kMaxWaves : kWaves);
     p.scan_lds = p.scan_dyn_lds + ((p.vec && p.copies == 1) ? (size_t)m * kLutStride * sizeof(float) : 0);
     p.tiled = false;
-#ifdef PQ_NO_TILED                                        // tuning builds only
-    if (false) {
-#else
     if (B >= 2 && (m == 8 || m == 16) && N * m >= 16) {       // batched kernel, if its tables and lists fit in LDS
-#endif
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
         if (all <= kMaxLdsBytes) {
@@ -1697,10 +1627,7 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
             const long long tiles = (B + kQ - 1) / kQ;
             const long long t_round = (long long)kThreads * kTileVecs;
             const long long t_rounds = (units + t_round - 1) / t_round;
-#ifndef PQ_TILED_BLOCKS_PER_CU
-#define PQ_TILED_BLOCKS_PER_CU 1
-#endif
-            long long want = ((long long)PQ_TILED_BLOCKS_PER_CU * kAssumedCUs) / tiles;
+            long long want = ((long long)kAssumedCUs) / tiles;
             if (want < 1) want = 1;                           // enough tiles to fill the machine: one workgroup each
             long long nb = t_rounds < want ? t_rounds : want;
             if (nb >= 8) nb &= ~7LL;                          // every tile's item block x lands on XCD x % 8
@@ -1759,9 +1686,8 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
 int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
                  void* workspace, hipStream_t st) {
     ScanArgs a;
-    a.phase_times = g_phase_times;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
-    a.checkpoint_factor = PQ_CHECKPOINT_FACTOR(K);
+    a.checkpoint_factor = K > 28 ? 2 : 8;                  // small K: the waves' own pruning already keeps floors tight
     a.cap = p.cap; a.candmax = p.candmax;
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
     a.ws_keys = static_cast<uint64_t*>(workspace);
@@ -1809,11 +1735,6 @@ void launch_subitem(const float* queries, const float* centroids, float* S, int 
 }  // namespace
 
 extern "C" {
-
-#ifdef PQ_PHASE_TIMES
-// debug builds: device buffer of 16 timestamps (100 MHz ticks) per workgroup
-void pq_debug_set_phase_times(unsigned long long* device_buffer) { g_phase_times = device_buffer; }
-#endif
 
 int pq_subitem_scores(const float* queries, const float* centroids, float* S, int B, int d, int m, int b,
                       void* stream) {
