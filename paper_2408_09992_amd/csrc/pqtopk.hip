@@ -601,10 +601,12 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
 
 // Unit (code vector, or item in the generic kernel) that thread `tid` of workgroup `blk` owns in slot u of its
 // round rr: ((rr * kUnits + u) * nblk + blk) * NT + tid.  Slot u of one round of all workgroups together is one
-// contiguous stretch of the catalogue, so the grid sweeps memory front to back.
+// contiguous stretch of the catalogue, so the grid sweeps memory front to back.  32-bit arithmetic: there are fewer
+// than 2^31 units (N < 2^31, m <= 16 in the vector kernels) and the few rounds a kernel reaches past the end add
+// less than 2^24 to that, so nothing wraps.
 template <int M, int NT>
-__device__ __forceinline__ long long unit_of(long long rr, int u, int nblk, int blk, int tid) {
-    return ((rr * Round<M>::kUnitsPerThread + u) * nblk + blk) * NT + tid;
+__device__ __forceinline__ uint32_t unit_of(uint32_t rr, int u, int nblk, int blk, int tid) {
+    return ((rr * Round<M>::kUnitsPerThread + u) * (uint32_t)nblk + (uint32_t)blk) * NT + (uint32_t)tid;
 }
 
 // The code vectors this thread owns in round rr (vector kernels only).  Always the same number of plain 16-byte
@@ -612,13 +614,13 @@ __device__ __forceinline__ long long unit_of(long long rr, int u, int nblk, int 
 // branch, so the compiler knows how many loads are outstanding at any point and lets several rounds stay in
 // flight.  A clamped vector's items are masked out by the caller.
 template <int M, int NT = kThreads>
-__device__ __forceinline__ void load_round(const ScanArgs& a, long long rr, int nblk, int blk, long long last_vec, int tid,
+__device__ __forceinline__ void load_round(const ScanArgs& a, uint32_t rr, int nblk, int blk, uint32_t last_vec, int tid,
                                            uint32_t (&w)[Round<M>::kWords]) {
     if constexpr (M > 0) {
         const uint4* base = reinterpret_cast<const uint4*>(a.codes);
 #pragma unroll
         for (int u = 0; u < Round<M>::kVecs; ++u) {
-            long long v = unit_of<M, NT>(rr, u, nblk, blk, tid);
+            uint32_t v = unit_of<M, NT>(rr, u, nblk, blk, tid);
             v = v < last_vec ? v : last_vec;
             const uint4 x = base[v];
             w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
@@ -630,8 +632,8 @@ __device__ __forceinline__ void load_round(const ScanArgs& a, long long rr, int 
 // `inside`: the round lies wholly inside the scanned units (n_units of them); otherwise vectors past the end are not
 // looked up at all (a wave whose lanes are all past the end skips the vector's table reads).
 template <int M, int C = 1, int NT = kThreads>
-__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, long long rr, int nblk, int blk, int tid,
-                                            bool inside, long long n_units, const uint32_t (&w)[Round<M>::kWords],
+__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, uint32_t rr, int nblk, int blk, int tid,
+                                            bool inside, uint32_t n_units, const uint32_t (&w)[Round<M>::kWords],
                                             float (&sc)[Round<M>::kItems]) {
     if constexpr (M > 0) {
 #pragma unroll
@@ -646,15 +648,15 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
     } else {
 #pragma unroll
         for (int u = 0; u < kGenericItemsPerThread; ++u) {
-            const long long item = unit_of<M, NT>(rr, u, nblk, blk, tid);
-            sc[u] = (item < a.N) ? score_row(lut, a.codes + item * a.m, a.m) : 0.0f;
+            const uint32_t item = unit_of<M, NT>(rr, u, nblk, blk, tid);
+            sc[u] = (item < n_units) ? score_row(lut, a.codes + (size_t)item * a.m, a.m) : 0.0f;
         }
     }
 }
 
 // Id of the item in slot e of this thread's round (may lie past the scanned items in the last round).
 template <int M, int NT = kThreads>
-__device__ __forceinline__ long long item_of_slot(long long rr, int nblk, int blk, int tid, int e) {
+__device__ __forceinline__ uint32_t item_of_slot(uint32_t rr, int nblk, int blk, int tid, int e) {
     constexpr int IPV = Round<M>::kIPV;
     return unit_of<M, NT>(rr, e / IPV, nblk, blk, tid) * IPV + (e % IPV);
 }
@@ -682,19 +684,19 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
 
     // Vector kernels scan the code vectors that lie wholly inside the catalogue; the fewer than 16 / M items after
     // them (when N * M is not a multiple of 16) are scored one by one at the end.  The generic kernel scans items.
-    const long long total_units = M ? (a.N * M) / 16 : a.N;
-    const long long n_scan = M ? total_units * Round<M>::kIPV : a.N;          // items the rounds cover
-    const long long last_vec = total_units > 0 ? total_units - 1 : 0;
-    const long long round_units = (long long)NT * kUnits * nblk;              // units all workgroups take per round
-    const long long rounds = (total_units + round_units - 1) / round_units;   // every workgroup runs them all
-    const long long inside_rounds = total_units / round_units;                // rounds with no ragged end
+    const uint32_t total_units = (uint32_t)(M ? (a.N * M) / 16 : a.N);
+    const uint32_t n_scan = M ? total_units * Round<M>::kIPV : total_units;   // items the rounds cover
+    const uint32_t last_vec = total_units - 1;                                // (total_units >= 1: the host sees to it)
+    const uint32_t round_units = (uint32_t)NT * kUnits * nblk;                // units all workgroups take per round
+    const uint32_t rounds = (total_units + round_units - 1) / round_units;    // every workgroup runs them all
+    const uint32_t inside_rounds = total_units / round_units;                 // rounds with no ragged end
 
     // ---- 1. the first kRing rounds' codes on their way, then the query's table into LDS
-    long long r = 0;
+    uint32_t r = 0;
     const int blk = blockIdx.x;
     uint32_t w[kRing][kWords];
     // (vt: the thread index whose share of round rr is meant; a wave may take over another wave's share)
-    auto fetch = [&](long long rr, int vt, uint32_t (&buf)[kWords]) { load_round<M, NT>(a, rr, nblk, blk, last_vec, vt, buf); };
+    auto fetch = [&](uint32_t rr, int vt, uint32_t (&buf)[kWords]) { load_round<M, NT>(a, rr, nblk, blk, last_vec, vt, buf); };
     // (the host sends catalogues with no whole code vector, N * M < 16, to the generic kernel: rounds >= 1 here)
     auto fetch_first = [&]() {                                // no branch: the loads can be counted, so what follows
 #pragma unroll                                                // waits for exactly what it needs
@@ -737,7 +739,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
 
     // what a round's scores offer to the wave's list: everything at or above its floor
-    auto offer = [&](const float (&sc)[kItems], long long rr, int vt) {
+    auto offer = [&](const float (&sc)[kItems], uint32_t rr, int vt) {
         float best = sc[0];
 #pragma unroll
         for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
@@ -745,36 +747,22 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         const bool inside = rr < inside_rounds;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const long long item = item_of_slot<M, NT>(rr, nblk, blk, vt, e);
+            const uint32_t item = item_of_slot<M, NT>(rr, nblk, blk, vt, e);
             const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
+            if (mask != 0) top.append(mask, take, sc[e], item, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
     };
     // one streamed round
-    auto process = [&](const uint32_t (&w)[kWords], long long rr, int vt) {
+    auto process = [&](const uint32_t (&w)[kWords], uint32_t rr, int vt) {
         float sc[kItems];
         score_round<M, C, NT>(a, lut, rr, nblk, blk, vt, rr < inside_rounds, total_units, w, sc);
         offer(sc, rr, vt);
     };
 
-    if (K <= kWave) {
-        // ---- 2a. first round, K <= 64: a floor that at least K of the lanes' best scores reach, so at least K of this
-        // wave's items do; it costs a dozen ballots and no workgroup barrier
-        if (tid == 0) { ctl->lo = 0.0f; ctl->scale = 0.0f; ctl->cut = -__builtin_inff(); ctl->bstar = 0; ctl->ncand = 0; }
-        float sc[kItems];
-        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
-        const bool inside = r < inside_rounds;
-        float best = -__builtin_inff();
-#pragma unroll
-        for (int e = 0; e < kItems; ++e)
-            if (inside || item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) best = fmaxf(best, sc[e]);
-        top.floor_ge = wave_floor_for_k(best, K);
-        offer(sc, r, tid);
-        r += 1;
-    } else {
-        // ---- 2b. first round, larger K: scores in registers, histogram over their range, cut
+    {
+        // ---- 2. first round: scores in registers, histogram over their range, cut
         float sc[kItems];
         score_round<M, C, NT>(a, lut, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
         float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -796,10 +784,10 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const long long item = item_of_slot<M, NT>(r, nblk, blk, tid, e);
+            const uint32_t item = item_of_slot<M, NT>(r, nblk, blk, tid, e);
             const bool take = item < n_scan && bk[e] >= bstar;
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], (uint32_t)item, lane);
+            if (mask != 0) top.append(mask, take, sc[e], item, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
         r += 1;
@@ -812,14 +800,16 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     // up at the end.  The counter's atomic is issued one step before its result is used, and a unit's loads are
     // unconditional (past the last unit they are clamped re-reads whose data is never used): no wait in the loop
     // is longer than it has to be.
-    if (rounds > 1) {
-        const long long units = rounds * NW;
+    if (rounds == 2) {
+        process(w[1], 1, tid);                                // a short scan: the second round is already loaded
+    } else if (rounds > 2) {
+        const uint32_t units = rounds * NW;
         int pending = 0;                                      // lane 0: result of the last counter request
         auto request_unit = [&]() { if (lane == 0) pending = atomicAdd(&ctl->next_unit, 1); };
-        auto requested_unit = [&]() -> long long { return (long long)__builtin_amdgcn_readfirstlane(pending); };
-        long long unit[kRing];                                // unit held by w[i]
+        auto requested_unit = [&]() -> uint32_t { return (uint32_t)__builtin_amdgcn_readfirstlane(pending); };
+        uint32_t unit[kRing];                                 // unit held by w[i]
 #pragma unroll
-        for (int i = 1; i < kRing; ++i) unit[i] = (long long)i * NW + wave;
+        for (int i = 1; i < kRing; ++i) unit[i] = (uint32_t)i * NW + wave;
         request_unit();
         unit[0] = requested_unit();
         request_unit();
@@ -838,11 +828,11 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     if constexpr (M > 0) {
         // the fewer than 16 / M items after the last whole code vector, one per lane of one wave
         if (blockIdx.x == 0 && wave == 0) {
-            const long long item = n_scan + lane;
+            const uint32_t item = n_scan + lane;
             float sc = 0.0f;
             bool take = false;
-            if (item < a.N) {
-                const uint8_t* row = a.codes + item * M;
+            if (item < (uint32_t)a.N) {
+                const uint8_t* row = a.codes + (size_t)item * M;
                 sc = lut[(size_t)row[0] * C];
 #pragma unroll
                 for (int k = 1; k < M; ++k) sc = sc + lut[((size_t)k * kLutStride + row[k]) * C];
@@ -864,21 +854,6 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         total += c;
     }
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
-    if (total <= kFastCand) {                                 // the usual case: wave 0 ranks them alone and stores
-        if (wave == 0) {
-            int at = 0;
-            for (int wv = 0; wv < NW; ++wv) {
-                const int n = ctl->wave_cnt[wv];
-                const uint64_t* src = L.lists + (size_t)wv * a.cap;
-                for (int t = lane; t < n; t += kWave) L.cand[at + t] = src[t];
-                at += n;
-            }
-            wave_sync();
-            wave_rank_select(L.cand, total, K, L.sorted, lane);
-            for (int t = lane; t < K; t += kWave) mine_out[t] = L.sorted[t];
-        }
-        return;
-    }
     if (total <= a.candmax) {
         for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
         rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
@@ -1439,59 +1414,6 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
             uint64_t key = key_at(i);
             if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
-    }
-    if (in_regs && K <= kWave) {
-        // Small K: every wave finds a floor that at least K of its lanes' best keys reach, keeps the keys at or above
-        // it (about K of them), and if the waves together kept few enough, wave 0 ranks those and writes the result.
-        // One barrier.  Otherwise the general path below starts over from the keys in registers.
-        constexpr int kWaveKeep = 64, kFoldFast = 256;        // keys a wave may keep here; keys wave 0 ranks alone
-        float best = -__builtin_inff();
-#pragma unroll
-        for (int r = 0; r < kFoldRegs; ++r)
-            if (keys[r]) best = fmaxf(best, score_of_key(keys[r]));
-        const float floor_ge = wave_floor_for_k(best, K);
-        const int wave = tid / kWave;
-        uint64_t* kept = stage + wave * kWaveKeep;            // stage has room for 2048 keys at least
-        int cnt = 0;
-#pragma unroll
-        for (int r = 0; r < kFoldRegs; ++r) {
-            const bool take = keys[r] != 0ull && score_of_key(keys[r]) >= floor_ge;
-            const uint64_t mask = __ballot(take);
-            if (mask != 0) {
-                const int pos = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-                if (take && pos < kWaveKeep) kept[pos] = keys[r];
-                cnt += __popcll(mask);
-            }
-        }
-        if (lane == 0) ctl->wave_cnt[wave] = cnt;
-        __syncthreads();
-        int total = 0;
-        bool fits = true;
-#pragma unroll
-        for (int wv = 0; wv < kWaves; ++wv) {
-            const int n = ctl->wave_cnt[wv];
-            total += n;
-            fits = fits && n <= kWaveKeep;
-        }
-        if (fits && total <= kFoldFast) {
-            if (wave == 0) {
-                int at = 0;
-                for (int wv = 0; wv < kWaves; ++wv) {
-                    const int n = ctl->wave_cnt[wv];
-                    for (int t = lane; t < n; t += kWave) cand[at + t] = stage[wv * kWaveKeep + t];
-                    at += n;
-                }
-                wave_sync();
-                wave_rank_select<kFoldFast>(cand, total, K, sorted, lane);
-                for (int t = lane; t < K; t += kWave) {
-                    const uint64_t key = sorted[t];
-                    a.out_ids[(size_t)q * K + t] = id_of_key(key);
-                    a.out_scores[(size_t)q * K + t] = score_of_key(key);
-                }
-            }
-            return;
-        }
-        __syncthreads();                                      // everyone has read the counts before they are reused
     }
     for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
     float lo, scale;
