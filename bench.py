@@ -18,6 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+LDS_PEAK_GBS = 128 * 256 * 2.4   # 128 B/clk/CU x 256 CUs x 2.4 GHz: what the LDS can return per second
 
 
 def cpu_baseline(G, cent, Q, K, budget_s=12.0):
@@ -135,6 +136,13 @@ def main():
                      "kernel": "catalogue scan (Eq. 5 + per-workgroup top-K)", "kernel_ms": scan_ms,
                      "algorithmic_bytes_per_launch": algo_bytes},
     }
+    if B > 1:
+        # a batch re-uses every code byte B times: the table lookups (4 bytes gathered from LDS per split, item and
+        # query), not HBM, bound the scan; reported beside the HBM figure, against what the LDS can return at best
+        lds_bytes = 4.0 * m * N * B
+        out["lds_gather"] = {"bound": "lds", "achieved": lds_bytes / (scan_ms * 1e-3) / 1e9, "peak": LDS_PEAK_GBS,
+                             "unit": "GB/s", "frac": lds_bytes / (scan_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
+                             "algorithmic_bytes_per_launch": lds_bytes}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(G, cent, Q, K)
     print(json.dumps(out))
