@@ -202,6 +202,53 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float
     }
 }
 
+// Eq. 4 for batches.  A workgroup (one wave) serves 64 sub-ids of ONE split and a tile of queries, so the query
+// chunk it multiplies with is the same for all its lanes (read through the scalar cache), and it runs the chains of
+// kSubInterleave queries side by side: the chains are independent, which hides the latency of each chain's
+// dependent multiply-adds.  Per query the arithmetic is the same left-to-right chain from +0 as above.
+constexpr int kSubInterleave = 8;     // queries whose chains run interleaved
+constexpr int kSubBatchTile = 8;      // queries per workgroup
+
+template <int S_ELEMS>   // d/m, a multiple of 4
+__global__ __launch_bounds__(kSubThreads) void subitem_scores_batched_kernel(const float* __restrict__ queries,
+                                                                             const float* __restrict__ centroids,
+                                                                             float* __restrict__ S, int B, int d, int m, int b) {
+    const int jblocks = (b + kSubThreads - 1) / kSubThreads;
+    const int k = blockIdx.x / jblocks;                              // the same for the whole workgroup
+    const int j = (blockIdx.x % jblocks) * kSubThreads + threadIdx.x;
+    const bool live = j < b;
+    const int kj = k * b + (live ? j : 0);
+    const float4* psi4 = reinterpret_cast<const float4*>(centroids + (size_t)kj * S_ELEMS);
+    const int q0 = blockIdx.y * kSubBatchTile;
+    int q1 = q0 + kSubBatchTile;
+    if (q1 > B) q1 = B;
+    for (int q = q0; q < q1; q += kSubInterleave) {
+        const float4* phi4[kSubInterleave];
+        float acc[kSubInterleave];
+#pragma unroll
+        for (int i = 0; i < kSubInterleave; ++i) {
+            const int qi = (q + i < q1) ? q + i : q1 - 1;            // past the tile: a repeat, computed and not stored
+            phi4[i] = reinterpret_cast<const float4*>(queries + (size_t)qi * d + (size_t)k * S_ELEMS);
+            acc[i] = 0.0f;
+        }
+#pragma unroll 4
+        for (int t4 = 0; t4 < S_ELEMS / 4; ++t4) {                   // four elements of every chain per step
+            const float4 wv = psi4[t4];
+#pragma unroll
+            for (int i = 0; i < kSubInterleave; ++i) {
+                const float4 pv = phi4[i][t4];
+                acc[i] = __builtin_fmaf(wv.x, pv.x, acc[i]);
+                acc[i] = __builtin_fmaf(wv.y, pv.y, acc[i]);
+                acc[i] = __builtin_fmaf(wv.z, pv.z, acc[i]);
+                acc[i] = __builtin_fmaf(wv.w, pv.w, acc[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kSubInterleave; ++i)
+            if (live && q + i < q1) S[(size_t)(q + i) * m * b + kj] = acc[i];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // Small per-workgroup control block in LDS.
 struct Ctl {
@@ -1650,6 +1697,15 @@ int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids,
 
 template <int S_ELEMS>
 void launch_subitem(const float* queries, const float* centroids, float* S, int B, int d, int m, int b, hipStream_t st) {
+    if constexpr (S_ELEMS > 0 && S_ELEMS % 4 == 0) {
+        // batches: the interleaved kernel (it needs 16-byte aligned rows of queries and centroids)
+        if (B >= kSubInterleave && (((uintptr_t)queries | (uintptr_t)centroids) & 15) == 0 && d % 4 == 0) {
+            dim3 grid(m * ((b + kSubThreads - 1) / kSubThreads), (B + kSubBatchTile - 1) / kSubBatchTile);
+            hipLaunchKernelGGL(subitem_scores_batched_kernel<S_ELEMS>, grid, dim3(kSubThreads), 0, st, queries, centroids, S,
+                               B, d, m, b);
+            return;
+        }
+    }
     dim3 grid((m * b + kSubThreads - 1) / kSubThreads, (B + kSubQueryTile - 1) / kSubQueryTile);
     hipLaunchKernelGGL(subitem_scores_kernel<S_ELEMS>, grid, dim3(kSubThreads), 0, st, queries, centroids, S, B, d, m, b);
 }
