@@ -172,6 +172,47 @@ int pq_oracle_score_topk(const uint8_t* codes, const float* S, long long N, int 
     return rc;
 }
 
+/* Algorithm 1 with a candidate list V (its optional argument, Section 3): for every query, score only the items
+ * whose ids are listed in subset[0..n) (each id in [0, N), no id listed twice), then TopK among them under the same
+ * order (score descending, lower ITEM ID first).  One candidate list serves all B queries.  The loop is the
+ * algorithm's own: for each listed item, the sum over splits of S[k][G[item][k]] from the k = 0 term on. */
+int pq_oracle_score_topk_subset(const uint8_t* codes, const float* S, const int* subset, long long n, long long N,
+                                int B, int m, int b, int K, int* out_ids, float* out_scores) {
+    if (!codes || !S || !subset || !out_ids || !out_scores || n < 1 || N < 1 || B < 1 || m < 1 || b < 1 || b > 256 ||
+        K < 1 || K > n || N >= 2147483648LL)
+        return -1;
+    for (long long p = 0; p < n; ++p)
+        if (subset[p] < 0 || subset[p] >= N) return -1;
+    for (int q = 0; q < B; ++q) {
+        const float* Sq = S + (size_t)q * m * b;
+        int* ids = out_ids + (size_t)q * K;
+        float* scs = out_scores + (size_t)q * K;
+        int kept = 0;
+        for (long long p = 0; p < n; ++p) {
+            const long long item = subset[p];
+            const uint8_t* row = codes + (size_t)item * m;
+            if (row[0] >= b) return -1;
+            float acc = Sq[row[0]];
+            for (int k = 1; k < m; ++k) {
+                if (row[k] >= b) return -1;
+                acc = acc + Sq[(size_t)k * b + row[k]];
+            }
+            const float sc = acc + 0.0f;                       /* a sum of -0 counts as +0 */
+            if (kept == K && !ranks_before(sc, item, scs[K - 1], ids[K - 1])) continue;
+            int pos = (kept < K) ? kept : K - 1;
+            while (pos > 0 && ranks_before(sc, item, scs[pos - 1], ids[pos - 1])) {
+                scs[pos] = scs[pos - 1];
+                ids[pos] = ids[pos - 1];
+                --pos;
+            }
+            scs[pos] = sc;
+            ids[pos] = (int)item;
+            if (kept < K) ++kept;
+        }
+    }
+    return 0;
+}
+
 /* The whole path from embeddings: Eq. 4, then Algorithm 1. */
 int pq_oracle_pqtopk(const uint8_t* codes, const float* centroids, const float* queries,
                      long long N, int B, int d, int m, int b, int K, int* out_ids, float* out_scores) {

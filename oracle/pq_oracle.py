@@ -41,6 +41,7 @@ def _load():
         lib.pq_oracle_topk_fullsort.argtypes = [P, LL, I, P, P]
         lib.pq_oracle_topk.argtypes = [P, LL, I, P, P]
         lib.pq_oracle_score_topk.argtypes = [P, P, LL, I, I, I, I, P, P]
+        lib.pq_oracle_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P]
         lib.pq_oracle_pqtopk.argtypes = [P, P, P, LL, I, I, I, I, I, P, P]
         lib.pq_oracle_bruteforce_topk.argtypes = [P, P, P, LL, I, I, I, I, I, P, P]
         _lib = lib
@@ -117,6 +118,22 @@ def score_topk(codes: np.ndarray, S: np.ndarray, K: int) -> Tuple[np.ndarray, np
     ids = np.empty((B, K), dtype=np.int32)
     sc = np.empty((B, K), dtype=np.float32)
     _check(_load().pq_oracle_score_topk(_p(codes), _p(S), N, B, m, b, K, _p(ids), _p(sc)), "score_topk")
+    return ids, sc
+
+
+def score_topk_subset(codes: np.ndarray, S: np.ndarray, subset: np.ndarray, K: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 1 with a candidate list V (distinct item ids, shared by the batch) -> (ids [B][K], scores [B][K])."""
+    codes = _c(codes, np.uint8)
+    S = _c(S, np.float32)
+    subset = _c(subset, np.int32)
+    N, m = codes.shape
+    B, m2, b = S.shape
+    if m2 != m:
+        raise ValueError("S does not match m")
+    ids = np.empty((B, K), dtype=np.int32)
+    sc = np.empty((B, K), dtype=np.float32)
+    _check(_load().pq_oracle_score_topk_subset(_p(codes), _p(S), _p(subset), subset.shape[0], N, B, m, b, K, _p(ids),
+                                                _p(sc)), "score_topk_subset")
     return ids, sc
 
 

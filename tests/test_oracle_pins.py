@@ -392,3 +392,68 @@ def test_argument_errors(oracle):
         oracle.score_topk(G, S, 1)                 # sub-id out of range for b = 4
     with pytest.raises(ValueError):
         oracle.subitem_scores(np.zeros((1, 5), np.float32), np.zeros((2, 4, 2), np.float32))
+
+
+# ---------------------------------------------------------------- Algorithm 1 with a candidate list V (its optional argument)
+
+def _subset_case(seed, N=3000, m=4, b=16, B=2):
+    G = W.codes_uniform(N, m, b, seed=seed)
+    S = W.normal_f32(W.stream_key(seed, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+    return G, S
+
+
+def test_subset_of_everything_is_the_full_scan(oracle):
+    G, S = _subset_case(11)
+    ids, sc = oracle.score_topk_subset(G, S, np.arange(G.shape[0], dtype=np.int32), 25)
+    fid, fsc = oracle.score_topk(G, S, 25)
+    assert np.array_equal(ids, fid) and np.array_equal(sc.view(np.uint32), fsc.view(np.uint32))
+
+
+def test_subset_matches_masked_full_scores(oracle):
+    """Definition check with numpy: score every item (pinned elsewhere), keep the listed ones, sort by
+    (score descending, item id ascending)."""
+    rng = np.random.default_rng(5)
+    for seed in range(6):
+        G, S = _subset_case(20 + seed, N=2000 + 37 * seed, m=(1, 2, 3, 4, 8, 5)[seed], b=(16, 4, 7, 256, 16, 2)[seed])
+        N = G.shape[0]
+        for n in (1, 7, 500, N):
+            V = rng.permutation(N)[:n].astype(np.int32)
+            K = min(n, 12)
+            ids, sc = oracle.score_topk_subset(G, S, V, K)
+            for q in range(S.shape[0]):
+                full = oracle.item_scores(G, S[q])
+                order = np.lexsort((V, -full[V].astype(np.float64)))[:K]
+                assert np.array_equal(ids[q], V[order])
+                assert np.array_equal(sc[q].view(np.uint32), (full[V][order] + np.float32(0)).view(np.uint32))
+
+
+def test_subset_order_of_the_list_does_not_matter(oracle):
+    G, S = _subset_case(31, b=3)                   # coarse tables: many exact ties, decided by item id
+    rng = np.random.default_rng(6)
+    V = rng.permutation(G.shape[0])[:800].astype(np.int32)
+    a = oracle.score_topk_subset(G, S, V, 40)
+    b2 = oracle.score_topk_subset(G, S, np.sort(V), 40)
+    c = oracle.score_topk_subset(G, S, V[::-1].copy(), 40)
+    for x in (b2, c):
+        assert np.array_equal(a[0], x[0]) and np.array_equal(a[1].view(np.uint32), x[1].view(np.uint32))
+
+
+def test_subset_that_holds_the_full_top_k_returns_it(oracle):
+    G, S = _subset_case(41, N=5000, m=8, b=256, B=1)
+    fid, fsc = oracle.score_topk(G, S, 10)
+    rng = np.random.default_rng(7)
+    others = np.setdiff1d(rng.permutation(5000)[:300], fid[0])
+    V = np.concatenate([others, fid[0]]).astype(np.int32)
+    ids, sc = oracle.score_topk_subset(G, S, V, 10)
+    assert np.array_equal(ids, fid) and np.array_equal(sc.view(np.uint32), fsc.view(np.uint32))
+    # and without the best item, everything moves up by one
+    ids2, _ = oracle.score_topk_subset(G, S, V[V != fid[0, 0]], 9)
+    assert np.array_equal(ids2[0], fid[0, 1:])
+
+
+def test_subset_rejects_bad_lists(oracle):
+    G, S = _subset_case(51)
+    with pytest.raises(Exception):
+        oracle.score_topk_subset(G, S, np.array([0, G.shape[0]], dtype=np.int32), 1)
+    with pytest.raises(Exception):
+        oracle.score_topk_subset(G, S, np.array([0, 1], dtype=np.int32), 3)
