@@ -82,6 +82,31 @@ int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int 
                   int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Bytes of device workspace pq_score_topk_subset() needs for a candidate list of n_subset items.  Pure host
+ * arithmetic, no HIP call.  Returns 0 for arguments pq_score_topk_subset() would reject.
+ */
+size_t pq_score_topk_subset_workspace_bytes(long long n_subset, int B, int m, int b, int K);
+
+/*
+ * Algorithm 1 with its optional argument V, a list of candidate items (Section 3): for each of B queries, score
+ * only the items named in `subset` by Eq. 5 and return the K best <item id, score> pairs among them.  The list is
+ * shared by the whole batch.  The rows G[V] are gathered from `codes` in place: no sub-matrix is materialised.
+ *   codes       in   uint8 [N][m]        codebook G (Eq. 1) of the whole catalogue
+ *   S           in   float [B][m][b]
+ *   subset      in   int32 [n_subset]    item ids in [0, N), pairwise distinct, in any order (device pointer,
+ *                                        4-byte aligned); the result does not depend on their order
+ *   out_ids     out  int32 [B][K]        item ids (not positions in the list); score descending, id ascending
+ *   out_scores  out  float [B][K]
+ *   workspace        at least pq_score_topk_subset_workspace_bytes(n_subset, B, m, b, K) bytes, 16-byte aligned
+ * The ids in the list cannot be checked on the host.  An id outside [0, N) is read as item N-1 (never out of
+ * bounds); with such an id, or with a repeated id, the result is unspecified.
+ * Errors: as pq_score_topk(), with PQ_ERR_SHAPE also for K > n_subset or n_subset > N.
+ */
+int pq_score_topk_subset(const uint8_t* codes, const float* S, const int* subset, long long n_subset, long long N,
+                         int B, int m, int b, int K, int* out_ids, float* out_scores, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid: enqueues the catalogue scan kernel of pq_score_topk() (the kernel that streams `codes`) once
  * untimed and then `iters` times back to back between two HIP events on `stream`, enqueues the fold so the outputs
  * are those of pq_score_topk(), waits for the stream, and stores elapsed / iters in milliseconds in *scan_ms (host

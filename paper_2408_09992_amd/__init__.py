@@ -5,11 +5,12 @@ C-ABI library on first use and raise if it has not been built (there is no CPU f
 """
 from __future__ import annotations
 
-__all__ = ["workloads", "pq_subitem_scores", "pq_score_topk", "pq_score_topk_workspace_bytes", "pq_strerror"]
+__all__ = ["workloads", "pq_subitem_scores", "pq_score_topk", "pq_score_topk_workspace_bytes", "pq_score_topk_subset",
+           "pq_score_topk_subset_workspace_bytes", "pq_strerror"]
 
 
 def __getattr__(name):
-    if name in ("pq_subitem_scores", "pq_score_topk", "pq_score_topk_workspace_bytes", "pq_strerror"):
+    if name in __all__[1:]:
         from . import binding
         return getattr(binding, name)
     if name in ("workloads", "binding", "build"):

@@ -43,6 +43,10 @@ def lib() -> ctypes.CDLL:
         L.pq_score_topk.restype = I
         L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
         L.pq_score_topk_profile.restype = I
+        L.pq_score_topk_subset_workspace_bytes.argtypes = [LL, I, I, I, I]
+        L.pq_score_topk_subset_workspace_bytes.restype = SZ
+        L.pq_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P, P, SZ, P]
+        L.pq_score_topk_subset.restype = I
         L.pq_strerror.argtypes = [I]
         L.pq_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -113,6 +117,39 @@ def pq_score_topk(codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optio
                              out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
     if rc != PQ_OK:
         raise PQError(rc, "pq_score_topk")
+    return out_ids, out_scores
+
+
+def pq_score_topk_subset_workspace_bytes(n_subset: int, B: int, m: int, b: int, K: int) -> int:
+    return int(lib().pq_score_topk_subset_workspace_bytes(n_subset, B, m, b, K))
+
+
+def pq_score_topk_subset(codes: torch.Tensor, S: torch.Tensor, subset: torch.Tensor, K: int,
+                         workspace: Optional[torch.Tensor] = None, out_ids: Optional[torch.Tensor] = None,
+                         out_scores: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Algorithm 1 with a candidate list V: subset int32 [n] of distinct item ids -> the K best items of the list."""
+    _dev(codes, torch.uint8, "codes")
+    _dev(S, torch.float32, "S")
+    _dev(subset, torch.int32, "subset")
+    N, m = codes.shape
+    B, m2, b = S.shape
+    if m2 != m or subset.dim() != 1:
+        raise PQError(PQ_ERR_SHAPE, "pq_score_topk_subset")
+    n = subset.numel()
+    if workspace is None:
+        need = pq_score_topk_subset_workspace_bytes(n, B, m, b, K)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=codes.device)
+    if out_ids is None:
+        out_ids = torch.empty((B, K), dtype=torch.int32, device=codes.device)
+    if out_scores is None:
+        out_scores = torch.empty((B, K), dtype=torch.float32, device=codes.device)
+    _dev(out_ids, torch.int32, "out_ids")
+    _dev(out_scores, torch.float32, "out_scores")
+    rc = lib().pq_score_topk_subset(codes.data_ptr(), S.data_ptr(), subset.data_ptr(), n, N, B, m, b, K,
+                                    out_ids.data_ptr(), out_scores.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_score_topk_subset")
     return out_ids, out_scores
 
 

@@ -579,6 +579,8 @@ struct ScanArgs {
     int candmax;         // keys of the exact-selection candidate array
     int prune_at;        // wave list length that triggers a tightening (0: only when full)
     uint64_t* ws_keys;   // [B][nblk][K]
+    const int* subset;   // candidate list V (generic kernel only): unit p stands for item subset[p]; nullptr: V = I
+    uint32_t n_items;    // items in the catalogue (bounds the ids read from `subset`)
     int checkpoint_factor;   // batched kernel: growth of the number of rounds between workgroup checkpoints (>= 2)
 };
 
@@ -695,8 +697,17 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
     } else {
 #pragma unroll
         for (int u = 0; u < kGenericItemsPerThread; ++u) {
-            const uint32_t item = unit_of<M, NT>(rr, u, nblk, blk, tid);
-            sc[u] = (item < n_units) ? score_row(lut, a.codes + (size_t)item * a.m, a.m) : 0.0f;
+            const uint32_t unit = unit_of<M, NT>(rr, u, nblk, blk, tid);
+            float v = 0.0f;
+            if (unit < n_units) {
+                uint32_t item = unit;
+                if (a.subset) {                                // an id past the catalogue is clamped: never out of bounds
+                    item = (uint32_t)a.subset[unit];
+                    item = item < a.n_items ? item : a.n_items - 1;
+                }
+                v = score_row(lut, a.codes + (size_t)item * a.m, a.m);
+            }
+            sc[u] = v;
         }
     }
 }
@@ -785,6 +796,16 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
 
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
 
+    // item id of a scanned unit (they differ only under a candidate list)
+    auto id_of = [&](uint32_t unit) -> uint32_t {
+        if constexpr (M == 0) {
+            if (a.subset) {
+                const uint32_t item = (uint32_t)a.subset[unit];
+                return item < a.n_items ? item : a.n_items - 1;
+            }
+        }
+        return unit;
+    };
     // what a round's scores offer to the wave's list: everything at or above its floor
     auto offer = [&](const float (&sc)[kItems], uint32_t rr, int vt) {
         float best = sc[0];
@@ -797,7 +818,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             const uint32_t item = item_of_slot<M, NT>(rr, nblk, blk, vt, e);
             const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], item, lane);
+            if (mask != 0) top.append(mask, take, sc[e], take ? id_of(item) : 0u, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
     };
@@ -834,7 +855,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             const uint32_t item = item_of_slot<M, NT>(r, nblk, blk, tid, e);
             const bool take = item < n_scan && bk[e] >= bstar;
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], item, lane);
+            if (mask != 0) top.append(mask, take, sc[e], take ? id_of(item) : 0u, lane);
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
         r += 1;
@@ -1546,9 +1567,10 @@ struct ScanPlan {
 
 bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16; }
 
-ScanPlan make_plan(long long N, int B, int m, int K) {
+// `generic`: plan for the generic kernel whatever m is (candidate-list scans use it: their rows are gathered)
+ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     ScanPlan p;
-    p.vec = is_vec_m(m) && N * m >= 16;                        // (the vector kernels need one whole code vector at least)
+    p.vec = !generic && is_vec_m(m) && N * m >= 16;            // (the vector kernels need one whole code vector at least)
     const long long units = p.vec ? (N * m) / 16 : N;          // whole code vectors (the few items after them are extra)
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
@@ -1586,7 +1608,7 @@ ScanPlan make_plan(long long N, int B, int m, int K) {
     p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.copies > 1 ? kMaxWaves : kWaves);
     p.scan_lds = p.scan_dyn_lds + ((p.vec && p.copies == 1) ? (size_t)m * kLutStride * sizeof(float) : 0);
     p.tiled = false;
-    if (B >= 2 && (m == 8 || m == 16) && N * m >= 16) {       // batched kernel, if its tables and lists fit in LDS
+    if (!generic && B >= 2 && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
         if (all <= kMaxLdsBytes) {
@@ -1652,10 +1674,12 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
 }
 
 // Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
+// `subset` / `n_items`: candidate list (then N is its length and the plan is a generic one) or nullptr / N
 int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                 void* workspace, hipStream_t st) {
+                 void* workspace, hipStream_t st, const int* subset = nullptr, long long n_items = 0) {
     ScanArgs a;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
+    a.subset = subset; a.n_items = (uint32_t)(subset ? n_items : N);
     a.checkpoint_factor = K > 28 ? 2 : 8;                  // small K: the waves' own pruning already keeps floors tight
     a.cap = p.cap; a.candmax = p.candmax;
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
@@ -1777,11 +1801,41 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
     return rc;
 }
 
+size_t pq_score_topk_subset_workspace_bytes(long long n_subset, int B, int m, int b, int K) {
+    if (n_subset < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > n_subset || n_subset >= 2147483648LL) return 0;
+    if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return 0;
+    const ScanPlan p = make_plan(n_subset, B, m, K, true);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
+    return workspace_bytes(p, B, K);
+}
+
+int pq_score_topk_subset(const uint8_t* codes, const float* S, const int* subset, long long n_subset, long long N,
+                         int B, int m, int b, int K, int* out_ids, float* out_scores, void* workspace,
+                         size_t workspace_bytes_given, void* stream) {
+    if (!codes || !S || !subset || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
+    if (n_subset < 1 || N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > n_subset || n_subset > N ||
+        N >= 2147483648LL)
+        return PQ_ERR_SHAPE;
+    if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
+    const ScanPlan p = make_plan(n_subset, B, m, K, true);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)codes & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)S & 3) || ((uintptr_t)subset & 3) ||
+        ((uintptr_t)out_ids & 3) || ((uintptr_t)out_scores & 3))
+        return PQ_ERR_ALIGN;
+    if (workspace_bytes_given < workspace_bytes(p, B, K)) return PQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = enqueue_scan(p, codes, S, n_subset, B, m, b, K, workspace, st, subset, N);
+    if (rc != PQ_OK) return rc;
+    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+}
+
 const char* pq_strerror(int code) {
     switch (code) {
         case PQ_OK: return "ok";
         case PQ_ERR_NULL: return "a required pointer is NULL";
-        case PQ_ERR_SHAPE: return "bad shape: need B,d,m,b,K,N >= 1, d % m == 0, b <= 256, K <= N, N < 2^31";
+        case PQ_ERR_SHAPE:
+            return "bad shape: need B,d,m,b,K,N >= 1, d % m == 0, b <= 256, K <= N (K <= |V| <= N with a candidate list), "
+                   "N < 2^31";
         case PQ_ERR_UNSUPPORTED:
             return "unsupported: K > 512, m > 128, B > 65535, or score tables plus candidate lists exceed LDS";
         case PQ_ERR_WORKSPACE: return "workspace smaller than pq_score_topk_workspace_bytes()";

@@ -39,6 +39,7 @@ STREAM_ZIPF_PERM = 4
 STREAM_DUP_MASK = 5
 STREAM_DUP_SRC = 6
 STREAM_PLANT = 7
+STREAM_CANDIDATES = 8
 
 _CHUNK = 1 << 22  # u64 draws per temporary block
 
@@ -188,6 +189,16 @@ def plant_ids(N: int, count: int, seed: int = 0) -> np.ndarray:
                     break
         start += 2 * count
     return np.sort(np.asarray(got, dtype=np.int64))
+
+
+def candidate_list(N: int, count: int, seed: int = 0, ascending: bool = False) -> np.ndarray:
+    """Candidate list V for Algorithm 1: `count` distinct seeded item ids in [0, N) as int32, in a seeded random
+    order (or ascending).  Drawn as the first `count` entries of a seeded permutation of the catalogue."""
+    if count > N:
+        raise ValueError("count > N")
+    key = stream_key(seed, STREAM_CANDIDATES)
+    order = np.argsort(u64_at(key, 0, N), kind="stable")[:count].astype(np.int32)
+    return np.sort(order) if ascending else order
 
 
 def plant_rows(codes: np.ndarray, ids: np.ndarray, row: np.ndarray) -> np.ndarray:

@@ -21,6 +21,9 @@ def lib(pqlib_path):
     L.pq_score_topk_workspace_bytes.restype = SZ
     L.pq_score_topk.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
     L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, P]
+    L.pq_score_topk_subset_workspace_bytes.argtypes = [LL, I, I, I, I]
+    L.pq_score_topk_subset_workspace_bytes.restype = SZ
+    L.pq_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P, P, SZ, P]
     L.pq_strerror.argtypes = [I]
     L.pq_strerror.restype = ctypes.c_char_p
     return L
@@ -112,6 +115,38 @@ def test_score_topk_argument_errors(lib):
     out = ctypes.c_float(0)
     assert g(p, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 0, ctypes.addressof(out)) == SHAPE
     assert g(None, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 3, ctypes.addressof(out)) == NULL
+
+
+def test_score_topk_subset_argument_errors(lib):
+    f = lib.pq_score_topk_subset
+    ws = lib.pq_score_topk_subset_workspace_bytes
+    p = 0x10000
+    big = 1 << 30
+    good = dict(codes=p, S=p, sub=p, n=500, N=1000, B=1, m=8, b=256, K=10, ids=p, sc=p, ws=p, wsb=big, st=None)
+
+    def call(**kw):
+        a = dict(good, **kw)
+        return f(a["codes"], a["S"], a["sub"], a["n"], a["N"], a["B"], a["m"], a["b"], a["K"], a["ids"], a["sc"],
+                 a["ws"], a["wsb"], a["st"])
+
+    for name in ("codes", "S", "sub", "ids", "sc", "ws"):
+        assert call(**{name: None}) == NULL, name
+    assert call(n=0) == SHAPE and call(N=0) == SHAPE and call(B=0) == SHAPE and call(m=0) == SHAPE
+    assert call(b=0) == SHAPE and call(b=257) == SHAPE and call(K=0) == SHAPE
+    assert call(K=501) == SHAPE                                       # K exceeds the list, not the catalogue
+    assert call(n=1001) == SHAPE                                      # a list of distinct ids cannot exceed N
+    assert call(N=2 ** 31) == SHAPE
+    assert call(n=10 ** 5, N=10 ** 6, K=513) == UNSUPPORTED and call(m=129) == UNSUPPORTED
+    assert call(B=65536) == UNSUPPORTED
+    assert call(codes=p + 8) == ALIGN and call(sub=p + 2) == ALIGN and call(ws=p + 4) == ALIGN
+    assert call(ids=p + 1) == ALIGN and call(sc=p + 3) == ALIGN and call(S=p + 2) == ALIGN
+    need = ws(500, 1, 8, 256, 10)
+    assert need > 0 and need % 16 == 0
+    assert call(wsb=need - 1) == WORKSPACE
+    assert ws(100_000, 3, 8, 256, 100) >= 3 * 100 * 8
+    for bad in ((0, 1, 8, 256, 1), (10, 1, 8, 256, 11), (10, 0, 8, 256, 1), (10, 1, 0, 256, 1), (10, 1, 8, 257, 1),
+                (2 ** 31, 1, 8, 256, 10), (10 ** 6, 1, 8, 256, 513), (10 ** 6, 1, 129, 256, 10)):
+        assert ws(*bad) == 0, bad
 
 
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):

@@ -182,6 +182,66 @@ def test_errors_reach_python(pq):
     assert e.value.code == pq.PQ_ERR_WORKSPACE
 
 
+# ---------------------------------------------------------------- Algorithm 1 with a candidate list V
+
+def assert_same_subset_topk(pq, oracle, G, S, V, K, tag=""):
+    print(f"case {tag} N={G.shape[0]} |V|={V.shape[0]} m={G.shape[1]} B={S.shape[0]} b={S.shape[2]} K={K}", flush=True)
+    ids, sc = pq.pq_score_topk_subset(dev(G), dev(S), dev(V), K)
+    torch.cuda.synchronize()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    rid, rsc = oracle.score_topk_subset(G, S, V, K)
+    assert np.array_equal(ids, rid), tag
+    check_scores(sc, rsc)
+    assert np.array_equal(sc.view(np.uint32), rsc.view(np.uint32)), tag
+    return ids, sc
+
+
+@pytest.mark.parametrize("m", [1, 3, 4, 8, 16, 64])
+def test_subset_small_shapes(pq, oracle, m):
+    for N in (1, 5, 64, 1000, 70_001):
+        for b in (256, 16):
+            G = W.codes_uniform(N, m, b, seed=N + m)
+            for B in (1, 3):
+                S = W.normal_f32(W.stream_key(N + m, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+                for n in sorted({1, min(N, 2), min(N, 65), min(N, 2049), min(N, 20_000), N}):
+                    V = W.candidate_list(N, n, seed=n)
+                    for K in sorted({1, min(n, 10), min(n, 100)}):
+                        assert_same_subset_topk(pq, oracle, G, S, V, K, "subset-small")
+
+
+def test_subset_of_the_large_catalogue(pq, oracle, large_codes):
+    cfg = W.CONFIGS["large"]
+    cent, Q = W.centroids(cfg.m, cfg.b, cfg.d, cfg.seed), W.queries(3, cfg.d, cfg.seed)
+    S = pq.pq_subitem_scores(dev(Q), dev(cent)).cpu().numpy()
+    full_ids, _ = oracle.score_topk(large_codes, S, cfg.K)
+    for n, K in ((10, 10), (1000, 10), (100_000, 10), (100_000, 512), (1_000_000, 100), (1_280_000, 10)):
+        V = W.candidate_list(cfg.N, n, seed=n, ascending=(n == 1_000_000))
+        ids, _ = assert_same_subset_topk(pq, oracle, large_codes, S, V, K, "subset-large")
+        if n == cfg.N:                                     # V = I in a shuffled order: the full scan's answer
+            assert np.array_equal(ids, full_ids)
+
+
+def test_subset_ties_go_to_the_lower_item_id(pq, oracle):
+    # every item scores the same: the K lowest ITEM ids of the list win, wherever they sit in it
+    N, m, K = 50_000, 8, 20
+    G = np.zeros((N, m), dtype=np.uint8)
+    S = np.ones((2, m, 256), dtype=np.float32)
+    V = W.candidate_list(N, 7001, seed=3)
+    ids, _ = assert_same_subset_topk(pq, oracle, G, S, V, K, "subset-ties")
+    assert ids[0].tolist() == np.sort(V)[:K].tolist()
+
+
+def test_subset_errors_reach_python(pq):
+    G = dev(W.codes_uniform(100, 8))
+    S = dev(np.zeros((1, 8, 256), dtype=np.float32))
+    V = dev(np.arange(50, dtype=np.int32))
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_score_topk_subset(G, S, V, 51)
+    assert e.value.code == pq.PQ_ERR_SHAPE
+    with pytest.raises(ValueError):
+        pq.pq_score_topk_subset(G, S, V.to(torch.int64), 10)
+
+
 # ---------------------------------------------------------------- the named configurations at full size
 
 def end_to_end(pq, oracle, cfg, B, G=None):
