@@ -420,6 +420,7 @@ struct WaveTopK {
 };
 
 constexpr int kFastCand = 128;   // keys one wave can rank on its own (two per lane)
+constexpr int kFilterMin = 64;   // single-query scan: final candidate sets larger than this are first cut by a floor
 
 // One wave: sorted exact K best of the T <= MAXT keys in c[] (LDS; c has room for T rounded up to a multiple of 8,
 // zeros allowed anywhere and ignored), written to dst[0..K) (LDS, zero where fewer than K exist).  More than 64 keys
@@ -479,25 +480,41 @@ __device__ __forceinline__ void wave_rank_select(uint64_t* c, int T, int K, uint
 
 // Sorted exact K best of the C candidates in cand[] by counting: the position of a key is the number of candidates
 // that beat it.  cand must have room for C rounded up to a multiple of 8 (the pad is zeroed here; a zero beats
-// nothing).  dst[0..K) is zero-filled where fewer than K exist.
+// nothing).  dst[0..K) is zero-filled where fewer than K exist.  When the workgroup has four threads per candidate,
+// four adjacent lanes share a key and each counts over a quarter of the candidates: the loop is bound by the latency
+// of its LDS reads, so a shorter loop per thread is what makes it faster.
 template <int NT = kThreads>
 __device__ void rank_select(uint64_t* cand, int C, int K, uint64_t* dst, int tid) {
     const int C8 = (C + 7) & ~7;
     for (int i = tid; i < K; i += NT) dst[i] = 0;
     if (tid < C8 - C) cand[C + tid] = 0;
     __syncthreads();
-    for (int t = tid; t < C; t += NT) {
-        const uint64_t mine = cand[t];
-        int rank = 0;
-        for (int u = 0; u < C8; u += 8) {
-            const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(cand + u);
-            const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(cand + u + 2);
-            const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(cand + u + 4);
-            const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(cand + u + 6);
-            rank += (p0.x > mine) + (p0.y > mine) + (p1.x > mine) + (p1.y > mine) + (p2.x > mine) + (p2.y > mine) +
-                    (p3.x > mine) + (p3.y > mine);
+    auto count8 = [&](int u, uint64_t mine) -> int {
+        const ulonglong2 p0 = *reinterpret_cast<const ulonglong2*>(cand + u);
+        const ulonglong2 p1 = *reinterpret_cast<const ulonglong2*>(cand + u + 2);
+        const ulonglong2 p2 = *reinterpret_cast<const ulonglong2*>(cand + u + 4);
+        const ulonglong2 p3 = *reinterpret_cast<const ulonglong2*>(cand + u + 6);
+        return (p0.x > mine) + (p0.y > mine) + (p1.x > mine) + (p1.y > mine) + (p2.x > mine) + (p2.y > mine) +
+               (p3.x > mine) + (p3.y > mine);
+    };
+    if (C8 * 4 <= NT) {
+        const int t = tid >> 2, part = tid & 3;              // (C8 is a multiple of 8: a wave is all in or all out)
+        if (t < C8) {
+            const uint64_t mine = cand[t];
+            uint32_t rank = 0;
+#pragma unroll 2
+            for (int u = part * 8; u < C8; u += 32) rank += (uint32_t)count8(u, mine);
+            rank += dpp_u32<kDppQuadSwap1>(0u, rank);
+            rank += dpp_u32<kDppQuadSwap2>(0u, rank);
+            if (part == 0 && mine != 0ull && rank < (uint32_t)K) dst[rank] = mine;
         }
-        if (rank < K) dst[rank] = mine;
+    } else {
+        for (int t = tid; t < C; t += NT) {
+            const uint64_t mine = cand[t];
+            int rank = 0;
+            for (int u = 0; u < C8; u += 8) rank += count8(u, mine);
+            if (rank < K) dst[rank] = mine;
+        }
     }
     __syncthreads();
 }
@@ -663,14 +680,14 @@ __device__ __forceinline__ uint32_t unit_of(uint32_t rr, int u, int nblk, int bl
 // branch, so the compiler knows how many loads are outstanding at any point and lets several rounds stay in
 // flight.  A clamped vector's items are masked out by the caller.
 template <int M, int NT = kThreads>
-__device__ __forceinline__ void load_round(const ScanArgs& a, uint32_t rr, int nblk, int blk, uint32_t last_vec, int tid,
-                                           uint32_t (&w)[Round<M>::kWords]) {
+__device__ __forceinline__ void load_round(const ScanArgs& a, uint32_t rr, int nblk, int blk, uint32_t last_vec,
+                                           uint32_t spare_vec, int tid, uint32_t (&w)[Round<M>::kWords]) {
     if constexpr (M > 0) {
         const uint4* base = reinterpret_cast<const uint4*>(a.codes);
 #pragma unroll
         for (int u = 0; u < Round<M>::kVecs; ++u) {
             uint32_t v = unit_of<M, NT>(rr, u, nblk, blk, tid);
-            v = v < last_vec ? v : last_vec;
+            v = v <= last_vec ? v : spare_vec;
             const uint4 x = base[v];
             w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
         }
@@ -754,7 +771,13 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     const int blk = blockIdx.x;
     uint32_t w[kRing][kWords];
     // (vt: the thread index whose share of round rr is meant; a wave may take over another wave's share)
-    auto fetch = [&](uint32_t rr, int vt, uint32_t (&buf)[kWords]) { load_round<M, NT>(a, rr, nblk, blk, last_vec, vt, buf); };
+    // (loads past the end go to a line of this wave's own instead of all to the last one: no single hot line when
+    // thousands of waves reach the end of their scan together)
+    const uint32_t own_vec = (uint32_t)(blk * NW + wave) * 4u;
+    const uint32_t spare_vec = own_vec < last_vec ? own_vec : last_vec;
+    auto fetch = [&](uint32_t rr, int vt, uint32_t (&buf)[kWords]) {
+        load_round<M, NT>(a, rr, nblk, blk, last_vec, spare_vec, vt, buf);
+    };
     // (the host sends catalogues with no whole code vector, N * M < 16, to the generic kernel: rounds >= 1 here)
     auto fetch_first = [&]() {                                // no branch: the loads can be counted, so what follows
 #pragma unroll                                                // waits for exactly what it needs
@@ -912,18 +935,39 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     }
 
     // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
-    if (lane == 0) ctl->wave_cnt[wave] = top.cnt;
-    __syncthreads();
-    int total = 0, before = 0;
-#pragma unroll
-    for (int wv = 0; wv < NW; ++wv) {
-        int c = ctl->wave_cnt[wv];
-        if (wv < wave) before += c;
-        total += c;
+    if (lane == 0) {
+        ctl->wave_cnt[wave] = top.cnt;
+        ctl->wave_max[wave] = top.thr != 0ull ? score_of_key(top.thr) : -__builtin_inff();   // <= the wave's K-th best
     }
+    if (tid == 0) ctl->ncand = 0;
+    __syncthreads();
+    // lane w of every wave holds wave w's count and floor: totals by cross-lane operations, one LDS round trip
+    static_assert(NW <= kWave, "one lane per wave");
+    const uint32_t cnt_w = lane < NW ? (uint32_t)ctl->wave_cnt[lane] : 0u;
+    float fl_lo = lane < NW ? ctl->wave_max[lane] : -__builtin_inff(), wg_floor = fl_lo;
+    const uint32_t upto = wave_prefix_sum(cnt_w);
+    int total = __builtin_amdgcn_readlane((int)upto, kWave - 1);
+    const int before = __builtin_amdgcn_readlane((int)(upto - cnt_w), wave);
+    wave_minmax(fl_lo, wg_floor);
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
     if (total <= a.candmax) {
-        for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
+        if (total > kFilterMin) {
+            // a long scan leaves every wave with its own K best and more: only keys that reach the best of the waves'
+            // K-th scores can be among the workgroup's K best (that score is a lower bound of the workgroup's K-th)
+            for (int t0 = 0; t0 < top.cnt; t0 += kWave) {
+                const uint64_t key = t0 + lane < top.cnt ? top.buf[t0 + lane] : 0ull;
+                const bool take = key != 0ull && score_of_key(key) >= wg_floor;
+                const uint64_t mask = __ballot(take);
+                int base = 0;
+                if (lane == 0 && mask != 0) base = atomicAdd(&ctl->ncand, __popcll(mask));
+                base = __builtin_amdgcn_readfirstlane(base);
+                if (take) L.cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+            }
+            __syncthreads();
+            total = ctl->ncand;
+        } else {
+            for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
+        }
         rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
     } else {
         for (int t = top.cnt + lane; t < a.cap; t += kWave) top.buf[t] = 0;
