@@ -40,7 +40,9 @@ constexpr int kMaxWaves = kBigThreads / kWave;
 constexpr int kLutStride = 256;                   // table entries per split in LDS (a uint8 sub-id never runs past it)
 constexpr int kBins = 1024;                       // score buckets of the pruning histogram
 // 16-byte code vectors a thread holds per round: 4 for m >= 8, fewer for small m so a thread never holds > 16 items
-__host__ __device__ constexpr int vec_per_thread(int m) { return m >= 8 ? 4 : (m == 4 ? 2 : 1); }
+// Units of work a thread holds per round in the kernels with a compile-time m.  m <= 16: a unit is one 16-byte code
+// vector (16/m items); m = 32, 64: a unit is one item (m/16 vectors).  Four vectors per thread from m = 8 on.
+__host__ __device__ constexpr int vec_per_thread(int m) { return m == 64 ? 1 : (m == 32 ? 2 : (m >= 8 ? 4 : (m == 4 ? 2 : 1))); }
 constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
 constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
@@ -605,10 +607,11 @@ struct ScanArgs {
 // per slot, row loads sized by m's alignment.
 template <int M>
 struct Round {
-    static constexpr int kVecs = M ? vec_per_thread(M) : 0;
-    static constexpr int kIPV = M ? 16 / M : 1;
-    static constexpr int kItems = M ? kVecs * kIPV : kGenericItemsPerThread;
-    static constexpr int kUnitsPerThread = M ? kVecs : kGenericItemsPerThread;           // lane-sized units of work
+    static constexpr int kUnitsPerThread = M ? vec_per_thread(M) : kGenericItemsPerThread;   // lane-sized units of work
+    static constexpr int kVPU = M > 16 ? M / 16 : 1;                                     // 16-byte vectors per unit
+    static constexpr int kIPV = (M && M <= 16) ? 16 / M : 1;                             // items per unit
+    static constexpr int kVecs = M ? kUnitsPerThread * kVPU : 0;                         // 16-byte loads per round
+    static constexpr int kItems = kUnitsPerThread * kIPV;
     static constexpr int kWords = M ? kVecs * 4 : 1;
 };
 
@@ -633,6 +636,26 @@ __device__ __forceinline__ void score_vector(const float* lut, const uint32_t* w
         for (int k = 1; k < M; ++k) acc = acc + v[e * M + k];
         sc[e] = acc;
     }
+}
+
+// Eq. 5 for one item of M = 32 or 64 sub-ids (M/16 vectors, words w[0 .. M/4)): one left-to-right chain over all M
+// values; the 16 table reads of a vector are issued together.
+template <int M>
+__device__ __forceinline__ float score_wide(const float* lut, const uint32_t* w) {
+    float acc = 0.0f;
+#pragma unroll
+    for (int j = 0; j < M / 16; ++j) {
+        float v[16];
+#pragma unroll
+        for (int byte = 0; byte < 16; ++byte) {
+            const uint32_t code = (w[4 * j + (byte >> 2)] >> ((byte & 3) * 8)) & 0xFFu;
+            v[byte] = lut[(j * 16 + byte) * kLutStride + code];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int byte = 0; byte < 16; ++byte) acc = (j == 0 && byte == 0) ? v[0] : acc + v[byte];
+    }
+    return acc;
 }
 
 __device__ float score_row(const float* lut, const uint8_t* row, int m) {
@@ -684,12 +707,17 @@ __device__ __forceinline__ void load_round(const ScanArgs& a, uint32_t rr, int n
                                            uint32_t spare_vec, int tid, uint32_t (&w)[Round<M>::kWords]) {
     if constexpr (M > 0) {
         const uint4* base = reinterpret_cast<const uint4*>(a.codes);
+        constexpr int VPU = Round<M>::kVPU;
 #pragma unroll
-        for (int u = 0; u < Round<M>::kVecs; ++u) {
+        for (int u = 0; u < Round<M>::kUnitsPerThread; ++u) {
             uint32_t v = unit_of<M, NT>(rr, u, nblk, blk, tid);
             v = v <= last_vec ? v : spare_vec;
-            const uint4 x = base[v];
-            w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
+#pragma unroll
+            for (int j = 0; j < VPU; ++j) {
+                const uint4 x = base[(size_t)v * VPU + j];
+                const int o = 4 * (u * VPU + j);
+                w[o] = x.x; w[o + 1] = x.y; w[o + 2] = x.z; w[o + 3] = x.w;
+            }
         }
     }
 }
@@ -703,9 +731,10 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
                                             float (&sc)[Round<M>::kItems]) {
     if constexpr (M > 0) {
 #pragma unroll
-        for (int u = 0; u < Round<M>::kVecs; ++u) {
+        for (int u = 0; u < Round<M>::kUnitsPerThread; ++u) {
             if (inside || unit_of<M, NT>(rr, u, nblk, blk, tid) < n_units) {
-                score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
+                if constexpr (M > 16) sc[u] = score_wide<M>(lut, &w[4 * Round<M>::kVPU * u]);
+                else score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
             } else {
 #pragma unroll
                 for (int e = 0; e < Round<M>::kIPV; ++e) sc[u * Round<M>::kIPV + e] = 0.0f;
@@ -759,7 +788,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
 
     // Vector kernels scan the code vectors that lie wholly inside the catalogue; the fewer than 16 / M items after
     // them (when N * M is not a multiple of 16) are scored one by one at the end.  The generic kernel scans items.
-    const uint32_t total_units = (uint32_t)(M ? (a.N * M) / 16 : a.N);
+    const uint32_t total_units = (uint32_t)((M && M <= 16) ? (a.N * M) / 16 : a.N);
     const uint32_t n_scan = M ? total_units * Round<M>::kIPV : total_units;   // items the rounds cover
     const uint32_t last_vec = total_units - 1;                                // (total_units >= 1: the host sees to it)
     const uint32_t round_units = (uint32_t)NT * kUnits * nblk;                // units all workgroups take per round
@@ -916,7 +945,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             }
         }
     }
-    if constexpr (M > 0) {
+    if constexpr (M > 0 && M <= 16) {
         // the fewer than 16 / M items after the last whole code vector, one per lane of one wave
         if (blockIdx.x == 0 && wave == 0) {
             const uint32_t item = n_scan + lane;
@@ -1599,6 +1628,7 @@ int next_pow2(int x) {
 struct ScanPlan {
     int copies;      // single-query kernel: copies of the score tables in LDS (1 or kTableCopies)
     bool tiled;      // batched kernel: kQ queries per workgroup
+    bool big;        // single-query kernel: kBigThreads threads per workgroup, one workgroup per CU
     int nblk;        // item blocks per query
     int cap;         // keys per wave list
     int candmax;     // keys of the candidate array
@@ -1609,13 +1639,13 @@ struct ScanPlan {
     bool vec;
 };
 
-bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16; }
+bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32 || m == 64; }
 
 // `generic`: plan for the generic kernel whatever m is (candidate-list scans use it: their rows are gathered)
 ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     ScanPlan p;
     p.vec = !generic && is_vec_m(m) && N * m >= 16;            // (the vector kernels need one whole code vector at least)
-    const long long units = p.vec ? (N * m) / 16 : N;          // whole code vectors (the few items after them are extra)
+    const long long units = (p.vec && m <= 16) ? (N * m) / 16 : N;   // whole code vectors (the few items after them are extra)
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
@@ -1648,8 +1678,26 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
             p.nblk = (int)nb;
         }
     }
+    // A generic scan whose tables leave room for only one 512-thread workgroup per CU (m > 36 or so) runs 1024-thread
+    // workgroups instead, one per CU: the same tables then serve sixteen waves, which is what hides the latency of
+    // the row loads.  Only when there is more than one workgroup's worth of work per CU.
+    p.big = p.copies > 1;
+    if (!p.vec || m == 64) {
+        const size_t small = scan_lds_bytes((size_t)m * kLutStride, p.cap, p.candmax, K, kWaves);
+        const size_t big = scan_lds_bytes((size_t)m * kLutStride, p.cap, p.candmax, K, kMaxWaves);
+        long long nb = kAssumedCUs / B;
+        if (nb < 8) nb = 8;
+        if (2 * small > kMaxLdsBytes && big <= kMaxLdsBytes && rounds > nb) {
+            const long long big_round = (long long)kBigThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
+            const long long big_rounds = (units + big_round - 1) / big_round;
+            if (big_rounds < nb) nb = big_rounds;
+            if (B > 1 && nb >= 8) nb &= ~7LL;
+            p.big = true;
+            p.nblk = (int)nb;
+        }
+    }
     const size_t lut_dyn = p.copies > 1 ? (size_t)m * kLutStride * p.copies : (p.vec ? 0 : (size_t)m * kLutStride);
-    p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.copies > 1 ? kMaxWaves : kWaves);
+    p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.big ? kMaxWaves : kWaves);
     p.scan_lds = p.scan_dyn_lds + ((p.vec && p.copies == 1) ? (size_t)m * kLutStride * sizeof(float) : 0);
     p.tiled = false;
     if (!generic && B >= 2 && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
@@ -1711,6 +1759,15 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
             return hipGetLastError();
         }
     }
+    if constexpr (M == 0 || M == 64) {
+        if (p.big) {
+            hipError_t e = allow_lds(scan_topk_kernel<M, 1, kBigThreads>, p.scan_dyn_lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((scan_topk_kernel<M, 1, kBigThreads>), dim3(p.nblk, B), dim3(kBigThreads),
+                               p.scan_dyn_lds, st, a);
+            return hipGetLastError();
+        }
+    }
     hipError_t e = allow_lds(scan_topk_kernel<M>, p.scan_dyn_lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(scan_topk_kernel<M>, dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
@@ -1746,6 +1803,8 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
         case 4: e = launch_scan<4>(p, a, B, st); break;
         case 8: e = launch_scan<8>(p, a, B, st); break;
         case 16: e = launch_scan<16>(p, a, B, st); break;
+        case 32: e = launch_scan<32>(p, a, B, st); break;
+        case 64: e = launch_scan<64>(p, a, B, st); break;
         default: e = launch_scan<0>(p, a, B, st); break;
     }
     return record_hip(e);

@@ -201,6 +201,16 @@ def candidate_list(N: int, count: int, seed: int = 0, ascending: bool = False) -
     return np.sort(order) if ascending else order
 
 
+def codes_uniform_device(N: int, m: int, b: int = 256, seed: int = 0):
+    """Uniform sub-ids drawn on the GPU (torch's seeded device generator) as a uint8 [N][m] device tensor: for
+    catalogues too large to draw on the host in reasonable time (the catalogue-size sweep).  Not the same stream
+    as codes_uniform(); whoever checks results copies the tensor back."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.randint(0, b, (N, m), dtype=torch.uint8, device="cuda", generator=g)
+
+
 def plant_rows(codes: np.ndarray, ids: np.ndarray, row: np.ndarray) -> np.ndarray:
     """Overwrite the code rows of `ids` with `row` (in place); the caller decides which row to plant."""
     codes[np.asarray(ids, dtype=np.int64)] = np.asarray(row, dtype=np.uint8)[None, :]

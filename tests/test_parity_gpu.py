@@ -103,6 +103,15 @@ def test_score_topk_long_scans_replicated_tables(pq, oracle, N, m, B):
 
 # ---------------------------------------------------------------- ties and adversarial orders
 
+@pytest.mark.parametrize("N,m,B,K", [(1_000_003, 64, 1, 10), (600_001, 64, 2, 100), (2_000_001, 32, 1, 10),
+                                     (300_000, 64, 3, 10), (150_001, 64, 1, 300), (5_000_000, 32, 1, 64)])
+def test_score_topk_wide_items(pq, oracle, N, m, B, K):
+    # m = 32, 64: one item spans two or four code vectors; long m = 64 scans run 1024-thread workgroups
+    G = W.codes_uniform(N, m, 256, seed=m)
+    S = W.normal_f32(W.stream_key(N, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    assert_same_topk(pq, oracle, G, S, K, "wide")
+
+
 def test_all_items_equal(pq, oracle):
     for N in (500, 100_000):
         G = np.full((N, 8), 17, dtype=np.uint8)
