@@ -422,6 +422,7 @@ struct WaveTopK {
 };
 
 constexpr int kFastCand = 128;   // keys one wave can rank on its own (two per lane)
+constexpr double kTiledMinLookups = 3.5e8;   // B * N * m from which the batched kernel takes over (measured crossover)
 constexpr int kFilterMin = 64;   // single-query scan: final candidate sets larger than this are first cut by a floor
 
 // One wave: sorted exact K best of the T <= MAXT keys in c[] (LDS; c has room for T rounded up to a multiple of 8,
@@ -830,10 +831,26 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             const int piece = tid + i * NT;
             if (piece < kPieces) reinterpret_cast<float4*>(lut_base)[piece] = make_float4(tv[i], tv[i], tv[i], tv[i]);
         }
-    } else if (b == kLutStride && m * kLutStride == 4 * NT) {  // m = 8, b = 256: one 16-byte load per thread
-        const float4 t4 = reinterpret_cast<const float4*>(Sq)[tid];
-        fetch_first();
-        reinterpret_cast<float4*>(lut_base)[tid] = t4;
+    } else if (b == kLutStride && ((uintptr_t)Sq & 15) == 0) {
+        // b = 256: the query's table is copied as it is, in 16-byte pieces, all requested before the first is stored
+        const float4* src = reinterpret_cast<const float4*>(Sq);
+        float4* dst = reinterpret_cast<float4*>(lut_base);
+        if constexpr (M > 0) {
+            constexpr int kPieces = M * kLutStride / 4;
+            constexpr int kPer = (kPieces + NT - 1) / NT;
+            float4 t4[kPer];
+#pragma unroll
+            for (int i = 0; i < kPer; ++i)
+                t4[i] = (kPieces % NT == 0 || tid + i * NT < kPieces) ? src[tid + i * NT] : make_float4(0, 0, 0, 0);
+            fetch_first();
+#pragma unroll
+            for (int i = 0; i < kPer; ++i)
+                if (kPieces % NT == 0 || tid + i * NT < kPieces) dst[tid + i * NT] = t4[i];
+        } else {
+            fetch_first();
+#pragma unroll 4
+            for (int e = tid; e < m * (kLutStride / 4); e += NT) dst[e] = src[e];
+        }
     } else {
         fetch_first();
         for (int e = tid; e < m * kLutStride; e += NT) {
@@ -1655,7 +1672,7 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     if (one_per_cu < 8) one_per_cu = 8;                        // then takes two or three (possibly ragged) rounds
     if (rounds > one_per_cu && rounds <= most) nblk = one_per_cu;
     if (nblk < 1) nblk = 1;
-    if (B > 1 && nblk >= 8) nblk &= ~7LL;                      // same item block of every query on the same XCD
+    if (B > 1 && nblk >= 32) nblk &= ~7LL;                     // same item block of every query on the same XCD
     p.nblk = (int)nblk;
     p.cap = next_pow2(K + kWave);
     if (p.cap < 128) p.cap = 128;
@@ -1668,12 +1685,12 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     // the tables, lanes l and l' collide only if l % kTableCopies == l' % kTableCopies.  Worth its LDS and fill time
     // only when every workgroup streams many rounds; one workgroup per CU then (the tables take 128 KB at m = 8).
     if (p.vec && m <= 8) {
-        long long nb = kAssumedCUs / B;                        // one workgroup (of kBigThreads) per CU over the whole grid
-        if (nb < 8) nb = 8;
+        const long long nb = kAssumedCUs / B;                  // one workgroup (of kBigThreads) per CU over the whole grid
         const long long big_round = (long long)kBigThreads * vec_per_thread(m);
         const long long big_rounds = (units + big_round - 1) / big_round;
         const size_t dyn = scan_lds_bytes((size_t)m * kLutStride * kTableCopies, p.cap, p.candmax, K, kMaxWaves);
-        if (big_rounds >= kTableCopiesMinRounds * nb && dyn <= kMaxLdsBytes) {
+        if (nb >= 8 && big_rounds >= kTableCopiesMinRounds * nb && dyn <= kMaxLdsBytes) {   // (nb < 8: more queries than
+                                                                                            // the grid has room for)
             p.copies = kTableCopies;
             p.nblk = (int)nb;
         }
@@ -1700,7 +1717,10 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.big ? kMaxWaves : kWaves);
     p.scan_lds = p.scan_dyn_lds + ((p.vec && p.copies == 1) ? (size_t)m * kLutStride * sizeof(float) : 0);
     p.tiled = false;
-    if (!generic && B >= 2 && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
+    // (a small batch over a small catalogue is faster as B single-query scans side by side: the batched kernel's
+    // fixed costs, about 15 us of table fill, first-round cuts and final merge, are not yet paid back)
+    const bool small_job = B <= 2 || (double)B * (double)N * m <= kTiledMinLookups;
+    if (!generic && !small_job && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
         if (all <= kMaxLdsBytes) {
@@ -1781,7 +1801,7 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     ScanArgs a;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
     a.subset = subset; a.n_items = (uint32_t)(subset ? n_items : N);
-    a.checkpoint_factor = K > 28 ? 2 : 8;                  // small K: the waves' own pruning already keeps floors tight
+    a.checkpoint_factor = K > 28 ? 2 : 4;                  // small K: the waves' own pruning already keeps floors tight
     a.cap = p.cap; a.candmax = p.candmax;
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
     a.ws_keys = static_cast<uint64_t*>(workspace);
@@ -1849,6 +1869,8 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
     if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)S & 3)) return PQ_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (d / m) {
+        case 4: launch_subitem<4>(queries, centroids, S, B, d, m, b, st); break;
+        case 8: launch_subitem<8>(queries, centroids, S, B, d, m, b, st); break;
         case 16: launch_subitem<16>(queries, centroids, S, B, d, m, b, st); break;
         case 32: launch_subitem<32>(queries, centroids, S, B, d, m, b, st); break;
         case 64: launch_subitem<64>(queries, centroids, S, B, d, m, b, st); break;
