@@ -422,7 +422,7 @@ struct WaveTopK {
 };
 
 constexpr int kFastCand = 128;   // keys one wave can rank on its own (two per lane)
-constexpr double kTiledMinLookups = 3.5e8;   // B * N * m from which the batched kernel takes over (measured crossover)
+constexpr double kTiledMinLookups = 2.0e8;   // B * N * m from which the batched kernel takes over (measured crossover)
 constexpr int kFilterMin = 64;   // single-query scan: final candidate sets larger than this are first cut by a floor
 
 // One wave: sorted exact K best of the T <= MAXT keys in c[] (LDS; c has room for T rounded up to a multiple of 8,
@@ -601,7 +601,6 @@ struct ScanArgs {
     uint64_t* ws_keys;   // [B][nblk][K]
     const int* subset;   // candidate list V (generic kernel only): unit p stands for item subset[p]; nullptr: V = I
     uint32_t n_items;    // items in the catalogue (bounds the ids read from `subset`)
-    int checkpoint_factor;   // batched kernel: growth of the number of rounds between workgroup checkpoints (>= 2)
 };
 
 // Items a thread holds per round.  M > 0: m is M and one 16-byte vector carries 16/M items; M == 0: any m, one item
@@ -1041,6 +1040,46 @@ struct WaveQ {
     float floor_ge;
 };
 
+// Workgroup-wide floors of the batched kernel.  Per query a histogram of kFloorBins buckets counts every score the
+// workgroup has appended to a list (and all of the first round's scores); its range is fixed after the first
+// round.  At least K counted scores lie in the buckets from b* up, so the lower edge of b* is a lower bound of the
+// workgroup's K-th best score so far: a floor for all eight waves, a bucket's width away from the exact one, kept up
+// to date for the price of one LDS atomic per candidate and a short scan of the histogram every few rounds.
+constexpr int kFloorBins = 256;
+struct FloorState {
+    float lo, scale;     // bucket of score s: (s - lo) * scale, clamped to [0, kFloorBins)
+    int dirty;           // a score was counted since the floor was last derived
+    int pad;
+};
+// (the floors themselves are kQ floats of their own, read once per round by kQ lanes of each wave; a racing store may
+// lower one briefly, which is still a valid floor)
+
+// One wave: the floor the histogram allows (see above), -inf if it counts fewer than K scores.  Same value in all lanes.
+__device__ __forceinline__ float floor_from_hist(const uint32_t* hist, int K, float lo, float scale, int lane) {
+    constexpr int per = kFloorBins / kWave;                  // buckets per lane; lane 0 owns the top ones
+    const int first = kFloorBins - per * (lane + 1);
+    const uint4 v = *reinterpret_cast<const uint4*>(hist + first);
+    static_assert(per == 4, "one 16-byte read per lane");
+    const uint32_t mine = v.x + v.y + v.z + v.w;
+    const uint32_t upto = wave_prefix_sum(mine);
+    const uint64_t has = __ballot(upto >= (uint32_t)K);
+    if (has == 0 || !(scale > 0.0f)) return -__builtin_inff();
+    const int owner = __builtin_ctzll(has);
+    uint32_t above = upto - mine;                            // counted in buckets above this lane's
+    int found = 0;
+    above += v.w; if (above >= (uint32_t)K) found = 3;
+    else { above += v.z; if (above >= (uint32_t)K) found = 2;
+    else { above += v.y; if (above >= (uint32_t)K) found = 1; } }
+    const int bstar = __builtin_amdgcn_readlane(first + found, owner);
+    if (bstar <= 0) return -__builtin_inff();
+    // a score cut with bucket(cut) < b*: by monotonicity every score counted in a bucket >= b* is > cut
+    const float width = 1.0f / scale;
+    float cut = lo + ((float)bstar - 0.5f) * width;
+    for (int guard = 0; guard < 8 && bucket_of<kFloorBins>(cut, lo, scale) >= bstar; ++guard) cut -= width;
+    if (bucket_of<kFloorBins>(cut, lo, scale) >= bstar) return -__builtin_inff();
+    return next_up(cut);
+}
+
 // keys of room per query in the workgroup's best[] array (a checkpoint may keep a few more than K)
 __host__ __device__ inline int tiled_best_keys(int K) { return ((K > 128 ? K : 128) + 1) & ~1; }
 
@@ -1048,7 +1087,8 @@ __host__ __device__ inline size_t tiled_lds_bytes(int cap, int candmax, int K) {
     return (size_t)kBins * sizeof(uint32_t) + (size_t)kQ * align16(sizeof(Ctl)) +
            (size_t)kWaves * kQ * sizeof(WaveQ) + (size_t)kQ * kWaves * cap * sizeof(uint64_t) +
            (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t)) +
-           (size_t)kQ * tiled_best_keys(K) * sizeof(uint64_t);
+           (size_t)kQ * tiled_best_keys(K) * sizeof(uint64_t) + (size_t)kQ * kFloorBins * sizeof(uint32_t) +
+           (size_t)kQ * sizeof(FloorState) + (size_t)kQ * sizeof(float);
 }
 
 // Eq. 5 for the 16/M items of one code vector and the kQ = 4 queries of the tile; sc[q][e], sums left to right.
@@ -1109,18 +1149,15 @@ struct TileLds {
     uint64_t* sorted;        // K
     uint64_t* best;          // [kQ][kpad]: per query, a superset of the workgroup's K best so far (ctl->keep keys)
     int kpad;
+    float* sfloor;           // [kQ] workgroup-wide floors
 };
 
-// Workgroup checkpoint of the batched kernel.  Per query it merges the waves' lists into best[q], empties the lists and
-// raises every wave's floor, so that the floors follow what the workgroup as a whole has scanned.  best[q] holds
-// ctl(q)->keep keys: a superset of the exact K best of everything scanned so far (exactly those, sorted, after a
-// `final` checkpoint).  Three paths, all exact in what they keep:
+// Final merge of the batched kernel.  Per query it merges the eight waves' lists (and whatever best[q] already holds:
+// ctl(q)->keep keys) into best[q]: the exact K best of everything the workgroup scanned, sorted.  Two paths:
 //   - few keys everywhere: wave q ranks query q by counting, no workgroup barrier inside;
-//   - otherwise, while K leaves room in best[]: all queries at once, two waves each: a histogram over the keys' own
-//     score range gives a cut with at least K keys above it; those keys are kept and the cut becomes the floor;
-//   - a query that fits neither (or `final`): ranking / sorting by the whole workgroup, one query at a time.
-// Every thread of the workgroup calls it at the same round.  Out of line: the streaming loop stays small.
-__device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, int tid, bool final) {
+//   - otherwise: ranking / sorting by the whole workgroup, one query at a time.
+// Every thread of the workgroup calls it.  Out of line: the streaming loop stays small.
+__device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, int tid) {
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(L.pctl + (size_t)q * align16(sizeof(Ctl))); };
     auto reset_lists = [&](int q, int wv, float floor_ge) {   // one thread per (query, wave)
@@ -1128,6 +1165,7 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
         st->cnt = 0;
         st->thr = 0ull;
         st->floor_ge = fmaxf(st->floor_ge, floor_ge);
+        if (wv == 0) L.sfloor[q] = fmaxf(L.sfloor[q], floor_ge);
     };
     __syncthreads();                                          // every wave's list state in LDS is final
     int total[kQ], keep[kQ];
@@ -1165,62 +1203,6 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
         }
         __syncthreads();
         return;
-    }
-
-    if (!final && K + 28 <= kFastCand) {
-        // all queries at once: waves 2q and 2q + 1 serve query q
-        const int q = wave >> 1, gt = tid & (2 * kWave - 1);
-        const bool active = q < nq;
-        Ctl* c = ctl_of(q);
-        uint32_t* h = L.hist + q * kTiledBins;
-        const uint64_t* bq = L.best + (size_t)q * L.kpad;
-        uint64_t* cq = L.cand + (size_t)q * kFastCand;
-        auto each_key = [&](auto&& f) {
-            for (int wv = 0; wv < kWaves; ++wv) {
-                const int n = L.states[wv * kQ + q].cnt;
-                const uint64_t* src = L.lists + ((size_t)q * kWaves + wv) * cap;
-                for (int t = gt; t < n; t += 2 * kWave) f(src[t]);
-            }
-            for (int t = gt; t < keep[q]; t += 2 * kWave) {
-                const uint64_t key = bq[t];
-                if (key != 0ull) f(key);
-            }
-        };
-        float mn = __builtin_inff(), mx = -__builtin_inff();
-        if (active) each_key([&](uint64_t key) { const float sc = score_of_key(key); mn = fminf(mn, sc); mx = fmaxf(mx, sc); });
-        wave_minmax(mn, mx);
-        if (lane == 0) { c->wave_min[wave] = mn; c->wave_max[wave] = mx; }
-        for (int i = gt; i < kTiledBins; i += 2 * kWave) h[i] = 0;
-        __syncthreads();
-        const float lo = fminf(c->wave_min[2 * q], c->wave_min[2 * q + 1]);
-        const float hi = fmaxf(c->wave_max[2 * q], c->wave_max[2 * q + 1]);
-        const float range = hi - lo;
-        float scale = (range > 0.0f) ? (float)kTiledBins / range : 0.0f;
-        if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
-        if (gt == 0) { c->lo = lo; c->scale = scale; c->ncand = 0; c->bstar = 0; c->cut = -__builtin_inff(); }
-        if (active) each_key([&](uint64_t key) { atomicAdd(&h[bucket_of<kTiledBins>(score_of_key(key), lo, scale)], 1u); });
-        __syncthreads();
-        if (active && (wave & 1) == 0) find_cut<kTiledBins>(h, K, c, lane);
-        __syncthreads();
-        const int bstar = c->bstar;
-        if (active)
-            each_key([&](uint64_t key) {
-                if (bucket_of<kTiledBins>(score_of_key(key), lo, scale) >= bstar) {
-                    const int pos = atomicAdd(&c->ncand, 1);
-                    if (pos < kFastCand) cq[pos] = key;
-                }
-            });
-        __syncthreads();
-        const int C = c->ncand;                               // kept keys: all those above the cut, at least min(K, all)
-        if (active && C <= kFastCand) {
-            uint64_t* bw = L.best + (size_t)q * L.kpad;
-            for (int t = gt; t < C; t += 2 * kWave) bw[t] = cq[t];
-            if (gt < kWaves) reset_lists(q, gt, next_up(c->cut));
-            if (gt == 0) c->keep = C;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int qq = 0; qq < kQ; ++qq) exact_needed[qq] = qq < nq && ctl_of(qq)->ncand > kFastCand;
     }
 
     for (int q = 0; q < nq; ++q) {
@@ -1267,8 +1249,11 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     uint64_t* sorted = cand + a.candmax;
     const int kpad = tiled_best_keys(a.K);
     uint64_t* best = sorted + align16((size_t)a.K * sizeof(uint64_t)) / sizeof(uint64_t);   // [kQ][kpad]
+    uint32_t* fhist = reinterpret_cast<uint32_t*>(best + (size_t)kQ * kpad);                 // [kQ][kFloorBins]
+    FloorState* fstate = reinterpret_cast<FloorState*>(fhist + kQ * kFloorBins);             // [kQ]
+    float* sfloor = reinterpret_cast<float*>(fstate + kQ);                                   // [kQ]
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(pctl + (size_t)q * align16(sizeof(Ctl))); };
-    const TileLds tl{hist, pctl, states, lists, cand, sorted, best, kpad};
+    const TileLds tl{hist, pctl, states, lists, cand, sorted, best, kpad, sfloor};
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q0 = blockIdx.y * kQ, nblk = gridDim.x, K = a.K, b = a.b;
@@ -1334,6 +1319,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             }
         }
         for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+        for (int i = tid; i < kQ * kFloorBins; i += kThreads) fhist[i] = 0;
         for (int i = tid; i < kQ * kpad; i += kThreads) best[i] = 0;
         if (tid < kQ) ctl_of(tid)->keep = 0;
         if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
@@ -1355,14 +1341,17 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     };
     auto offer_round = [&](const float (&sc)[kQ][kItems], long long rr, const int* bk, const int* bstar) {
         const bool inside = rr < inside_rounds;
+        // the kQ floors: read by kQ lanes only (an LDS read costs by the lane), then handed to the whole wave
+        const int my_floor = lane < kQ ? __float_as_int(sfloor[lane]) : 0;
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             if (q >= nq) continue;
             float best = sc[q][0];
 #pragma unroll
             for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[q][e]);
-            const float floor_ge = my_state[q].floor_ge;
+            const float floor_ge = __int_as_float(__builtin_amdgcn_readlane(my_floor, q));
             if (__ballot(best >= floor_ge) == 0) continue;    // the usual case
+            const float flo = fstate[q].lo, fscale = fstate[q].scale;
             uint64_t* const buf = list_of(q);
             int stop = kItems;                                // first item the inline path had to leave
             bool ok[kItems];
@@ -1377,8 +1366,13 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
                 const int n = __popcll(mask);
                 if (cnt[q] + n > a.cap) { stop = e; continue; }
                 const int pos = cnt[q] + __popcll(mask & ((1ull << lane) - 1ull));
-                if (take) buf[pos] = make_key(sc[q][e] + 0.0f, (uint32_t)item);
+                if (take) {
+                    buf[pos] = make_key(sc[q][e] + 0.0f, (uint32_t)item);
+                    if (bk == nullptr)                            // (the first round's scores are all counted already)
+                        atomicAdd(&fhist[q * kFloorBins + bucket_of<kFloorBins>(sc[q][e], flo, fscale)], 1u);
+                }
                 cnt[q] += n;
+                if (bk == nullptr && lane == 0) fstate[q].dirty = 1;
             }
             if (stop < kItems || (a.prune_at != 0 && cnt[q] >= a.prune_at)) {
                 Slots<kItems> s;
@@ -1392,9 +1386,23 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
                 wave_sync();
                 offer_slow<kItems>(&my_state[q], buf, a.cap, K, a.prune_at, s, lane);
                 cnt[q] = __builtin_amdgcn_readfirstlane(my_state[q].cnt);
+                if (lane == 0 && my_state[q].floor_ge > sfloor[q]) sfloor[q] = my_state[q].floor_ge;   // the wave's K-th best
             }
         }
     };
+
+    // Every eighth round of a wave (the waves take turns): floors of the queries whose histograms have grown.
+    auto refresh_floors = [&]() {
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            if (q >= nq || fstate[q].dirty == 0) continue;
+            if (lane == 0) fstate[q].dirty = 0;               // before the histogram is read: a count that lands
+            wave_sync();                                      // later sets it again
+            const float f = floor_from_hist(fhist + q * kFloorBins, K, fstate[q].lo, fstate[q].scale, lane);
+            if (lane == 0 && f > sfloor[q]) sfloor[q] = f;
+        }
+    };
+    int turn = wave;                                          // rounds until this wave's next refresh
 
     {
         // ---- 2. first round: per query a histogram over its own score range gives that query's cut
@@ -1418,18 +1426,26 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             float lo = c->wave_min[0], hi = c->wave_max[0];
 #pragma unroll
             for (int w = 1; w < kWaves; ++w) { lo = fminf(lo, c->wave_min[w]); hi = fmaxf(hi, c->wave_max[w]); }
-            const float range = hi - lo;
-            float scale = (range > 0.0f) ? (float)kTiledBins / range : 0.0f;
+            // (the histogram lives on as the query's floor histogram: a quarter of the range is added on top, for
+            // the scores of later rounds that beat everything in this one)
+            const float range = (hi - lo) * 1.25f;
+            float scale = (range > 0.0f) ? (float)kFloorBins / range : 0.0f;
             if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
-            if (tid == q) { c->lo = lo; c->scale = scale; c->cut = -__builtin_inff(); c->bstar = 0; c->ncand = 0; }
+            if (tid == q) {
+                c->lo = lo; c->scale = scale; c->cut = -__builtin_inff(); c->bstar = 0; c->ncand = 0;
+                fstate[q].lo = lo; fstate[q].scale = scale; fstate[q].dirty = 0;
+            }
 #pragma unroll
             for (int e = 0; e < kItems; ++e) {
-                bk[q * kItems + e] = bucket_of<kTiledBins>(sc[q][e], lo, scale);
-                if (q < nq && item_of(r, e) < n_scan) atomicAdd(&hist[q * kTiledBins + bk[q * kItems + e]], 1u);
+                bk[q * kItems + e] = bucket_of<kFloorBins>(sc[q][e], lo, scale);
+                if (q < nq && item_of(r, e) < n_scan) atomicAdd(&fhist[q * kFloorBins + bk[q * kItems + e]], 1u);
             }
         }
         __syncthreads();
-        if (wave < kQ) find_cut<kTiledBins>(hist + wave * kTiledBins, K, ctl_of(wave), lane);
+        if (wave < kQ) {
+            find_cut<kFloorBins>(fhist + wave * kFloorBins, K, ctl_of(wave), lane);
+            if (lane == 0) sfloor[wave] = next_up(ctl_of(wave)->cut);
+        }
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
@@ -1441,41 +1457,32 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         r += nblk;
     }
 
-    // ---- 3. stream: wb holds round r, wa round r + nblk.  Segments of 2, 2 f, 2 f^2, ... rounds, a workgroup
-    // checkpoint between segments: the floors stay close to what the scanned part of the catalogue allows.
-    long long segment = 2;                                    // even, so that every segment starts with wb
-    while (r < rounds) {
-        long long left = segment;
-        while (left > 0 && r + nblk < rounds) {               // two rounds at a time, no branch between their loads
-            {
-                float sc[kQ][kItems];
-                score(wb, sc);
-                load(r + 2 * nblk, wb);
-                offer_round(sc, r, nullptr, nullptr);
-            }
-            r += nblk;
-            {
-                float sc[kQ][kItems];
-                score(wa, sc);
-                load(r + 2 * nblk, wa);
-                offer_round(sc, r, nullptr, nullptr);
-            }
-            r += nblk;
-            left -= 2;
-        }
-        if (left > 0 && r < rounds) {                         // a last single round
+    // ---- 3. stream: wb holds round r, wa round r + nblk; two rounds at a time, no branch between their loads.
+    // No workgroup-wide step in here: the shared floors keep every wave's candidates few, and a list that fills up all
+    // the same is sorted and cut back by its own wave.
+    while (r + nblk < rounds) {
+        {
             float sc[kQ][kItems];
             score(wb, sc);
+            load(r + 2 * nblk, wb);
             offer_round(sc, r, nullptr, nullptr);
-            r += nblk;
         }
-        if (r < rounds) {
-            publish_counts();
-            tile_checkpoint(tl, nq, K, a.cap, a.candmax, tid, false);
-#pragma unroll
-            for (int q = 0; q < kQ; ++q) cnt[q] = 0;          // a checkpoint empties every list
-            segment *= a.checkpoint_factor;
+        r += nblk;
+        {
+            float sc[kQ][kItems];
+            score(wa, sc);
+            load(r + 2 * nblk, wa);
+            offer_round(sc, r, nullptr, nullptr);
         }
+        r += nblk;
+        turn -= 2;
+        if (turn < 0) { turn += kWaves; refresh_floors(); }
+    }
+    if (r < rounds) {                                         // a last single round
+        float sc[kQ][kItems];
+        score(wb, sc);
+        offer_round(sc, r, nullptr, nullptr);
+        r += nblk;
     }
     // the fewer than 16 / M items after the last whole code vector: one per lane of one wave, per query
     if (blockIdx.x == 0 && wave == 0 && n_scan < a.N) {
@@ -1514,7 +1521,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 
     // ---- 4. last checkpoint, then the workgroup's exact K best per query go to the workspace, sorted
     publish_counts();
-    tile_checkpoint(tl, nq, K, a.cap, a.candmax, tid, true);
+    tile_checkpoint(tl, nq, K, a.cap, a.candmax, tid);
     for (int i = tid; i < nq * K; i += kThreads) {
         const int q = i / K, t = i % K;
         a.ws_keys[((size_t)(q0 + q) * nblk + blockIdx.x) * K + t] = best[(size_t)q * kpad + t];
@@ -1801,7 +1808,6 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     ScanArgs a;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
     a.subset = subset; a.n_items = (uint32_t)(subset ? n_items : N);
-    a.checkpoint_factor = K > 28 ? 2 : 4;                  // small K: the waves' own pruning already keeps floors tight
     a.cap = p.cap; a.candmax = p.candmax;
     a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
     a.ws_keys = static_cast<uint64_t*>(workspace);
