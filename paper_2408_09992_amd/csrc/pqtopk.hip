@@ -1271,18 +1271,19 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 
     // a round's code vectors: always kTileVecs plain 16-byte loads, the index clamped to the last whole vector (no
     // branch, so the loads can be counted and a second round stays in flight); clamped items are masked out later
-    auto load = [&](long long rr, uint32_t (&w)[kWords]) {
+    // (vt: the thread index whose share of the round is meant; a wave may take over another wave's share)
+    auto load = [&](long long rr, int vt, uint32_t (&w)[kWords]) {
         const uint4* base = reinterpret_cast<const uint4*>(a.codes);
 #pragma unroll
         for (int u = 0; u < kTileVecs; ++u) {
-            long long v = rr * round_units + (long long)u * kThreads + tid;
+            long long v = rr * round_units + (long long)u * kThreads + vt;
             v = v < last_vec ? v : last_vec;
             const uint4 x = base[v];
             w[4 * u] = x.x; w[4 * u + 1] = x.y; w[4 * u + 2] = x.z; w[4 * u + 3] = x.w;
         }
     };
-    auto item_of = [&](long long rr, int e) {
-        return (rr * round_units + (long long)(e / IPV) * kThreads + tid) * IPV + (e % IPV);
+    auto item_of = [&](long long rr, int vt, int e) {
+        return (rr * round_units + (long long)(e / IPV) * kThreads + vt) * IPV + (e % IPV);
     };
     auto score = [&](const uint32_t (&w)[kWords], float (&sc)[kQ][kItems]) {
 #pragma unroll
@@ -1299,8 +1300,8 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     // ---- 1. codes on their way, the tile's tables into LDS (queries past B get zero tables and are never scored)
     long long r = blockIdx.x;
     uint32_t wa[kWords], wb[kWords];
-    load(r, wa);
-    load(r + nblk, wb);
+    load(r, tid, wa);
+    load(r + nblk, tid, wb);
     {
         float* lutf = reinterpret_cast<float*>(lut4);
         if (b == kLutStride) {                                // whole rows: 16-byte loads, four sub-ids at a time
@@ -1322,6 +1323,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         for (int i = tid; i < kQ * kFloorBins; i += kThreads) fhist[i] = 0;
         for (int i = tid; i < kQ * kpad; i += kThreads) best[i] = 0;
         if (tid < kQ) ctl_of(tid)->keep = 0;
+        if (tid == 0) ctl_of(0)->next_unit = 3 * kWaves;       // units 0 .. 3 kWaves - 1 are the waves' own (see 3.)
         if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
     }
     __syncthreads();
@@ -1339,7 +1341,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             for (int q = 0; q < kQ; ++q) my_state[q].cnt = cnt[q];
         }
     };
-    auto offer_round = [&](const float (&sc)[kQ][kItems], long long rr, const int* bk, const int* bstar) {
+    auto offer_round = [&](const float (&sc)[kQ][kItems], long long rr, int vt, const int* bk, const int* bstar) {
         const bool inside = rr < inside_rounds;
         // the kQ floors: read by kQ lanes only (an LDS read costs by the lane), then handed to the whole wave
         const int my_floor = lane < kQ ? __float_as_int(sfloor[lane]) : 0;
@@ -1357,7 +1359,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             bool ok[kItems];
 #pragma unroll
             for (int e = 0; e < kItems; ++e) {
-                const long long item = item_of(rr, e);
+                const long long item = item_of(rr, vt, e);
                 ok[e] = (inside || item < n_scan) && (bk == nullptr || bk[q * kItems + e] >= bstar[q]);
                 if (stop < kItems) continue;
                 const bool take = ok[e] && sc[q][e] >= floor_ge;
@@ -1379,7 +1381,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
                 for (int e = 0; e < kItems; ++e) {
                     s.sc[e] = sc[q][e];
-                    s.id[e] = (uint32_t)item_of(rr, e);
+                    s.id[e] = (uint32_t)item_of(rr, vt, e);
                     s.ok[e] = ok[e] && e >= stop;
                 }
                 if (lane == 0) my_state[q].cnt = cnt[q];
@@ -1408,13 +1410,13 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         // ---- 2. first round: per query a histogram over its own score range gives that query's cut
         float sc[kQ][kItems];
         score(wa, sc);
-        load(r + 2 * nblk, wa);
+        load(r + 2 * nblk, tid, wa);
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
             for (int e = 0; e < kItems; ++e)
-                if (item_of(r, e) < n_scan) { mn = fminf(mn, sc[q][e]); mx = fmaxf(mx, sc[q][e]); }
+                if (item_of(r, tid, e) < n_scan) { mn = fminf(mn, sc[q][e]); mx = fmaxf(mx, sc[q][e]); }
             wave_minmax(mn, mx);
             if (lane == 0) { ctl_of(q)->wave_min[wave] = mn; ctl_of(q)->wave_max[wave] = mx; }
         }
@@ -1438,7 +1440,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 #pragma unroll
             for (int e = 0; e < kItems; ++e) {
                 bk[q * kItems + e] = bucket_of<kFloorBins>(sc[q][e], lo, scale);
-                if (q < nq && item_of(r, e) < n_scan) atomicAdd(&fhist[q * kFloorBins + bk[q * kItems + e]], 1u);
+                if (q < nq && item_of(r, tid, e) < n_scan) atomicAdd(&fhist[q * kFloorBins + bk[q * kItems + e]], 1u);
             }
         }
         __syncthreads();
@@ -1453,36 +1455,49 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             if (lane == 0) my_state[q].floor_ge = next_up(ctl_of(q)->cut);
         }
         wave_sync();
-        offer_round(sc, r, bk, bstar);
-        r += nblk;
+        offer_round(sc, r, tid, bk, bstar);
     }
 
-    // ---- 3. stream: wb holds round r, wa round r + nblk; two rounds at a time, no branch between their loads.
-    // No workgroup-wide step in here: the shared floors keep every wave's candidates few, and a list that fills up all
-    // the same is sorted and cut back by its own wave.
-    while (r + nblk < rounds) {
-        {
-            float sc[kQ][kItems];
-            score(wb, sc);
-            load(r + 2 * nblk, wb);
-            offer_round(sc, r, nullptr, nullptr);
+    // ---- 3. stream.  Work is handed out in units of one wave's share of one of this workgroup's rounds: unit u is
+    // the share of wave u % kWaves in the workgroup's round u / kWaves (catalogue round blockIdx.x + that * nblk).
+    // wb and wa hold the wave's own shares of rounds 1 and 2; after those a wave takes the next free unit from a
+    // counter in LDS (requested one step before it is needed).  Without this the four waves that were launched first
+    // finish their static shares 15-25 % earlier than the other four and the scan ends on half-empty SIMDs.  Loads
+    // are unconditional (past the end they are clamped re-reads, never scored): the waits stay exact.
+    // No workgroup-wide step in here: the shared floors keep every wave's candidates few, and a list that fills up
+    // all the same is sorted and cut back by its own wave.
+    {
+        const uint32_t my_rounds = (uint32_t)((rounds - blockIdx.x + nblk - 1) / nblk);
+        const uint32_t units = my_rounds * kWaves;
+        int pending = 0;                                      // lane 0: result of the last counter request
+        auto request_unit = [&]() { if (lane == 0) pending = atomicAdd(&ctl_of(0)->next_unit, 1); };
+        auto requested_unit = [&]() -> uint32_t { return (uint32_t)__builtin_amdgcn_readfirstlane(pending); };
+        auto round_of = [&](uint32_t u) -> long long { return (long long)blockIdx.x + (long long)(u / kWaves) * nblk; };
+        auto vt_of = [&](uint32_t u) -> int { return (int)(u % kWaves) * kWave + lane; };
+        uint32_t ub = kWaves + wave, ua = 2 * kWaves + wave;  // units held by wb and wa
+        request_unit();
+        while (ub < units) {                                  // ub is the older of the two
+            {
+                float sc[kQ][kItems];
+                score(wb, sc);
+                const uint32_t done = ub;
+                ub = requested_unit();
+                request_unit();
+                load(round_of(ub), vt_of(ub), wb);
+                offer_round(sc, round_of(done), vt_of(done), nullptr, nullptr);
+            }
+            {
+                float sc[kQ][kItems];
+                const uint32_t done = ua;
+                if (done < units) score(wa, sc);
+                ua = requested_unit();
+                request_unit();
+                load(round_of(ua), vt_of(ua), wa);
+                if (done < units) offer_round(sc, round_of(done), vt_of(done), nullptr, nullptr);
+            }
+            turn -= 2;
+            if (turn < 0) { turn += kWaves; refresh_floors(); }
         }
-        r += nblk;
-        {
-            float sc[kQ][kItems];
-            score(wa, sc);
-            load(r + 2 * nblk, wa);
-            offer_round(sc, r, nullptr, nullptr);
-        }
-        r += nblk;
-        turn -= 2;
-        if (turn < 0) { turn += kWaves; refresh_floors(); }
-    }
-    if (r < rounds) {                                         // a last single round
-        float sc[kQ][kItems];
-        score(wb, sc);
-        offer_round(sc, r, nullptr, nullptr);
-        r += nblk;
     }
     // the fewer than 16 / M items after the last whole code vector: one per lane of one wave, per query
     if (blockIdx.x == 0 && wave == 0 && n_scan < a.N) {
