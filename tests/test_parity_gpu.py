@@ -86,6 +86,30 @@ def test_score_topk_single_query_mid_k(pq, oracle):
             assert_same_topk(pq, oracle, G, S, K, "midK")
 
 
+@pytest.mark.parametrize("N,m,B,K", [(40_000_003, 4, 1, 10), (30_000_001, 8, 2, 10), (18_000_001, 16, 1, 100),
+                                     (4_500_001, 64, 1, 10), (20_000_001, 3, 1, 10), (70_000_001, 2, 1, 64)])
+def test_score_topk_many_rounds(pq, oracle, N, m, B, K):
+    """Scans of sixteen or more rounds per workgroup, for the replicated-table, plain, wide-item and generic kernels:
+    the streaming loop with work units taken from the counter in LDS runs long, and the last item sits in the last,
+    ragged round."""
+    assert pq.pq_score_topk_workspace_bytes(N, B, m, 256, K) % 256 == 0
+    G = W.codes_uniform(N, m, 256, seed=m + B)
+    S = W.normal_f32(W.stream_key(N, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    assert_same_topk(pq, oracle, G, S, K, "many-rounds")
+    G[N - 1] = S[B - 1].argmax(axis=1)                 # the very last item wins for the last query
+    ids, _ = assert_same_topk(pq, oracle, G, S, K, "many-rounds+last")
+    if m >= 4:
+        assert ids[B - 1][0] == N - 1
+
+
+def test_subset_long_list(pq, oracle):
+    N, m = 20_000_000, 8
+    G = W.codes_uniform(N, m, 256, seed=9)
+    S = W.normal_f32(W.stream_key(9, W.STREAM_QUERIES), m * 256).reshape(1, m, 256)
+    V = W.candidate_list(N, 17_000_001, seed=2)
+    assert_same_subset_topk(pq, oracle, G, S, V, 10, "subset-long")
+
+
 @pytest.mark.parametrize("N,m,B", [(17_000_003, 4, 1), (17_000_001, 2, 1), (34_000_001, 1, 1), (6_000_001, 4, 3)])
 def test_score_topk_long_scans_replicated_tables(pq, oracle, N, m, B):
     """Catalogues long enough for the single-query kernel that keeps several copies of the score tables in LDS
