@@ -270,3 +270,34 @@ int pq_oracle_bruteforce_topk(const uint8_t* codes, const float* centroids, cons
     free(all);
     return 0;
 }
+
+/* Eq. 2 (Section 2): the reconstructed item embedding matrix W, float [N][d]: row i is the concatenation of the
+ * item's m sub-item embeddings psi_{k, G[i][k]}.  Copies only: exact. */
+int pq_oracle_reconstruct(const uint8_t* codes, const float* centroids, long long N, int d, int m, int b, float* W) {
+    if (!codes || !centroids || !W || N < 1 || d < 1 || m < 1 || b < 1 || b > 256 || d % m != 0) return -1;
+    const int s = d / m;
+    for (long long i = 0; i < N; ++i)
+        for (int k = 0; k < m; ++k) {
+            int g = codes[i * m + k];
+            if (g >= b) return -1;
+            for (int t = 0; t < s; ++t) W[i * d + (long long)k * s + t] = centroids[((size_t)k * b + g) * s + t];
+        }
+    return 0;
+}
+
+/* Eq. 3 (Section 2), the Transformer's default scoring r = W phi, in float64: scores double [B][N].
+ * The paper fixes no evaluation order for this product; float64 is the reference a float32 product is held to. */
+int pq_oracle_default_scores(const float* W, const float* queries, long long N, int B, int d, double* scores) {
+    if (!W || !queries || !scores || N < 1 || B < 1 || d < 1) return -1;
+    for (int q = 0; q < B; ++q) {
+        const float* phi = queries + (size_t)q * d;
+#pragma omp parallel for schedule(static)
+        for (long long i = 0; i < N; ++i) {
+            double r = 0.0;
+            for (int t = 0; t < d; ++t) r += (double)W[i * d + t] * (double)phi[t];
+            scores[(size_t)q * N + i] = r;
+        }
+    }
+    return 0;
+}
+

@@ -44,6 +44,8 @@ def _load():
         lib.pq_oracle_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P]
         lib.pq_oracle_pqtopk.argtypes = [P, P, P, LL, I, I, I, I, I, P, P]
         lib.pq_oracle_bruteforce_topk.argtypes = [P, P, P, LL, I, I, I, I, I, P, P]
+        lib.pq_oracle_reconstruct.argtypes = [P, P, LL, I, I, I, P]
+        lib.pq_oracle_default_scores.argtypes = [P, P, LL, I, I, P]
         _lib = lib
     return _lib
 
@@ -170,3 +172,30 @@ def bruteforce_topk(codes: np.ndarray, centroids: np.ndarray, queries: np.ndarra
     _check(_load().pq_oracle_bruteforce_topk(_p(codes), _p(centroids), _p(queries), N, B, d, m, b, K,
                                              _p(ids), _p(sc)), "bruteforce_topk")
     return ids, sc
+
+
+def reconstruct(codes: np.ndarray, centroids: np.ndarray) -> np.ndarray:
+    """Eq. 2: item embedding matrix W fp32 [N][d], row i = concatenation of item i's sub-item embeddings."""
+    codes = _c(codes, np.uint8)
+    centroids = _c(centroids, np.float32)
+    N, m = codes.shape
+    m2, b, s = centroids.shape
+    if m2 != m:
+        raise ValueError("shape mismatch")
+    W = np.empty((N, m * s), dtype=np.float32)
+    _check(_load().pq_oracle_reconstruct(_p(codes), _p(centroids), N, m * s, m, b, _p(W)), "reconstruct")
+    return W
+
+
+def default_scores(W: np.ndarray, queries: np.ndarray) -> np.ndarray:
+    """Eq. 3 in float64: r = W phi -> scores float64 [B][N]."""
+    W = _c(W, np.float32)
+    queries = _c(queries, np.float32)
+    N, d = W.shape
+    B, d2 = queries.shape
+    if d2 != d:
+        raise ValueError("shape mismatch")
+    out = np.empty((B, N), dtype=np.float64)
+    _check(_load().pq_oracle_default_scores(_p(W), _p(queries), N, B, d, _p(out)), "default_scores")
+    return out
+

@@ -457,3 +457,61 @@ def test_subset_rejects_bad_lists(oracle):
         oracle.score_topk_subset(G, S, np.array([0, G.shape[0]], dtype=np.int32), 1)
     with pytest.raises(Exception):
         oracle.score_topk_subset(G, S, np.array([0, 1], dtype=np.int32), 3)
+
+
+# ---------------------------------------------------------------- Eq. 2 / Eq. 3: reconstruction and the default scoring
+
+def test_reconstruct_hand_example(oracle):
+    # the two item embeddings the hand example spells out: w_2 = [0,1,1,1], w_3 = [0,1,2,-2]
+    import os
+    g = load_golden(os.path.join(os.path.dirname(__file__), "golden", "hand_example.txt"))
+    d, m, b = int(g["d"][0]), int(g["m"][0]), int(g["b"][0])
+    cent = np.stack([np.asarray(g[f"psi_{k}"], dtype=np.float32).reshape(b, d // m) for k in range(m)])
+    G = np.asarray(g["G"], dtype=np.uint8).reshape(-1, m)
+    Wm = oracle.reconstruct(G, cent)
+    assert Wm[2].tolist() == [0, 1, 1, 1] and Wm[3].tolist() == [0, 1, 2, -2]
+    r = oracle.default_scores(Wm, np.asarray(g["phi"], dtype=np.float32).reshape(1, d))
+    assert r[0].tolist() == [float(x) for x in g["scores"]]           # small integers: exact in any precision
+
+
+def test_reconstruct_is_a_block_gather(oracle):
+    rng = np.random.default_rng(5)
+    for N, d, m, b in ((50, 12, 3, 7), (200, 64, 4, 256), (31, 8, 8, 2), (17, 5, 1, 9)):
+        cent = rng.standard_normal((m, b, d // m)).astype(np.float32)
+        G = rng.integers(0, b, size=(N, m)).astype(np.uint8)
+        Wm = oracle.reconstruct(G, cent)
+        for i in (0, N // 2, N - 1):
+            for k in range(m):
+                assert np.array_equal(Wm[i, k * (d // m):(k + 1) * (d // m)], cent[k, G[i, k]])
+    with pytest.raises(ValueError):
+        oracle.reconstruct(np.full((3, 2), 9, dtype=np.uint8), np.zeros((2, 4, 3), dtype=np.float32))   # sub-id >= b
+
+
+def test_default_scores_agree_with_sub_item_scores(oracle):
+    # Eq. 3 on reconstructed embeddings and Eq. 4 + Eq. 5 are two formulas for the same number (Section 3): they meet
+    # within float32 rounding of the latter, and the exhaustive ranking is the one the brute-force routine returns
+    rng = np.random.default_rng(6)
+    N, d, m, b, B, K = 3000, 64, 8, 256, 3, 20
+    cent = (rng.standard_normal((m, b, d // m)) / np.sqrt(d)).astype(np.float32)
+    G = rng.integers(0, b, size=(N, m)).astype(np.uint8)
+    Q = rng.standard_normal((B, d)).astype(np.float32)
+    r = oracle.default_scores(oracle.reconstruct(G, cent), Q)
+    S = oracle.subitem_scores(Q, cent)
+    for q in range(B):
+        pq_scores = oracle.item_scores(G, S[q])
+        assert np.all(np.abs(r[q] - pq_scores) <= 1e-5 * np.maximum(np.abs(r[q]), 1.0))
+    bid, bsc = oracle.bruteforce_topk(G, cent, Q, K)
+    for q in range(B):
+        order = np.lexsort((np.arange(N), -r[q]))[:K]
+        assert np.array_equal(order, bid[q])
+        assert np.allclose(r[q][order], bsc[q], rtol=0, atol=1e-12)
+
+
+def test_default_scores_linear_and_exact_on_integers(oracle):
+    rng = np.random.default_rng(7)
+    Wm = rng.integers(-8, 9, size=(40, 16)).astype(np.float32)
+    Q = rng.integers(-8, 9, size=(2, 16)).astype(np.float32)
+    r = oracle.default_scores(Wm, Q)
+    assert np.array_equal(r, (Wm.astype(np.int64) @ Q.astype(np.int64).T).T.astype(np.float64))
+    assert np.array_equal(oracle.default_scores(Wm, Q[:1] + Q[1:]), r[:1] + r[1:])
+
