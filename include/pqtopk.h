@@ -107,6 +107,57 @@ int pq_score_topk_subset(const uint8_t* codes, const float* S, const int* subset
                          size_t workspace_bytes, void* stream);
 
 /*
+ * The two scoring methods the paper compares PQTopK with, on the same inputs: the Transformer's default scoring
+ * r = W phi over reconstructed item embeddings (Section 2, Eq. 2 and Eq. 3) and RecJPQ's original split-major
+ * scoring (Algorithm 2, Section 3).  Both write one score per item to memory; pq_topk_scores() then ranks them.
+ * They exist for comparison and cross-checks: pq_score_topk() is the product path and never materialises scores.
+ */
+
+/* Bytes of device workspace pq_topk_scores() needs; pure host arithmetic; 0 for arguments it would reject. */
+size_t pq_topk_scores_workspace_bytes(long long N, int B, int K);
+
+/*
+ * TopK (Algorithm 1's and Algorithm 2's last step) over score rows that sit in memory.
+ *   scores      in   float [B][ld]   row q holds query q's N scores (ld >= N; 16-byte aligned; ld % 4 == 0 if B > 1)
+ *   out_ids     out  int32 [B][K]    score descending, id ascending;  out_scores float [B][K]  (-0 returned as +0)
+ *   workspace        at least pq_topk_scores_workspace_bytes(N, B, K) bytes, 16-byte aligned
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE (N, B, K < 1, K > N, ld < N, N >= 2^31), PQ_ERR_UNSUPPORTED (K > PQ_MAX_K,
+ *         B > PQ_MAX_B), PQ_ERR_WORKSPACE, PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_topk_scores(const float* scores, long long ld, long long N, int B, int K, int* out_ids, float* out_scores,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Algorithm 2 (RecJPQScore) without its TopK: for k = 0 .. m-1 in turn, one pass over all items adds split k's sub-id
+ * score to the item's running score, scores[q][i] (+)= S[q][k][G[i][k]] (m launches, the score array re-read and
+ * re-written by each).  Per item the additions happen in the same order as in pq_score_topk(), so the scores are
+ * bit-equal to Eq. 5's as defined above.
+ *   codes uint8 [N][m];  S float [B][m][b];  scores out float [B][ld], ld >= N
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (m > PQ_MAX_M, B > PQ_MAX_B), PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_recjpq_scores(const uint8_t* codes, const float* S, long long N, int B, int m, int b, float* scores,
+                     long long ld, void* stream);
+
+/*
+ * Eq. 2: the reconstructed item embedding matrix, W[i] = psi_{0,G[i][0]} || ... || psi_{m-1,G[i][m-1]} (copies only).
+ *   codes uint8 [N][m];  centroids float [m][b][d/m];  W out float [N][d]  (N*d*4 bytes: 2.6 GB at N = 1.28M, d = 512)
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (m > PQ_MAX_M), PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_reconstruct_items(const uint8_t* codes, const float* centroids, long long N, int d, int m, int b, float* W,
+                         void* stream);
+
+/*
+ * Eq. 3, the default scoring: scores[q][i] = W[i] . phi_q in float32.  The paper fixes no order for this product;
+ * here sixteen lanes share a row of W, each accumulates every sixteenth 16-byte piece with fused multiply-adds, and
+ * the sixteen partial sums are added across lanes, so results agree with a float64 product to float32 rounding
+ * (not bit for bit with any particular serial order).  One pass over W per query.
+ *   W float [N][d] (16-byte aligned);  queries float [B][d] (16-byte aligned);  scores out float [B][ld], ld >= N
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (d % 4 != 0, d > 16384, B > PQ_MAX_B), PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_default_scores(const float* W, const float* queries, long long N, int B, int d, float* scores, long long ld,
+                      void* stream);
+
+/*
  * Measurement aid: enqueues the catalogue scan kernel of pq_score_topk() (the kernel that streams `codes`) once
  * untimed and then `iters` times back to back between two HIP events on `stream`, enqueues the fold so the outputs
  * are those of pq_score_topk(), waits for the stream, and stores elapsed / iters in milliseconds in *scan_ms (host

@@ -47,6 +47,16 @@ def lib() -> ctypes.CDLL:
         L.pq_score_topk_subset_workspace_bytes.restype = SZ
         L.pq_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P, P, SZ, P]
         L.pq_score_topk_subset.restype = I
+        L.pq_topk_scores_workspace_bytes.argtypes = [LL, I, I]
+        L.pq_topk_scores_workspace_bytes.restype = SZ
+        L.pq_topk_scores.argtypes = [P, LL, LL, I, I, P, P, P, SZ, P]
+        L.pq_topk_scores.restype = I
+        L.pq_recjpq_scores.argtypes = [P, P, LL, I, I, I, P, LL, P]
+        L.pq_recjpq_scores.restype = I
+        L.pq_reconstruct_items.argtypes = [P, P, LL, I, I, I, P, P]
+        L.pq_reconstruct_items.restype = I
+        L.pq_default_scores.argtypes = [P, P, LL, I, I, P, LL, P]
+        L.pq_default_scores.restype = I
         L.pq_strerror.argtypes = [I]
         L.pq_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -151,6 +161,84 @@ def pq_score_topk_subset(codes: torch.Tensor, S: torch.Tensor, subset: torch.Ten
     if rc != PQ_OK:
         raise PQError(rc, "pq_score_topk_subset")
     return out_ids, out_scores
+
+
+def pq_topk_scores_workspace_bytes(N: int, B: int, K: int) -> int:
+    return int(lib().pq_topk_scores_workspace_bytes(N, B, K))
+
+
+def pq_topk_scores(scores: torch.Tensor, K: int, N: Optional[int] = None, workspace: Optional[torch.Tensor] = None,
+                   out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None
+                   ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """TopK over score rows: scores fp32 [B][ld] (the first N of each row count; default N = ld)."""
+    _dev(scores, torch.float32, "scores")
+    B, ld = scores.shape
+    N = ld if N is None else N
+    if workspace is None:
+        workspace = torch.empty(max(pq_topk_scores_workspace_bytes(N, B, K), 16), dtype=torch.uint8, device=scores.device)
+    if out_ids is None:
+        out_ids = torch.empty((B, K), dtype=torch.int32, device=scores.device)
+    if out_scores is None:
+        out_scores = torch.empty((B, K), dtype=torch.float32, device=scores.device)
+    _dev(out_ids, torch.int32, "out_ids")
+    _dev(out_scores, torch.float32, "out_scores")
+    rc = lib().pq_topk_scores(scores.data_ptr(), ld, N, B, K, out_ids.data_ptr(), out_scores.data_ptr(),
+                              workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_topk_scores")
+    return out_ids, out_scores
+
+
+def pq_recjpq_scores(codes: torch.Tensor, S: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Algorithm 2 without its TopK: codes uint8 [N][m], S fp32 [B][m][b] -> scores fp32 [B][ld] (ld = N rounded up
+    to a multiple of 4 when allocated here)."""
+    _dev(codes, torch.uint8, "codes")
+    _dev(S, torch.float32, "S")
+    N, m = codes.shape
+    B, m2, b = S.shape
+    if m2 != m:
+        raise PQError(PQ_ERR_SHAPE, "pq_recjpq_scores")
+    if out is None:
+        out = torch.empty((B, (N + 3) // 4 * 4), dtype=torch.float32, device=codes.device)
+    _dev(out, torch.float32, "scores")
+    rc = lib().pq_recjpq_scores(codes.data_ptr(), S.data_ptr(), N, B, m, b, out.data_ptr(), out.shape[1], _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_recjpq_scores")
+    return out
+
+
+def pq_reconstruct_items(codes: torch.Tensor, centroids: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 2: codes uint8 [N][m], centroids fp32 [m][b][d/m] -> W fp32 [N][d]."""
+    _dev(codes, torch.uint8, "codes")
+    _dev(centroids, torch.float32, "centroids")
+    N, m = codes.shape
+    m2, b, s = centroids.shape
+    if m2 != m:
+        raise PQError(PQ_ERR_SHAPE, "pq_reconstruct_items")
+    if out is None:
+        out = torch.empty((N, m * s), dtype=torch.float32, device=codes.device)
+    _dev(out, torch.float32, "W")
+    rc = lib().pq_reconstruct_items(codes.data_ptr(), centroids.data_ptr(), N, m * s, m, b, out.data_ptr(), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_reconstruct_items")
+    return out
+
+
+def pq_default_scores(W: torch.Tensor, queries: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 3: W fp32 [N][d], queries fp32 [B][d] -> scores fp32 [B][ld]."""
+    _dev(W, torch.float32, "W")
+    _dev(queries, torch.float32, "queries")
+    N, d = W.shape
+    B, d2 = queries.shape
+    if d2 != d:
+        raise PQError(PQ_ERR_SHAPE, "pq_default_scores")
+    if out is None:
+        out = torch.empty((B, (N + 3) // 4 * 4), dtype=torch.float32, device=W.device)
+    _dev(out, torch.float32, "scores")
+    rc = lib().pq_default_scores(W.data_ptr(), queries.data_ptr(), N, B, d, out.data_ptr(), out.shape[1], _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_default_scores")
+    return out
 
 
 def pq_score_topk_profile(codes: torch.Tensor, S: torch.Tensor, K: int, iters: int,

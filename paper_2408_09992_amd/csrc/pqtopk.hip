@@ -603,6 +603,61 @@ struct ScanArgs {
     uint32_t n_items;    // items in the catalogue (bounds the ids read from `subset`)
 };
 
+// The end of a single-query scan: the waves' lists -> the workgroup's exact K best, sorted, in L.sorted (zero where
+// fewer than K exist).  Every thread of the workgroup calls it once its wave has offered everything.
+template <int NT>
+__device__ __forceinline__ void workgroup_select(const ScanLds& L, Ctl* ctl, WaveTopK& top, int K, int cap, int candmax,
+                                                 int tid) {
+    constexpr int NW = NT / kWave;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    if (lane == 0) {
+        ctl->wave_cnt[wave] = top.cnt;
+        ctl->wave_max[wave] = top.thr != 0ull ? score_of_key(top.thr) : -__builtin_inff();   // <= the wave's K-th best
+    }
+    if (tid == 0) ctl->ncand = 0;
+    __syncthreads();
+    // lane w of every wave holds wave w's count and floor: totals by cross-lane operations, one LDS round trip
+    static_assert(NW <= kWave, "one lane per wave");
+    const uint32_t cnt_w = lane < NW ? (uint32_t)ctl->wave_cnt[lane] : 0u;
+    float fl_lo = lane < NW ? ctl->wave_max[lane] : -__builtin_inff(), wg_floor = fl_lo;
+    const uint32_t upto = wave_prefix_sum(cnt_w);
+    int total = __builtin_amdgcn_readlane((int)upto, kWave - 1);
+    const int before = __builtin_amdgcn_readlane((int)(upto - cnt_w), wave);
+    wave_minmax(fl_lo, wg_floor);
+    if (total <= candmax) {
+        if (total > kFilterMin) {
+            // a long scan leaves every wave with its own K best and more: only keys that reach the best of the waves'
+            // K-th scores can be among the workgroup's K best (that score is a lower bound of the workgroup's K-th)
+            for (int t0 = 0; t0 < top.cnt; t0 += kWave) {
+                const uint64_t key = t0 + lane < top.cnt ? top.buf[t0 + lane] : 0ull;
+                const bool take = key != 0ull && score_of_key(key) >= wg_floor;
+                const uint64_t mask = __ballot(take);
+                int base = 0;
+                if (lane == 0 && mask != 0) base = atomicAdd(&ctl->ncand, __popcll(mask));
+                base = __builtin_amdgcn_readfirstlane(base);
+                if (take) L.cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+            }
+            __syncthreads();
+            total = ctl->ncand;
+        } else {
+            for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
+        }
+        rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
+    } else {
+        // too many keys for one ranking (long lists, large K): histogram over the listed keys' own range, or a sort
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        for (int t = lane; t < top.cnt; t += kWave) {
+            const float v = score_of_key(top.buf[t]);
+            mn = fminf(mn, v); mx = fmaxf(mx, v);
+        }
+        float lo, scale;
+        set_range<NW>(mn, mx, ctl, tid, lo, scale);
+        for (int t = top.cnt + lane; t < cap; t += kWave) top.buf[t] = 0;
+        __syncthreads();
+        block_select<NT>(L.lists, NW * cap, K, L.sorted, L.cand, candmax, L.hist, ctl, tid);
+    }
+}
+
 // Items a thread holds per round.  M > 0: m is M and one 16-byte vector carries 16/M items; M == 0: any m, one item
 // per slot, row loads sized by m's alignment.
 template <int M>
@@ -980,45 +1035,8 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     }
 
     // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
-    if (lane == 0) {
-        ctl->wave_cnt[wave] = top.cnt;
-        ctl->wave_max[wave] = top.thr != 0ull ? score_of_key(top.thr) : -__builtin_inff();   // <= the wave's K-th best
-    }
-    if (tid == 0) ctl->ncand = 0;
-    __syncthreads();
-    // lane w of every wave holds wave w's count and floor: totals by cross-lane operations, one LDS round trip
-    static_assert(NW <= kWave, "one lane per wave");
-    const uint32_t cnt_w = lane < NW ? (uint32_t)ctl->wave_cnt[lane] : 0u;
-    float fl_lo = lane < NW ? ctl->wave_max[lane] : -__builtin_inff(), wg_floor = fl_lo;
-    const uint32_t upto = wave_prefix_sum(cnt_w);
-    int total = __builtin_amdgcn_readlane((int)upto, kWave - 1);
-    const int before = __builtin_amdgcn_readlane((int)(upto - cnt_w), wave);
-    wave_minmax(fl_lo, wg_floor);
+    workgroup_select<NT>(L, ctl, top, K, a.cap, a.candmax, tid);
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
-    if (total <= a.candmax) {
-        if (total > kFilterMin) {
-            // a long scan leaves every wave with its own K best and more: only keys that reach the best of the waves'
-            // K-th scores can be among the workgroup's K best (that score is a lower bound of the workgroup's K-th)
-            for (int t0 = 0; t0 < top.cnt; t0 += kWave) {
-                const uint64_t key = t0 + lane < top.cnt ? top.buf[t0 + lane] : 0ull;
-                const bool take = key != 0ull && score_of_key(key) >= wg_floor;
-                const uint64_t mask = __ballot(take);
-                int base = 0;
-                if (lane == 0 && mask != 0) base = atomicAdd(&ctl->ncand, __popcll(mask));
-                base = __builtin_amdgcn_readfirstlane(base);
-                if (take) L.cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
-            }
-            __syncthreads();
-            total = ctl->ncand;
-        } else {
-            for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
-        }
-        rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
-    } else {
-        for (int t = top.cnt + lane; t < a.cap; t += kWave) top.buf[t] = 0;
-        __syncthreads();
-        block_select<NT>(L.lists, NW * a.cap, K, L.sorted, L.cand, a.candmax, L.hist, ctl, tid);
-    }
     for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
 }
 
@@ -1664,6 +1682,161 @@ int next_pow2(int x) {
     return p;
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// The paper's two other scoring methods (Section 2 and Algorithm 2), for comparison on the same inputs.  Both
+// materialise a score per item in HBM, which PQTopK never does; TopK over that array is a kernel of its own.
+
+// TopK of score rows that already sit in memory: scores float [B][ld], N of them used per row.  grid = (blocks, B).
+// Same lists, keys and final selection as the catalogue scan; a wave's first floor is one that K of its lanes' best
+// scores reach.  Leaves each workgroup's K best keys in the workspace for fold_topk_kernel.
+struct TopkScoresArgs {
+    const float* scores;
+    long long ld, N;
+    int K, cap, candmax, prune_at;
+    uint64_t* ws_keys;   // [B][nblk][K]
+};
+
+constexpr int kScoreVecs = 4;            // 16-byte vectors (four scores each) a thread holds per round
+
+__global__ __launch_bounds__(kThreads, 4) void topk_scores_kernel(TopkScoresArgs a) {
+    constexpr int NT = kThreads, NW = kWaves;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const ScanLds L = carve_scan(smem, 0, a.cap, a.candmax, NW);
+    Ctl* ctl = L.ctl;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int q = blockIdx.y, nblk = gridDim.x, K = a.K;
+    const float* row = a.scores + (size_t)q * a.ld;
+    const float4* row4 = reinterpret_cast<const float4*>(row);
+    const uint32_t total_vec = (uint32_t)(a.N / 4);          // whole vectors; the up to three scores after them come last
+    const uint32_t round_vecs = (uint32_t)NT * kScoreVecs;
+    const uint32_t rounds = (total_vec + round_vecs - 1) / round_vecs;
+    const uint32_t last_vec = total_vec ? total_vec - 1 : 0;
+    WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
+
+    auto vec_of = [&](uint32_t rr, int u) { return rr * round_vecs + (uint32_t)u * NT + (uint32_t)tid; };
+    auto load = [&](uint32_t rr, float4 (&w)[kScoreVecs]) {   // branch-free: past the end the last vector is re-read
+#pragma unroll
+        for (int u = 0; u < kScoreVecs; ++u) {
+            const uint32_t v = vec_of(rr, u);
+            w[u] = row4[v < last_vec ? v : last_vec];
+        }
+    };
+    bool first = true;
+    auto offer = [&](const float4 (&w)[kScoreVecs], uint32_t rr) {
+        float sc[kScoreVecs * 4];
+        float best = -__builtin_inff();
+#pragma unroll
+        for (int u = 0; u < kScoreVecs; ++u) {
+            sc[4 * u] = w[u].x; sc[4 * u + 1] = w[u].y; sc[4 * u + 2] = w[u].z; sc[4 * u + 3] = w[u].w;
+            if (vec_of(rr, u) < total_vec) best = fmaxf(best, fmaxf(fmaxf(w[u].x, w[u].y), fmaxf(w[u].z, w[u].w)));
+        }
+        if (first && K <= kWave) top.floor_ge = wave_floor_for_k(best, K);
+        first = false;
+        if (__ballot(best >= top.floor_ge) == 0) return;
+#pragma unroll
+        for (int e = 0; e < kScoreVecs * 4; ++e) {
+            const uint32_t v = vec_of(rr, e / 4);
+            const bool take = v < total_vec && sc[e] >= top.floor_ge;
+            const uint64_t mask = __ballot(take);
+            if (mask != 0) top.append(mask, take, sc[e], v * 4u + (uint32_t)(e % 4), lane);
+        }
+        if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
+    };
+
+    if (total_vec != 0) {
+        float4 wa[kScoreVecs], wb[kScoreVecs];
+        uint32_t r = blockIdx.x;                              // this workgroup's rounds: r, r + nblk, ...
+        load(r, wa);
+        load(r + nblk, wb);
+        for (; r < rounds; r += 2 * nblk) {                   // (a round past the end offers nothing)
+            offer(wa, r);
+            load(r + 2 * nblk, wa);
+            offer(wb, r + nblk);
+            load(r + 3 * nblk, wb);
+        }
+    }
+    if (blockIdx.x == 0 && wave == 0) {                       // the scores after the last whole vector
+        const long long item = (long long)total_vec * 4 + lane;
+        const bool have = item < a.N;
+        const float sc = have ? row[item] : 0.0f;
+        const bool take = have && sc >= top.floor_ge;
+        const uint64_t mask = __ballot(take);
+        if (mask != 0) top.append(mask, take, sc, (uint32_t)item, lane);
+    }
+    workgroup_select<NT>(L, ctl, top, K, a.cap, a.candmax, tid);
+    uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
+    for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
+}
+
+// Algorithm 2 (RecJPQScore), one pass of its outer loop: split k's sub-id scores are added to every item's running
+// score, scores[q][i] (+)= S[q][k][G[i][k]].  The caller runs k = 0 .. m-1 in order, so every item's sum is the
+// same left-to-right chain as in Algorithm 1.  grid = (item blocks, B); a thread owns four consecutive items.
+constexpr int kRecjpqThreads = 256;
+__global__ __launch_bounds__(kRecjpqThreads) void recjpq_pass_kernel(const uint8_t* codes, const float* S, float* scores,
+                                                                     long long ld, long long N, int m, int b, int k) {
+    __shared__ float row[kLutStride];
+    const int q = blockIdx.y;
+    for (int j = threadIdx.x; j < kLutStride; j += kRecjpqThreads)
+        row[j] = j < b ? S[((size_t)q * m + k) * b + j] : 0.0f;
+    __syncthreads();
+    float* out = scores + (size_t)q * ld;
+    const long long i0 = ((long long)blockIdx.x * kRecjpqThreads + threadIdx.x) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const long long i = i0 + j;
+        if (i < N) {
+            const float s = row[codes[i * m + k]];
+            out[i] = k == 0 ? s : out[i] + s;
+        }
+    }
+}
+
+// Eq. 2: the reconstructed item embedding matrix, W[i] = psi_{0,G[i][0]} || .. || psi_{m-1,G[i][m-1]}; one element per
+// thread, grid-stride.
+__global__ __launch_bounds__(256) void reconstruct_kernel(const uint8_t* codes, const float* centroids, float* W,
+                                                          long long N, int d, int m, int b) {
+    const int s = d / m;
+    const long long total = N * d, stride = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const long long i = idx / d;
+        const int t = (int)(idx % d), k = t / s;
+        W[idx] = centroids[((size_t)k * b + codes[i * m + k]) * s + (t % s)];
+    }
+}
+
+// Eq. 3, the default scoring r = W phi for one query per grid row, float32: sixteen lanes share an item's row of W
+// (each takes every sixteenth 16-byte piece and multiplies-and-adds it into one accumulator, in order), then their
+// sixteen partial sums are added up across the lanes.  d must be a multiple of 4.  Dynamic LDS: the query, d floats.
+constexpr int kDefaultThreads = 256;
+__global__ __launch_bounds__(kDefaultThreads) void default_scores_kernel(const float* W, const float* queries, float* scores,
+                                                                        long long ld, long long N, int d) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float4* phi4 = reinterpret_cast<float4*>(smem);
+    const int q = blockIdx.y, d4 = d / 4;
+    for (int c = threadIdx.x; c < d4; c += kDefaultThreads)
+        phi4[c] = reinterpret_cast<const float4*>(queries + (size_t)q * d)[c];
+    __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1), sub = lane & 15;
+    const long long rows_per_pass = (long long)gridDim.x * (kDefaultThreads / 16);
+    for (long long row = (long long)blockIdx.x * (kDefaultThreads / 16) + threadIdx.x / 16; row < N; row += rows_per_pass) {
+        // (the sixteen lanes of a group share `row`, so they enter and leave the loop together)
+        const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)row * d);
+        float acc = 0.0f;
+        for (int c = sub; c < d4; c += 16) {
+            const float4 w = w4[c], p = phi4[c];
+            acc = __builtin_fmaf(w.x, p.x, acc);
+            acc = __builtin_fmaf(w.y, p.y, acc);
+            acc = __builtin_fmaf(w.z, p.z, acc);
+            acc = __builtin_fmaf(w.w, p.w, acc);
+        }
+        acc += dpp_f32<kDppRowShr + 1>(0.0f, acc);
+        acc += dpp_f32<kDppRowShr + 2>(0.0f, acc);
+        acc += dpp_f32<kDppRowShr + 4>(0.0f, acc);
+        acc += dpp_f32<kDppRowShr + 8>(0.0f, acc);            // lane 15 of each group of sixteen holds the sum
+        if (sub == 15) scores[(size_t)q * ld + row] = acc;
+    }
+}
+
 struct ScanPlan {
     int copies;      // single-query kernel: copies of the score tables in LDS (1 or kTableCopies)
     bool tiled;      // batched kernel: kQ queries per workgroup
@@ -1973,6 +2146,112 @@ int pq_score_topk_subset(const uint8_t* codes, const float* S, const int* subset
     int rc = enqueue_scan(p, codes, S, n_subset, B, m, b, K, workspace, st, subset, N);
     if (rc != PQ_OK) return rc;
     return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+}
+
+// ---- the comparison scorers (Section 2's default scoring, Algorithm 2) and TopK over score rows
+
+namespace {
+// plan of pq_topk_scores: blocks per query, list and candidate sizes (as for the scan), LDS of the two launches
+ScanPlan make_topk_scores_plan(long long N, int B, int K) {
+    ScanPlan p = {};
+    const long long vecs = N / 4;
+    const long long per_round = (long long)kThreads * kScoreVecs;
+    long long rounds = (vecs + per_round - 1) / per_round;
+    if (rounds < 1) rounds = 1;
+    long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;
+    if (most < 8) most = 8;
+    p.nblk = (int)(rounds < most ? rounds : most);
+    p.cap = next_pow2(K + kWave);
+    if (p.cap < 128) p.cap = 128;
+    p.candmax = next_pow2(2 * K);
+    if (p.candmax < 512) p.candmax = 512;
+    p.stage_keys = next_pow2(2 * K);
+    if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
+    p.copies = 1;
+    p.scan_dyn_lds = p.scan_lds = scan_lds_bytes(0, p.cap, p.candmax, K, kWaves);
+    p.fold_lds = fold_lds_bytes(p.stage_keys, p.candmax, K);
+    return p;
+}
+
+int check_topk_scores_shape(long long ld, long long N, int B, int K) {
+    if (N < 1 || B < 1 || K < 1 || K > N || ld < N || N >= 2147483648LL) return PQ_ERR_SHAPE;
+    if (K > PQ_MAX_K || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
+    return PQ_OK;
+}
+}  // namespace
+
+size_t pq_topk_scores_workspace_bytes(long long N, int B, int K) {
+    if (check_topk_scores_shape(N, N, B, K) != PQ_OK) return 0;
+    const ScanPlan p = make_topk_scores_plan(N, B, K);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
+    return workspace_bytes(p, B, K);
+}
+
+int pq_topk_scores(const float* scores, long long ld, long long N, int B, int K, int* out_ids, float* out_scores,
+                   void* workspace, size_t workspace_bytes_given, void* stream) {
+    if (!scores || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
+    int rc = check_topk_scores_shape(ld, N, B, K);
+    if (rc != PQ_OK) return rc;
+    const ScanPlan p = make_topk_scores_plan(N, B, K);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)scores & 15) || (B > 1 && (ld & 3)) || ((uintptr_t)workspace & 15) || ((uintptr_t)out_ids & 3) ||
+        ((uintptr_t)out_scores & 3))
+        return PQ_ERR_ALIGN;
+    if (workspace_bytes_given < workspace_bytes(p, B, K)) return PQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TopkScoresArgs a;
+    a.scores = scores; a.ld = ld; a.N = N; a.K = K; a.cap = p.cap; a.candmax = p.candmax;
+    a.prune_at = (K <= 28) ? 2 * K + 8 : 0;
+    a.ws_keys = static_cast<uint64_t*>(workspace);
+    hipError_t e = allow_lds(topk_scores_kernel, p.scan_dyn_lds);
+    if (e != hipSuccess) return record_hip(e);
+    hipLaunchKernelGGL(topk_scores_kernel, dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return record_hip(e);
+    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+}
+
+int pq_recjpq_scores(const uint8_t* codes, const float* S, long long N, int B, int m, int b, float* scores,
+                     long long ld, void* stream) {
+    if (!codes || !S || !scores) return PQ_ERR_NULL;
+    if (N < 1 || B < 1 || m < 1 || b < 1 || b > 256 || ld < N || N >= 2147483648LL) return PQ_ERR_SHAPE;
+    if (m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)S & 3) || ((uintptr_t)scores & 3)) return PQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)((N + 4LL * kRecjpqThreads - 1) / (4LL * kRecjpqThreads)), B);
+    for (int k = 0; k < m; ++k) {                            // Algorithm 2's outer loop: one pass over the items per split
+        hipLaunchKernelGGL(recjpq_pass_kernel, grid, dim3(kRecjpqThreads), 0, st, codes, S, scores, ld, N, m, b, k);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return record_hip(e);
+    }
+    return PQ_OK;
+}
+
+int pq_reconstruct_items(const uint8_t* codes, const float* centroids, long long N, int d, int m, int b, float* W,
+                         void* stream) {
+    if (!codes || !centroids || !W) return PQ_ERR_NULL;
+    if (N < 1 || d < 1 || m < 1 || b < 1 || b > 256 || d % m != 0 || N >= 2147483648LL) return PQ_ERR_SHAPE;
+    if (m > PQ_MAX_M) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)centroids & 3) || ((uintptr_t)W & 3)) return PQ_ERR_ALIGN;
+    const long long total = N * d;
+    long long blocks = (total + 255) / 256;
+    if (blocks > 64 * kAssumedCUs) blocks = 64 * kAssumedCUs;
+    hipLaunchKernelGGL(reconstruct_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), codes,
+                       centroids, W, N, d, m, b);
+    return record_hip(hipGetLastError());
+}
+
+int pq_default_scores(const float* W, const float* queries, long long N, int B, int d, float* scores, long long ld,
+                      void* stream) {
+    if (!W || !queries || !scores) return PQ_ERR_NULL;
+    if (N < 1 || B < 1 || d < 1 || ld < N || N >= 2147483648LL) return PQ_ERR_SHAPE;
+    if (B > PQ_MAX_B || d % 4 != 0 || (size_t)d * sizeof(float) > 64 * 1024) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)W & 15) || ((uintptr_t)queries & 15) || ((uintptr_t)scores & 3)) return PQ_ERR_ALIGN;
+    long long blocks = (N + kDefaultThreads / 16 - 1) / (kDefaultThreads / 16);
+    if (blocks > 16 * kAssumedCUs) blocks = 16 * kAssumedCUs;
+    hipLaunchKernelGGL(default_scores_kernel, dim3((unsigned)blocks, B), dim3(kDefaultThreads), (size_t)d * sizeof(float),
+                       static_cast<hipStream_t>(stream), W, queries, scores, ld, N, d);
+    return record_hip(hipGetLastError());
 }
 
 const char* pq_strerror(int code) {

@@ -24,6 +24,12 @@ def lib(pqlib_path):
     L.pq_score_topk_subset_workspace_bytes.argtypes = [LL, I, I, I, I]
     L.pq_score_topk_subset_workspace_bytes.restype = SZ
     L.pq_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P, P, SZ, P]
+    L.pq_topk_scores_workspace_bytes.argtypes = [LL, I, I]
+    L.pq_topk_scores_workspace_bytes.restype = SZ
+    L.pq_topk_scores.argtypes = [P, LL, LL, I, I, P, P, P, SZ, P]
+    L.pq_recjpq_scores.argtypes = [P, P, LL, I, I, I, P, LL, P]
+    L.pq_reconstruct_items.argtypes = [P, P, LL, I, I, I, P, P]
+    L.pq_default_scores.argtypes = [P, P, LL, I, I, P, LL, P]
     L.pq_strerror.argtypes = [I]
     L.pq_strerror.restype = ctypes.c_char_p
     return L
@@ -147,6 +153,43 @@ def test_score_topk_subset_argument_errors(lib):
     for bad in ((0, 1, 8, 256, 1), (10, 1, 8, 256, 11), (10, 0, 8, 256, 1), (10, 1, 0, 256, 1), (10, 1, 8, 257, 1),
                 (2 ** 31, 1, 8, 256, 10), (10 ** 6, 1, 8, 256, 513), (10 ** 6, 1, 129, 256, 10)):
         assert ws(*bad) == 0, bad
+
+
+def test_comparison_scorers_argument_errors(lib):
+    p, big = 0x10000, 1 << 30
+    f = lib.pq_topk_scores
+    assert f(None, 1000, 1000, 1, 10, p, p, p, big, None) == NULL
+    assert f(p, 1000, 1000, 1, 10, None, p, p, big, None) == NULL
+    assert f(p, 1000, 1000, 1, 10, p, p, None, big, None) == NULL
+    assert f(p, 1000, 0, 1, 10, p, p, p, big, None) == SHAPE
+    assert f(p, 1000, 1000, 0, 10, p, p, p, big, None) == SHAPE
+    assert f(p, 1000, 1000, 1, 0, p, p, p, big, None) == SHAPE
+    assert f(p, 1000, 1000, 1, 1001, p, p, p, big, None) == SHAPE
+    assert f(p, 999, 1000, 1, 10, p, p, p, big, None) == SHAPE               # row shorter than N
+    assert f(p, 10 ** 6, 10 ** 6, 1, 513, p, p, p, big, None) == UNSUPPORTED
+    assert f(p + 4, 1000, 1000, 1, 10, p, p, p, big, None) == ALIGN
+    assert f(p, 1001, 1000, 2, 10, p, p, p, big, None) == ALIGN              # rows of a batch must stay 16-byte aligned
+    need = lib.pq_topk_scores_workspace_bytes(1000, 1, 10)
+    assert need > 0 and need % 16 == 0
+    assert f(p, 1000, 1000, 1, 10, p, p, p, need - 1, None) == WORKSPACE
+    for bad in ((0, 1, 1), (10, 0, 1), (10, 1, 0), (10, 1, 11), (2 ** 31, 1, 1), (10 ** 6, 1, 513)):
+        assert lib.pq_topk_scores_workspace_bytes(*bad) == 0, bad
+
+    g = lib.pq_recjpq_scores
+    assert g(None, p, 1000, 1, 8, 256, p, 1000, None) == NULL and g(p, p, 1000, 1, 8, 256, None, 1000, None) == NULL
+    assert g(p, p, 0, 1, 8, 256, p, 1000, None) == SHAPE and g(p, p, 1000, 1, 8, 257, p, 1000, None) == SHAPE
+    assert g(p, p, 1000, 1, 8, 256, p, 999, None) == SHAPE
+    assert g(p, p, 1000, 1, 129, 256, p, 1000, None) == UNSUPPORTED and g(p, p + 2, 1000, 1, 8, 256, p, 1000, None) == ALIGN
+
+    h = lib.pq_reconstruct_items
+    assert h(None, p, 1000, 64, 4, 256, p, None) == NULL and h(p, p, 1000, 64, 4, 256, None, None) == NULL
+    assert h(p, p, 1000, 66, 4, 256, p, None) == SHAPE and h(p, p, 0, 64, 4, 256, p, None) == SHAPE
+    assert h(p, p, 1000, 258, 129, 256, p, None) == UNSUPPORTED and h(p, p, 1000, 64, 4, 256, p + 1, None) == ALIGN
+
+    e = lib.pq_default_scores
+    assert e(None, p, 1000, 1, 64, p, 1000, None) == NULL and e(p, None, 1000, 1, 64, p, 1000, None) == NULL
+    assert e(p, p, 1000, 0, 64, p, 1000, None) == SHAPE and e(p, p, 1000, 1, 64, p, 999, None) == SHAPE
+    assert e(p, p, 1000, 1, 66, p, 1000, None) == UNSUPPORTED and e(p + 4, p, 1000, 1, 64, p, 1000, None) == ALIGN
 
 
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):

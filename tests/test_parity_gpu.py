@@ -286,6 +286,81 @@ def test_subset_errors_reach_python(pq):
         pq.pq_score_topk_subset(G, S, V.to(torch.int64), 10)
 
 
+# ---------------------------------------------------------------- the paper's two other scorers (comparison path)
+
+def test_topk_scores_matches_oracle(pq, oracle):
+    for N in (1, 3, 4, 5, 63, 1000, 4099, 70_001, 1_280_000, 3_000_003):
+        for B in ((1, 3) if N < 2_000_000 else (1,)):
+            ld = (N + 3) // 4 * 4 + (8 if B > 1 else 0)
+            sc = np.zeros((B, ld), dtype=np.float32)
+            sc[:, :N] = W.normal_f32(W.stream_key(N + B, W.STREAM_QUERIES), B * N).reshape(B, N)
+            if N > 100:
+                sc[:, 7] = -0.0                                  # a negative zero, and a tie at the very top
+                sc[0, N - 1] = sc[0, 11] = sc[0].max() + 1.0
+            for K in sorted({1, min(N, 10), min(N, 100), min(N, 512)}):
+                print(f"case topk-scores N={N} B={B} K={K}", flush=True)
+                ids, out = pq.pq_topk_scores(dev(sc), K, N=N)
+                torch.cuda.synchronize()
+                ids, out = ids.cpu().numpy(), out.cpu().numpy()
+                for q in range(B):
+                    rid, rsc = oracle.topk(sc[q, :N], K)
+                    assert np.array_equal(ids[q], rid)
+                    assert np.array_equal(out[q], rsc)               # same values (a -0 comes back as +0)
+                    assert not np.any(np.signbit(out[q]) & (out[q] == 0))
+
+
+@pytest.mark.parametrize("N,m,b,B", [(1, 8, 256, 1), (1027, 3, 7, 2), (70_001, 8, 256, 3), (300_000, 64, 256, 1),
+                                     (1_280_000, 8, 256, 1)])
+def test_recjpq_scores_equal_algorithm_1(pq, oracle, N, m, b, B):
+    # Algorithm 2 adds the same terms in the same order per item: bit-equal scores, hence the same TopK as PQTopK
+    G = W.codes_uniform(N, m, b, seed=N)
+    S = W.normal_f32(W.stream_key(N, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+    sc = pq.pq_recjpq_scores(dev(G), dev(S))
+    torch.cuda.synchronize()
+    got = sc.cpu().numpy()[:, :N]
+    for q in range(B):
+        ref = oracle.item_scores(G, S[q], split_major=True)
+        assert np.array_equal(got[q].view(np.uint32), ref.view(np.uint32))
+    K = min(N, 10)
+    ids, out = pq.pq_topk_scores(sc, K, N=N)
+    ids2, out2 = pq.pq_score_topk(dev(G), dev(S), K)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, ids2) and torch.equal(out, out2)
+    rid, rsc = oracle.score_topk(G, S, K)
+    assert np.array_equal(ids.cpu().numpy(), rid)
+
+
+@pytest.mark.parametrize("N,d,m,b,B", [(1, 8, 2, 4, 1), (1000, 64, 4, 256, 2), (4099, 96, 3, 7, 1), (200_000, 512, 8, 256, 2)])
+def test_default_scoring_against_float64(pq, oracle, N, d, m, b, B):
+    cent = W.centroids(m, b, d, seed=N)
+    Q = W.queries(B, d, seed=N)
+    G = W.codes_uniform(N, m, b, seed=N)
+    Wd = pq.pq_reconstruct_items(dev(G), dev(cent))
+    torch.cuda.synchronize()
+    assert np.array_equal(Wd.cpu().numpy(), oracle.reconstruct(G, cent))           # Eq. 2 copies: exact
+    sc = pq.pq_default_scores(Wd, dev(Q))
+    torch.cuda.synchronize()
+    got = sc.cpu().numpy()[:, :N]
+    ref = oracle.default_scores(oracle.reconstruct(G, cent), Q)                    # Eq. 3 in float64
+    check_scores(got, ref)
+    # ranking: the GPU's TopK of its own float32 scores is exact; against the float64 ranking ids agree wherever the
+    # float64 scores are further apart than the float32 tolerance (what is unique), and every returned item is valid
+    K = min(N, 10)
+    ids, out = pq.pq_topk_scores(sc, K, N=N)
+    torch.cuda.synchronize()
+    ids, out = ids.cpu().numpy(), out.cpu().numpy()
+    for q in range(B):
+        rid, rsc = oracle.topk(got[q], K)
+        assert np.array_equal(ids[q], rid) and np.array_equal(out[q].view(np.uint32), rsc.view(np.uint32))
+        order = np.lexsort((np.arange(N), -ref[q]))[:K + 1]
+        for r in range(K):
+            gap_ok = r + 1 >= len(order) or ref[q][order[r]] - ref[q][order[r + 1]] > 2e-5 * max(abs(ref[q][order[r]]), 1.0)
+            prev_ok = r == 0 or ref[q][order[r - 1]] - ref[q][order[r]] > 2e-5 * max(abs(ref[q][order[r]]), 1.0)
+            if gap_ok and prev_ok:
+                assert ids[q][r] == order[r]
+        check_scores(out[q], ref[q][ids[q]])
+
+
 # ---------------------------------------------------------------- the named configurations at full size
 
 def end_to_end(pq, oracle, cfg, B, G=None):
