@@ -238,9 +238,14 @@ def main():
         torch.empty_like(Gd).copy_(Gd)
         torch.cuda.synchronize()
 
+    t_warm = time.perf_counter()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    while time.perf_counter() - t_warm < 0.03:             # (untimed) a GPU that was idle needs ~20 ms of work before
+        for _ in range(50):                                 # its clocks settle, however few warm-up steps were asked for
+            step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
