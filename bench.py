@@ -22,23 +22,34 @@ LDS_PEAK_GBS = 128 * 256 * 2.4   # 128 B/clk/CU x 256 CUs x 2.4 GHz: what the LD
 
 
 def cpu_baseline(G, cent, Q, K, budget_s=12.0):
-    """The CPU oracle as it stands, timed on this host on whole-catalogue queries (bounded sample)."""
+    """The CPU oracle as it stands, timed on this host on whole-catalogue queries (bounded sample): on all host
+    threads (the reported baseline) and, for a few seconds, on one."""
     import numpy as np
     from oracle import pq_oracle
     threads = pq_oracle.num_threads()
     q1 = np.ascontiguousarray(Q[:1])
-    pq_oracle.pqtopk(G, cent, q1, K)                      # warm-up
-    t0 = time.perf_counter()
-    n = 0
-    while True:
-        pq_oracle.pqtopk(G, cent, q1, K)
-        n += 1
-        el = time.perf_counter() - t0
-        if el > budget_s or n >= 200:
-            break
     N = G.shape[0]
+
+    def run(budget):
+        pq_oracle.pqtopk(G, cent, q1, K)                  # warm-up
+        t0 = time.perf_counter()
+        n = 0
+        while True:
+            pq_oracle.pqtopk(G, cent, q1, K)
+            n += 1
+            el = time.perf_counter() - t0
+            if el > budget or n >= 200:
+                return n, el
+
+    n, el = run(budget_s)
+    pq_oracle.set_num_threads(1)
+    try:
+        n1, el1 = run(3.0)
+    finally:
+        pq_oracle.set_num_threads(threads)
     return {"value": N * n / el, "unit": "items/s", "queries_per_s": n / el, "cores": threads, "kind": "oracle",
-            "sample": f"{n} single-query passes of the oracle (Eq. 4, Eq. 5 over all {N} items, TopK) in {el:.2f} s"}
+            "sample": f"{n} single-query passes of the oracle (Eq. 4, Eq. 5 over all {N} items, TopK) in {el:.2f} s",
+            "one_thread_items_per_s": N * n1 / el1}
 
 
 def measured_traffic(workload: str):
@@ -265,6 +276,44 @@ def main():
     algo_bytes = float(N) * m                               # one pass over the code matrix per launch
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9
 
+    # what a kernel that only reads gets out of this machine on the same bytes: the yardstick beside the published peak
+    read_ms = sorted(pq.pq_read_bandwidth_profile(Gd, args.profile_iters) for _ in range(5))[2]
+    read_gbs = algo_bytes / (read_ms * 1e-3) / 1e9
+
+    # stage times (HIP events on the stream the kernels run on, back-to-back launches of one stage)
+    def stage_us(fn, iters=200):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3
+    n_stage = 200 if N * B < 2e8 else 20
+    t_sub, t_top = stage_us(sub, n_stage), stage_us(top, n_stage)
+
+    # one call at a time (the paper's per-user response time: Table 3 quotes a median, Figure 2 a mean): host-side
+    # time from enqueue to completion of one step, caches warm; then the same with the caches evicted before every call
+    lat = []
+    for _ in range(200 if N * B < 2e8 else 30):
+        t1 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        lat.append((time.perf_counter() - t1) * 1e6)
+    lat = np.asarray(lat)
+    evict = torch.empty(768 << 20, dtype=torch.uint8, device="cuda")       # larger than L2 + the 256 MB Infinity Cache
+    cold = []
+    for i in range(20):
+        evict.fill_(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        cold.append((time.perf_counter() - t1) * 1e6)
+    cold = np.asarray(cold)
+    del evict
+
     ms_per_step = el / args.steps * 1e3
     workload = f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch={B}, codes {cfg.codes}, seed {cfg.seed}"
     out = {
@@ -280,7 +329,12 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(workload),
                      "kernel": "catalogue scan (Eq. 5 + per-workgroup top-K)", "kernel_ms": scan_ms,
-                     "algorithmic_bytes_per_launch": algo_bytes},
+                     "algorithmic_bytes_per_launch": algo_bytes,
+                     "read_kernel_GBps": read_gbs, "frac_of_read_kernel": achieved / read_gbs},
+        "stage_us": {"pq_subitem_scores": t_sub, "pq_score_topk": t_top, "scan_kernel": scan_ms * 1e3},
+        "latency_us": {"what": "one step at a time, host enqueue to completion", "median": float(np.median(lat)),
+                       "mean": float(lat.mean()), "p99": float(np.percentile(lat, 99)),
+                       "cold_caches_median": float(np.median(cold))},
     }
     if B > 1:
         # a batch re-uses every code byte B times: the table lookups (4 bytes gathered from LDS per split, item and

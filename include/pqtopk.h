@@ -168,6 +168,15 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
                           int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
                           void* stream, int iters, float* scan_ms);
 
+/*
+ * Measurement aid: a plain streaming-read kernel (16-byte loads and nothing else) over `bytes` bytes at `data`
+ * (device pointer, 16-byte aligned), launched once untimed and then `iters` times back to back between two HIP events;
+ * *read_ms (host pointer) receives elapsed / iters in milliseconds.  The yardstick for the scan's HBM rate: what this
+ * machine delivers to a kernel that does nothing but read.  Synchronises; creates and destroys two HIP events.
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE (bytes < 16, iters < 1), PQ_ERR_ALIGN, PQ_ERR_HIP.
+ */
+int pq_read_bandwidth_profile(const void* data, size_t bytes, void* stream, int iters, float* read_ms);
+
 /* Text for a PQ_* code; for PQ_ERR_HIP the text of the most recent HIP error seen by this thread. */
 const char* pq_strerror(int code);
 

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.pq_reconstruct_items.restype = I
         L.pq_default_scores.argtypes = [P, P, LL, I, I, P, LL, P]
         L.pq_default_scores.restype = I
+        L.pq_read_bandwidth_profile.argtypes = [P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
+        L.pq_read_bandwidth_profile.restype = I
         L.pq_strerror.argtypes = [I]
         L.pq_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -251,6 +253,18 @@ def pq_score_topk_profile(codes: torch.Tensor, S: torch.Tensor, K: int, iters: i
                                      iters, ctypes.byref(ms))
     if rc != PQ_OK:
         raise PQError(rc, "pq_score_topk_profile")
+    return float(ms.value)
+
+
+def pq_read_bandwidth_profile(buf: torch.Tensor, iters: int) -> float:
+    """Mean duration (ms) of a plain streaming-read kernel over the whole of `buf`."""
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise ValueError("buf must be a contiguous device tensor")
+    ms = ctypes.c_float(0.0)
+    rc = lib().pq_read_bandwidth_profile(buf.data_ptr(), buf.numel() * buf.element_size(), _stream(), iters,
+                                         ctypes.byref(ms))
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_read_bandwidth_profile")
     return float(ms.value)
 
 

@@ -1837,6 +1837,23 @@ __global__ __launch_bounds__(kDefaultThreads) void default_scores_kernel(const f
     }
 }
 
+// Measurement aid: a plain streaming read (16-byte loads, nothing else), the yardstick the scan's HBM rate is held to.
+constexpr int kReadThreads = 256, kReadUnroll = 8;     // (eight waves per CU with eight loads in flight each read fastest here)
+__global__ __launch_bounds__(kReadThreads) void stream_read_kernel(const uint4* src, long long nvec) {
+    uint32_t acc = 0;
+    const long long stride = (long long)gridDim.x * kReadThreads;
+    long long i = (long long)blockIdx.x * kReadThreads + threadIdx.x;
+    for (; i + (kReadUnroll - 1) * stride < nvec; i += kReadUnroll * stride) {
+        uint4 v[kReadUnroll];
+#pragma unroll
+        for (int u = 0; u < kReadUnroll; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < kReadUnroll; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < nvec; i += stride) { const uint4 v = src[i]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+    asm volatile("" ::"v"(acc));                              // (the loaded data is used: the loads stay)
+}
+
 struct ScanPlan {
     int copies;      // single-query kernel: copies of the score tables in LDS (1 or kTableCopies)
     bool tiled;      // batched kernel: kQ queries per workgroup
@@ -2146,6 +2163,37 @@ int pq_score_topk_subset(const uint8_t* codes, const float* S, const int* subset
     int rc = enqueue_scan(p, codes, S, n_subset, B, m, b, K, workspace, st, subset, N);
     if (rc != PQ_OK) return rc;
     return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+}
+
+int pq_read_bandwidth_profile(const void* data, size_t bytes, void* stream, int iters, float* read_ms) {
+    if (!data || !read_ms) return PQ_ERR_NULL;
+    if (bytes < 16 || iters < 1) return PQ_ERR_SHAPE;
+    if ((uintptr_t)data & 15) return PQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const long long nvec = (long long)(bytes / 16);
+    long long blocks = (nvec + kReadThreads - 1) / kReadThreads;
+    if (blocks > 2LL * kAssumedCUs) blocks = 2LL * kAssumedCUs;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    hipError_t e = hipEventCreate(&ev0);
+    if (e != hipSuccess) return record_hip(e);
+    e = hipEventCreate(&ev1);
+    if (e != hipSuccess) { (void)hipEventDestroy(ev0); return record_hip(e); }
+    auto launch = [&]() {
+        hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(kReadThreads), 0, st,
+                           static_cast<const uint4*>(data), nvec);
+        return record_hip(hipGetLastError());
+    };
+    int rc = launch();                                       // untimed warm-up launch
+    if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev0, st));
+    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = launch();
+    if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev1, st));
+    if (rc == PQ_OK) rc = record_hip(hipStreamSynchronize(st));
+    float ms = 0.0f;
+    if (rc == PQ_OK) rc = record_hip(hipEventElapsedTime(&ms, ev0, ev1));
+    (void)hipEventDestroy(ev0);
+    (void)hipEventDestroy(ev1);
+    if (rc == PQ_OK) *read_ms = ms / (float)iters;
+    return rc;
 }
 
 // ---- the comparison scorers (Section 2's default scoring, Algorithm 2) and TopK over score rows

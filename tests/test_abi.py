@@ -30,6 +30,7 @@ def lib(pqlib_path):
     L.pq_recjpq_scores.argtypes = [P, P, LL, I, I, I, P, LL, P]
     L.pq_reconstruct_items.argtypes = [P, P, LL, I, I, I, P, P]
     L.pq_default_scores.argtypes = [P, P, LL, I, I, P, LL, P]
+    L.pq_read_bandwidth_profile.argtypes = [P, SZ, P, I, P]
     L.pq_strerror.argtypes = [I]
     L.pq_strerror.restype = ctypes.c_char_p
     return L
@@ -185,6 +186,12 @@ def test_comparison_scorers_argument_errors(lib):
     assert h(None, p, 1000, 64, 4, 256, p, None) == NULL and h(p, p, 1000, 64, 4, 256, None, None) == NULL
     assert h(p, p, 1000, 66, 4, 256, p, None) == SHAPE and h(p, p, 0, 64, 4, 256, p, None) == SHAPE
     assert h(p, p, 1000, 258, 129, 256, p, None) == UNSUPPORTED and h(p, p, 1000, 64, 4, 256, p + 1, None) == ALIGN
+
+    r = lib.pq_read_bandwidth_profile
+    out = ctypes.c_float(0)
+    assert r(None, 1 << 20, None, 3, ctypes.addressof(out)) == NULL and r(p, 1 << 20, None, 3, None) == NULL
+    assert r(p, 8, None, 3, ctypes.addressof(out)) == SHAPE and r(p, 1 << 20, None, 0, ctypes.addressof(out)) == SHAPE
+    assert r(p + 8, 1 << 20, None, 3, ctypes.addressof(out)) == ALIGN
 
     e = lib.pq_default_scores
     assert e(None, p, 1000, 1, 64, p, 1000, None) == NULL and e(p, None, 1000, 1, 64, p, 1000, None) == NULL
