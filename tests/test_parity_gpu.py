@@ -147,6 +147,16 @@ def test_score_topk_batched_kernel_shapes(pq, oracle, N, m, B, K, b):
     assert_same_topk(pq, oracle, G, S, K, "batched")
 
 
+@pytest.mark.parametrize("N,m,b,B,K", [(300, 8, 256, 2000, 10), (40, 16, 256, 5000, 40), (5000, 8, 1, 7, 50),
+                                       (1_200_000, 128, 256, 1, 10), (900, 4, 256, 65535, 1)])
+def test_score_topk_odd_corners(pq, oracle, N, m, b, B, K):
+    # thousands of queries over a tiny catalogue (one workgroup per query), K = N, a single sub-id per split, the largest
+    # m on a scan long enough for 1024-thread workgroups, the largest batch
+    G = W.codes_uniform(N, m, b, seed=N)
+    S = W.normal_f32(W.stream_key(N + B, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+    assert_same_topk(pq, oracle, G, S, K, "corner")
+
+
 def test_all_items_equal(pq, oracle):
     for N in (500, 100_000):
         G = np.full((N, 8), 17, dtype=np.uint8)
