@@ -157,6 +157,27 @@ def test_score_topk_odd_corners(pq, oracle, N, m, b, B, K):
     assert_same_topk(pq, oracle, G, S, K, "corner")
 
 
+def test_score_topk_seeded_random_shapes(pq, oracle):
+    # a seeded walk through shape space: every m from 1 to 20 plus the wide ones, short alphabets, odd batch sizes,
+    # K anywhere up to min(N, 512), with and without a candidate list
+    rng = np.random.default_rng(20240819)
+    for case in range(160):
+        m = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16, 20, 32, 64]))
+        b = int(rng.choice([1, 2, 7, 16, 100, 255, 256]))
+        N = int(rng.choice([1, 2, 17, 64, 255, 1000, 4097, 20_000]))
+        B = int(rng.integers(1, 10))
+        K = int(rng.integers(1, min(N, 512) + 1))
+        G = W.codes_uniform(N, m, b, seed=case)
+        S = W.normal_f32(W.stream_key(case, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+        if rng.random() < 0.3:                              # coarse tables: many exact ties
+            S = np.round(S * 2).astype(np.float32) / 2
+        assert_same_topk(pq, oracle, G, S, K, f"random#{case}")
+        if case % 4 == 0:
+            n = int(rng.integers(K, N + 1))
+            V = W.candidate_list(N, n, seed=case)
+            assert_same_subset_topk(pq, oracle, G, S, V, K, f"random-subset#{case}")
+
+
 def test_all_items_equal(pq, oracle):
     for N in (500, 100_000):
         G = np.full((N, 8), 17, dtype=np.uint8)
