@@ -1,4 +1,4 @@
-"""Compile the HIP library (csrc/pqtopk.hip -> libpqtopk.so, in-tree) for gfx950 with hipcc."""
+"""Compile the HIP library (csrc/pqtopk.hip and the .hpp parts it includes -> libpqtopk.so, in-tree) for gfx950."""
 from __future__ import annotations
 
 import os
@@ -6,8 +6,10 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SOURCES = [os.path.join(_HERE, "csrc", "pqtopk.hip")]
-HEADERS = [os.path.join(ROOT, "include", "pqtopk.h")]
+CSRC = os.path.join(_HERE, "csrc")
+SOURCES = [os.path.join(CSRC, "pqtopk.hip")]                    # one translation unit; it includes the .hpp parts
+HEADERS = [os.path.join(ROOT, "include", "pqtopk.h")] + sorted(
+    os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp"))
 LIB = os.path.join(_HERE, "libpqtopk.so")
 
 HIPCC_FLAGS = [

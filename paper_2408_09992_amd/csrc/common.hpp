@@ -1,0 +1,128 @@
+// Constants, cross-lane helpers (DPP), wave-level reductions and the bitonic sort shared by every kernel.
+// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
+#pragma once
+
+constexpr int kWave = 64;
+constexpr int kThreads = 512;                     // scan workgroup: 8 waves
+constexpr int kWaves = kThreads / kWave;
+constexpr int kBigThreads = 1024;                 // workgroup of the long single-query scan with replicated tables
+constexpr int kMaxWaves = kBigThreads / kWave;
+constexpr int kLutStride = 256;                   // table entries per split in LDS (a uint8 sub-id never runs past it)
+constexpr int kBins = 1024;                       // score buckets of the pruning histogram
+// 16-byte code vectors a thread holds per round: 4 for m >= 8, fewer for small m so a thread never holds > 16 items
+// Units of work a thread holds per round in the kernels with a compile-time m.  m <= 16: a unit is one 16-byte code
+// vector (16/m items); m = 32, 64: a unit is one item (m/16 vectors).  Four vectors per thread from m = 8 on.
+__host__ __device__ constexpr int vec_per_thread(int m) { return m == 64 ? 1 : (m == 32 ? 2 : (m >= 8 ? 4 : (m == 4 ? 2 : 1))); }
+constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
+constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
+constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
+constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
+constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
+constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace
+constexpr int kBlocksPerCU = 2;                   // single-query scan workgroups per CU over the whole grid
+constexpr int kTableCopies = 16;                  // copies of the score tables in the long single-query scan
+constexpr int kTableCopiesMinRounds = 8;          // rounds per workgroup from which the copies pay for themselves
+
+__device__ __forceinline__ uint32_t orderable_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float score_of_key(uint64_t key) {
+    uint32_t u = (uint32_t)(key >> 32);
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ int id_of_key(uint64_t key) { return (int)(~(uint32_t)key); }
+__device__ __forceinline__ uint64_t make_key(float score, uint32_t id) {
+    return ((uint64_t)orderable_bits(score) << 32) | (uint32_t)(~id);
+}
+
+// Ordering point between LDS accesses of the lanes of ONE wave (LDS serves a wave's requests in issue order).
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Cross-lane steps through the DPP data path (no LDS traffic).  Lanes whose source lies outside their row of 16
+// keep `identity`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f32(float identity, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t identity, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+constexpr int kDppRowShr = 0x110;        // + n
+constexpr int kDppBcast15 = 0x142;
+constexpr int kDppBcast31 = 0x143;
+
+// min and max over the wave, returned in every lane
+__device__ __forceinline__ void wave_minmax(float& mn, float& mx) {
+    mn = fminf(mn, dpp_f32<kDppQuadSwap1>(mn, mn));       mx = fmaxf(mx, dpp_f32<kDppQuadSwap1>(mx, mx));
+    mn = fminf(mn, dpp_f32<kDppQuadSwap2>(mn, mn));       mx = fmaxf(mx, dpp_f32<kDppQuadSwap2>(mx, mx));
+    mn = fminf(mn, dpp_f32<kDppRowHalfMirror>(mn, mn));   mx = fmaxf(mx, dpp_f32<kDppRowHalfMirror>(mx, mx));
+    mn = fminf(mn, dpp_f32<kDppRowMirror>(mn, mn));       mx = fmaxf(mx, dpp_f32<kDppRowMirror>(mx, mx));
+    // every row of 16 lanes now holds its own extremes; combine the four rows through scalar reads
+    float m0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 0));
+    float m1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 16));
+    float m2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 32));
+    float m3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 48));
+    float x0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 0));
+    float x1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 16));
+    float x2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 32));
+    float x3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 48));
+    mn = fminf(fminf(m0, m1), fminf(m2, m3));
+    mx = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+}
+
+// A floor for a wave's top K (K in 1..64): a value that at least K of the lanes' values v reach, found by bisection
+// between the wave's extremes with one ballot per step (so close below the K-th largest, not exactly it).  Lanes
+// with nothing to offer pass -inf; if fewer than K lanes have a value the floor is -inf.  Same result in every lane.
+__device__ __forceinline__ float wave_floor_for_k(float v, int K) {
+    const float ninf = -__builtin_inff();
+    if (__popcll(__ballot(v > ninf)) < K) return ninf;
+    float lo = v > ninf ? v : __builtin_inff(), hi = v;
+    wave_minmax(lo, hi);                                      // at least K lanes reach lo
+#pragma unroll
+    for (int step = 0; step < 12; ++step) {
+        const float mid = lo + (hi - lo) * 0.5f;
+        if (__popcll(__ballot(v >= mid)) >= K) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// inclusive prefix sum over the lanes of the wave (lane i gets v[0] + .. + v[i])
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v) {
+    v += dpp_u32<kDppRowShr + 1>(0u, v);
+    v += dpp_u32<kDppRowShr + 2>(0u, v);
+    v += dpp_u32<kDppRowShr + 4>(0u, v);
+    v += dpp_u32<kDppRowShr + 8>(0u, v);
+    v += dpp_u32<kDppBcast15, 0xA>(0u, v);               // lane 15 -> lanes 16..31, lane 47 -> lanes 48..63
+    v += dpp_u32<kDppBcast31, 0xC>(0u, v);               // lane 31 -> lanes 32..63
+    return v;
+}
+
+// Bitonic sort of n (a power of two) keys in LDS, descending.  BLOCK: all threads of the workgroup take part and
+// stages are separated by workgroup barriers; otherwise one wave sorts its own array.
+template <bool BLOCK>
+__device__ void bitonic_sort_desc(uint64_t* a, int n, int tid, int nthr) {
+    for (int k = 2; k <= n; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < (n >> 1); t += nthr) {
+                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                int p = i | j;
+                bool desc = (i & k) == 0;
+                uint64_t x = a[i], y = a[p];
+                if ((x < y) == desc) { a[i] = y; a[p] = x; }
+            }
+            if (BLOCK) __syncthreads(); else wave_sync();
+        }
+    }
+}

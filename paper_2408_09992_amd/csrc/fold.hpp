@@ -1,0 +1,107 @@
+// The second launch of every TopK call: the workgroups' lists -> the final sorted K per query (fold_topk_kernel).
+// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
+#pragma once
+
+// Grid-level fold: one workgroup per query turns the nblk sorted lists of K keys into the final K, sorted.
+// Dynamic LDS: hist | ctl | stage (stage_keys, a power of two >= 2K) | cand | sorted
+struct FoldArgs {
+    const uint64_t* ws_keys;   // [B][nblk][K]
+    int nblk, K;
+    int stage_keys, candmax;
+    int* out_ids;
+    float* out_scores;
+};
+
+__host__ __device__ inline size_t fold_lds_bytes(int stage_keys, int candmax, int K) {
+    return kBins * sizeof(uint32_t) + align16(sizeof(Ctl)) + (size_t)stage_keys * sizeof(uint64_t) +
+           (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
+}
+
+__global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
+    Ctl* ctl = reinterpret_cast<Ctl*>(smem + kBins * sizeof(uint32_t));
+    uint64_t* stage = reinterpret_cast<uint64_t*>(smem + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)));
+    uint64_t* cand = stage + a.stage_keys;
+    uint64_t* sorted = cand + a.candmax;
+    const int tid = threadIdx.x, q = blockIdx.x, K = a.K;
+    const uint64_t* all = a.ws_keys + (size_t)q * a.nblk * K;
+    const long long nkeys = (long long)a.nblk * K;
+    auto key_at = [&](long long i) { return all[i]; };
+    auto emit = [&](const uint64_t* sorted_keys) {
+        for (int t = tid; t < K; t += kThreads) {
+            const uint64_t key = sorted_keys[t];
+            a.out_ids[(size_t)q * K + t] = id_of_key(key);
+            a.out_scores[(size_t)q * K + t] = score_of_key(key);
+        }
+    };
+
+    // score range of all the keys (empty slots of short lists are 0); a modest number of keys stays in registers
+    const int lane = tid & (kWave - 1);
+    const bool in_regs = nkeys <= (long long)kThreads * kFoldRegs;
+    uint64_t keys[kFoldRegs];
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    if (in_regs) {
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            const long long i = (long long)r * kThreads + tid;
+            keys[r] = (i < nkeys) ? key_at(i) : 0ull;
+            if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
+        }
+    } else {
+        for (long long i = tid; i < nkeys; i += kThreads) {
+            uint64_t key = key_at(i);
+            if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
+        }
+    }
+    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+    float lo, scale;
+    set_range(mn, mx, ctl, tid, lo, scale);
+
+    if (in_regs) {
+        // one pass: histogram, cut, collect the few keys at or above the cut, rank them
+        int bk[kFoldRegs];
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            bk[r] = -1;
+            if (keys[r]) { bk[r] = bucket_of(score_of_key(keys[r]), lo, scale); atomicAdd(&hist[bk[r]], 1u); }
+        }
+        __syncthreads();
+        if (tid < kWave) find_cut(hist, K, ctl, lane);
+        __syncthreads();
+        const int bstar = ctl->bstar;
+#pragma unroll
+        for (int r = 0; r < kFoldRegs; ++r) {
+            if (bk[r] >= bstar) {
+                int pos = atomicAdd(&ctl->ncand, 1);
+                if (pos < a.candmax) cand[pos] = keys[r];
+            }
+        }
+        __syncthreads();
+        const int C = ctl->ncand;
+        if (C <= a.candmax) {
+            rank_select(cand, C, K, sorted, tid);
+            emit(sorted);
+            return;
+        }
+        // too many keys share the cut bucket (heavy ties): take the staged, sorting path below
+    }
+
+    int keep = 0;                                            // best-so-far keys carried at the front of stage
+    long long done = 0;
+    while (done < nkeys) {
+        long long take = nkeys - done;
+        if (take > a.stage_keys - keep) take = a.stage_keys - keep;
+        for (int t = tid; t < a.stage_keys - keep; t += kThreads) stage[keep + t] = (t < take) ? key_at(done + t) : 0ull;
+        __syncthreads();
+        block_select(stage, a.stage_keys, K, sorted, cand, a.candmax, hist, ctl, tid);
+        done += take;
+        keep = K;
+        if (done < nkeys) {
+            for (int t = tid; t < K; t += kThreads) stage[t] = sorted[t];
+            __syncthreads();
+        }
+    }
+    emit(sorted);
+}
