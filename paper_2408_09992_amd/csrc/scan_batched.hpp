@@ -374,7 +374,9 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         }
     };
 
-    // Every eighth round of a wave (the waves take turns): floors of the queries whose histograms have grown.
+    // Floors of the queries whose histograms have grown.  The waves take turns: at first each refreshes every eighth of
+    // its rounds, then at intervals that grow by a quarter each time (candidates thin out as 1 / rounds, so the floors
+    // move ever more slowly, and a refresh costs a wave some eighty instructions per query).
     auto refresh_floors = [&]() {
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
@@ -386,6 +388,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         }
     };
     int turn = wave;                                          // rounds until this wave's next refresh
+    int gap = kWaves;                                         // rounds between two refreshes; grows by a quarter each time
 
     {
         // ---- 2. first round: per query a histogram over its own score range gives that query's cut
@@ -477,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
                 if (done < units) offer_round(sc, round_of(done), vt_of(done), nullptr, nullptr);
             }
             turn -= 2;
-            if (turn < 0) { turn += kWaves; refresh_floors(); }
+            if (turn < 0) { gap += gap >> 2; turn += gap; refresh_floors(); }
         }
     }
     // the fewer than 16 / M items after the last whole code vector: one per lane of one wave, per query
