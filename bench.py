@@ -270,13 +270,18 @@ def main():
     parity = bool(np.array_equal(got_ids[:len(rid)], rid) and
                   np.all(np.abs(got_sc[:len(rid)] - rsc) <= 1e-5 * np.maximum(np.abs(rsc), 1.0)))
 
-    # the scan kernel's own duration: median of five back-to-back sequences, taken while the GPU is still warm
+    # the scan kernel's own duration: median of five back-to-back sequences.  The oracle run above left the GPU idle
+    # for tens of milliseconds, so its clocks are brought back up first (untimed).
+    t_warm = time.perf_counter()
+    while time.perf_counter() - t_warm < 0.04:
+        pq.pq_score_topk_profile(Gd, Sd, K, args.profile_iters, workspace=ws)
     scan_ms = sorted(pq.pq_score_topk_profile(Gd, Sd, K, args.profile_iters, workspace=ws) for _ in range(5))[2]
     torch.cuda.synchronize()
     algo_bytes = float(N) * m                               # one pass over the code matrix per launch
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9
 
     # what a kernel that only reads gets out of this machine on the same bytes: the yardstick beside the published peak
+    pq.pq_read_bandwidth_profile(Gd, args.profile_iters)
     read_ms = sorted(pq.pq_read_bandwidth_profile(Gd, args.profile_iters) for _ in range(5))[2]
     read_gbs = algo_bytes / (read_ms * 1e-3) / 1e9
 
