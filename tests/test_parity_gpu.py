@@ -178,6 +178,23 @@ def test_score_topk_seeded_random_shapes(pq, oracle):
             assert_same_subset_topk(pq, oracle, G, S, V, K, f"random-subset#{case}")
 
 
+def test_score_topk_largest_catalogue(pq, oracle):
+    # N = 2^31 - 1, the largest the interface takes (m = 1: 2 GB of codes): every index computation at its limit,
+    # with the winner planted as the very last item
+    N, m, K = 2 ** 31 - 1, 1, 10
+    G = np.empty((N, m), dtype=np.uint8)
+    step = 1 << 26
+    for a0 in range(0, N, step):                              # a cheap seeded pattern, drawn in chunks
+        idx = np.arange(a0, min(a0 + step, N), dtype=np.uint64)
+        G[a0:a0 + len(idx), 0] = ((idx * np.uint64(0x9E3779B97F4A7C15)) >> np.uint64(56)).astype(np.uint8)
+    S = W.normal_f32(W.stream_key(31, W.STREAM_QUERIES), m * 256).reshape(1, m, 256)
+    best = int(S[0, 0].argmax())
+    G[G[:, 0] == best, 0] = (best + 1) % 256                  # nobody holds the best sub-id ...
+    G[N - 1, 0] = best                                        # ... except the last item
+    ids, sc = assert_same_topk(pq, oracle, G, S, K, "largest")
+    assert ids[0][0] == N - 1
+
+
 def test_all_items_equal(pq, oracle):
     for N in (500, 100_000):
         G = np.full((N, 8), 17, dtype=np.uint8)
