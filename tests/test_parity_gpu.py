@@ -263,6 +263,43 @@ def test_deterministic_and_workspace_reuse(pq, oracle):
     assert np.array_equal(a[0].cpu().numpy(), rid)
 
 
+def test_side_streams_and_concurrent_calls(pq, oracle):
+    # two calls in flight on two streams, each with its own workspace and outputs: the library keeps no state between
+    # calls, so both must equal what the oracle says
+    cfg = W.CONFIGS["large"]
+    G, cent, Q = W.make(cfg, B=2, N=400_000)
+    Gd = dev(G)
+    S = pq.pq_subitem_scores(dev(Q), dev(cent))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep in range(3):
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                outs.append((i, pq.pq_score_topk(Gd, S[i:i + 1].contiguous(), cfg.K)))
+    torch.cuda.synchronize()
+    rid, rsc = oracle.score_topk(G, S.cpu().numpy(), cfg.K)
+    for i, (ids, sc) in outs:
+        assert np.array_equal(ids.cpu().numpy()[0], rid[i])
+        assert np.array_equal(sc.cpu().numpy()[0].view(np.uint32), rsc[i].view(np.uint32))
+
+
+@pytest.mark.parametrize("N,m,B", [(100_000, 8, 1), (100_000, 3, 2), (50_000, 64, 1), (700_001, 8, 64)])
+def test_tables_that_are_only_four_byte_aligned(pq, oracle, N, m, B):
+    # S may sit at any 4-byte boundary (the table fill then copies element by element, or loads unaligned)
+    G = W.codes_uniform(N, m, 256, seed=m)
+    S = W.normal_f32(W.stream_key(N + m, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    flat = torch.empty(S.size + 1, dtype=torch.float32, device="cuda")
+    Sd = flat[1:].view(B, m, 256)
+    Sd.copy_(torch.from_numpy(S))
+    assert Sd.data_ptr() % 16 == 4 and Sd.is_contiguous()
+    ids, sc = pq.pq_score_topk(dev(G), Sd, 10)
+    torch.cuda.synchronize()
+    rid, rsc = oracle.score_topk(G, S, 10)
+    assert np.array_equal(ids.cpu().numpy(), rid)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), rsc.view(np.uint32))
+
+
 def test_errors_reach_python(pq):
     G = dev(W.codes_uniform(100, 8))
     S = dev(np.zeros((1, 8, 256), dtype=np.float32))
