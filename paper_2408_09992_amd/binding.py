@@ -318,3 +318,39 @@ class PreparedScoreTopK:
         if rc != PQ_OK:
             raise PQError(rc, "pq_score_topk")
         return self.ids, self.scores
+
+
+class PreparedScoreTopKSubset:
+    """pq_score_topk_subset with its arguments marshalled once (workspace and outputs allocated here if not given)."""
+
+    def __init__(self, codes: torch.Tensor, S: torch.Tensor, subset: torch.Tensor, K: int,
+                 workspace: Optional[torch.Tensor] = None, stream: Optional[int] = None):
+        _dev(codes, torch.uint8, "codes")
+        _dev(S, torch.float32, "S")
+        _dev(subset, torch.int32, "subset")
+        N, m = codes.shape
+        B, m2, b = S.shape
+        if m2 != m or subset.dim() != 1:
+            raise PQError(PQ_ERR_SHAPE, "pq_score_topk_subset")
+        n = subset.numel()
+        if workspace is None:
+            workspace = torch.empty(max(pq_score_topk_subset_workspace_bytes(n, B, m, b, K), 16), dtype=torch.uint8,
+                                    device=codes.device)
+        self.ids = torch.empty((B, K), dtype=torch.int32, device=codes.device)
+        self.scores = torch.empty((B, K), dtype=torch.float32, device=codes.device)
+        self.workspace = workspace
+        self._keep = (codes, S, subset)
+        st = _stream() if stream is None else stream
+        c = ctypes
+        self._fn = lib().pq_score_topk_subset
+        self._args = (c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_void_p(subset.data_ptr()),
+                      c.c_longlong(n), c.c_longlong(N), c.c_int(B), c.c_int(m), c.c_int(b), c.c_int(K),
+                      c.c_void_p(self.ids.data_ptr()), c.c_void_p(self.scores.data_ptr()),
+                      c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), c.c_void_p(st))
+
+    def __call__(self) -> Tuple[torch.Tensor, torch.Tensor]:
+        rc = self._fn(*self._args)
+        if rc != PQ_OK:
+            raise PQError(rc, "pq_score_topk_subset")
+        return self.ids, self.scores
+
