@@ -90,3 +90,20 @@ def test_named_configs():
     # duplicated rows exist
     _, inv, cnt = np.unique(G2, axis=0, return_inverse=True, return_counts=True)
     assert (cnt > 1).sum() > 100
+
+
+def test_candidate_lists_are_seeded_distinct_and_in_range():
+    a = W.candidate_list(10_000, 777, seed=3)
+    b = W.candidate_list(10_000, 777, seed=3)
+    c = W.candidate_list(10_000, 777, seed=4)
+    assert a.dtype == np.int32 and a.shape == (777,)
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    assert len(set(a.tolist())) == 777 and a.min() >= 0 and a.max() < 10_000
+    assert not np.array_equal(a, np.sort(a))                                  # a random order, not a sorted one
+    s = W.candidate_list(10_000, 777, seed=3, ascending=True)
+    assert np.array_equal(s, np.sort(a))
+    full = W.candidate_list(500, 500, seed=1)
+    assert np.array_equal(np.sort(full), np.arange(500))                      # the whole catalogue: a permutation
+    with pytest.raises(ValueError):
+        W.candidate_list(10, 11)
+
