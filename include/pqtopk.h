@@ -71,8 +71,8 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K);
  *   out_ids     out  int32 [B][K]     rank r of query q at [q][r]; score descending, id ascending
  *   out_scores  out  float [B][K]     the scores of those items
  *   workspace        scratch of at least pq_score_topk_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned;
- *                    contents on entry are irrelevant (it receives every workgroup's K best keys, which a second
- *                    small launch folds into the result); calls sharing a workspace must not overlap in time
+ *                    contents on entry are irrelevant (it receives every workgroup's K best keys, which one or
+ *                    more small launches fold into the result); calls sharing a workspace must not overlap in time
  * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (K > PQ_MAX_K, m > PQ_MAX_M, B > PQ_MAX_B, or m and K together
  *         too large for the 160 KB of LDS: m KB of score tables plus about 80*nextpow2(K+64) bytes of candidate
  *         lists; every K <= 512 fits with m <= 64, and m = 128 fits with K <= 64),

@@ -6,10 +6,12 @@
 // Grid-level fold: one workgroup per query turns the nblk sorted lists of K keys into the final K, sorted.
 // Dynamic LDS: hist | ctl | stage (stage_keys, a power of two >= 2K) | cand | sorted
 struct FoldArgs {
-    const uint64_t* ws_keys;   // [B][nblk][K]
-    int nblk, K;
+    const uint64_t* ws_keys;   // [B][nlists][K]: per query, nlists sorted lists of K keys
+    int nlists, K;
+    int lists_per_group;       // lists one workgroup folds; grid = (ceil(nlists / lists_per_group), B)
     int stage_keys, candmax;
-    int* out_ids;
+    uint64_t* out_keys;        // intermediate level: [B][groups][K] keys; nullptr at the last level, which writes
+    int* out_ids;              // ... the result
     float* out_scores;
 };
 
@@ -25,15 +27,21 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     uint64_t* stage = reinterpret_cast<uint64_t*>(smem + kBins * sizeof(uint32_t) + align16(sizeof(Ctl)));
     uint64_t* cand = stage + a.stage_keys;
     uint64_t* sorted = cand + a.candmax;
-    const int tid = threadIdx.x, q = blockIdx.x, K = a.K;
-    const uint64_t* all = a.ws_keys + (size_t)q * a.nblk * K;
-    const long long nkeys = (long long)a.nblk * K;
+    const int tid = threadIdx.x, q = blockIdx.y, group = blockIdx.x, K = a.K;
+    const int first_list = group * a.lists_per_group;
+    const int my_lists = a.nlists - first_list < a.lists_per_group ? a.nlists - first_list : a.lists_per_group;
+    const uint64_t* all = a.ws_keys + ((size_t)q * a.nlists + first_list) * K;
+    const long long nkeys = (long long)my_lists * K;
     auto key_at = [&](long long i) { return all[i]; };
     auto emit = [&](const uint64_t* sorted_keys) {
         for (int t = tid; t < K; t += kThreads) {
             const uint64_t key = sorted_keys[t];
-            a.out_ids[(size_t)q * K + t] = id_of_key(key);
-            a.out_scores[(size_t)q * K + t] = score_of_key(key);
+            if (a.out_keys != nullptr) {
+                a.out_keys[((size_t)q * gridDim.x + group) * K + t] = key;
+            } else {
+                a.out_ids[(size_t)q * K + t] = id_of_key(key);
+                a.out_scores[(size_t)q * K + t] = score_of_key(key);
+            }
         }
     };
 
@@ -50,9 +58,16 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
             if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
     } else {
-        for (long long i = tid; i < nkeys; i += kThreads) {
-            uint64_t key = key_at(i);
-            if (key) { float s = score_of_key(key); mn = fminf(mn, s); mx = fmaxf(mx, s); }
+        for (long long i0 = tid; i0 < nkeys; i0 += 8LL * kThreads) {          // eight loads in flight per thread
+            uint64_t kk[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const long long i = i0 + (long long)j * kThreads;
+                kk[j] = i < nkeys ? key_at(i) : 0ull;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (kk[j]) { float s = score_of_key(kk[j]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
     }
     for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
@@ -86,6 +101,55 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
             return;
         }
         // too many keys share the cut bucket (heavy ties): take the staged, sorting path below
+    } else {
+        // many keys (many workgroups times a large K): the same three steps, with the keys re-read from the workspace
+        // (they sit in L2) instead of held in registers: histogram, cut, collect, rank
+        constexpr int kBatch = 8;                            // loads in flight per thread (the passes are latency-bound)
+        auto for_each_key = [&](auto&& f) {
+            for (long long i0 = tid; i0 < nkeys; i0 += (long long)kBatch * kThreads) {
+                uint64_t kk[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const long long i = i0 + (long long)j * kThreads;
+                    kk[j] = i < nkeys ? key_at(i) : 0ull;
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j)
+                    if (kk[j]) f(kk[j]);
+            }
+        };
+        for_each_key([&](uint64_t key) { atomicAdd(&hist[bucket_of(score_of_key(key), lo, scale)], 1u); });
+        __syncthreads();
+        if (tid < kWave) find_cut(hist, K, ctl, lane);
+        __syncthreads();
+        const int bstar = ctl->bstar;
+        for (long long i0 = tid; i0 - tid < nkeys; i0 += (long long)kBatch * kThreads) {   // (whole waves stay in the loop)
+            uint64_t kk[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const long long i = i0 + (long long)j * kThreads;
+                kk[j] = i < nkeys ? key_at(i) : 0ull;
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {               // kept keys are compacted per wave: one counter update each
+                const bool take = kk[j] != 0ull && bucket_of(score_of_key(kk[j]), lo, scale) >= bstar;
+                const uint64_t mask = __ballot(take);
+                if (mask == 0) continue;
+                int base = 0;
+                if (lane == 0) base = atomicAdd(&ctl->ncand, __popcll(mask));
+                base = __builtin_amdgcn_readfirstlane(base);
+                const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
+                if (take && pos < a.candmax) cand[pos] = kk[j];
+            }
+        }
+        __syncthreads();
+        const int C = ctl->ncand;
+        if (C <= a.candmax) {
+            rank_select(cand, C, K, sorted, tid);
+            emit(sorted);
+            return;
+        }
+        __syncthreads();                                     // (cand and hist are reused below)
     }
 
     int keep = 0;                                            // best-so-far keys carried at the front of stage

@@ -160,9 +160,16 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     return p;
 }
 
-size_t workspace_bytes(const ScanPlan& p, int B, int K) {
+size_t keys_bytes(const ScanPlan& p, int B, int K) {
     const size_t bytes = (size_t)B * p.nblk * K * sizeof(uint64_t);
     return (bytes + 255) & ~(size_t)255;
+}
+
+size_t fold_area_keys(int nblk, int B, int K);
+
+// workspace: [B][nblk][K] keys from the scan | a second, smaller key area for folds that take more than one level
+size_t workspace_bytes(const ScanPlan& p, int B, int K) {
+    return keys_bytes(p, B, K) + ((fold_area_keys(p.nblk, B, K) * sizeof(uint64_t) + 255) & ~(size_t)255);
 }
 
 int check_topk_args(const void* codes, const void* S, long long N, int B, int m, int b, int K, const void* out_ids,
@@ -248,15 +255,44 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
 }
 
 // Enqueue the fold of the workspace's lists into the outputs.
+// Lists one fold workgroup takes: as many as it can hold in registers (kThreads * kFoldRegs keys), at least two.
+int fold_lists_per_group(int K) {
+    const int fit = kThreads * kFoldRegs / K;
+    return fit < 2 ? 2 : fit;
+}
+
+// Keys of the second key area of the workspace: what the first fold level writes when the lists of a query do not fit
+// one workgroup's registers (later levels alternate between the two areas, each needing less than the one before).
+size_t fold_area_keys(int nblk, int B, int K) {
+    const int per = fold_lists_per_group(K);
+    if (nblk <= per) return 0;
+    return (size_t)B * ((nblk + per - 1) / per) * K;
+}
+
+// Enqueue the fold of the workspace's lists into the outputs: one launch when a query's lists fit one workgroup's
+// registers, else levels of launches that each fold groups of lists into one list per group.
 int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
-    FoldArgs f;
-    f.ws_keys = static_cast<const uint64_t*>(workspace);
-    f.nblk = p.nblk; f.K = K; f.stage_keys = p.stage_keys; f.candmax = p.candmax;
-    f.out_ids = out_ids; f.out_scores = out_scores;
     hipError_t e = allow_lds(fold_topk_kernel, p.fold_lds);
     if (e != hipSuccess) return record_hip(e);
-    hipLaunchKernelGGL(fold_topk_kernel, dim3(B), dim3(kThreads), p.fold_lds, st, f);
-    return record_hip(hipGetLastError());
+    uint64_t* area[2] = {static_cast<uint64_t*>(workspace),
+                         reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + keys_bytes(p, B, K))};
+    const int per = fold_lists_per_group(K);
+    int nlists = p.nblk, src = 0;
+    for (;;) {
+        const int groups = nlists <= per ? 1 : (nlists + per - 1) / per;
+        FoldArgs f;
+        f.ws_keys = area[src];
+        f.nlists = nlists; f.K = K; f.lists_per_group = groups == 1 ? nlists : per;
+        f.stage_keys = p.stage_keys; f.candmax = p.candmax;
+        f.out_keys = groups == 1 ? nullptr : area[1 - src];
+        f.out_ids = out_ids; f.out_scores = out_scores;
+        hipLaunchKernelGGL(fold_topk_kernel, dim3(groups, B), dim3(kThreads), p.fold_lds, st, f);
+        e = hipGetLastError();
+        if (e != hipSuccess) return record_hip(e);
+        if (groups == 1) return PQ_OK;
+        nlists = groups;
+        src = 1 - src;
+    }
 }
 
 template <int S_ELEMS>
