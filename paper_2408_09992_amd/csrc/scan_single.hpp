@@ -95,8 +95,27 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
             }
         }
     } else {
-        acc = lut[row[0]];
-        for (int k = 1; k < m; ++k) acc = acc + lut[k * kLutStride + row[k]];
+        // rows that start at any byte: the aligned words covering the row are read (every one of them holds at least
+        // one byte of the row, so none lies outside the matrix) and realigned two at a time
+        const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(addr & ~(uintptr_t)3);
+        const uint32_t off = (uint32_t)(addr & 3);
+        const int last_word = (int)((off + (uint32_t)m - 1) >> 2);
+        uint32_t cur = p[0];
+        const int full = m >> 2;
+        for (int v = 0; v <= full; ++v) {                     // the last trip takes the m % 4 bytes left over
+            const uint32_t nxt = (v + 1 <= last_word) ? p[v + 1] : 0u;
+            const uint32_t w = __builtin_amdgcn_alignbyte(nxt, cur, off);       // bytes off .. off + 3 of nxt:cur
+            const int nbytes = v < full ? 4 : (m & 3);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (k < nbytes) {
+                    const float t = lut[(v * 4 + k) * kLutStride + ((w >> (k * 8)) & 0xFFu)];
+                    acc = (v == 0 && k == 0) ? t : acc + t;
+                }
+            }
+            cur = nxt;
+        }
     }
     return acc;
 }
