@@ -297,9 +297,11 @@ int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids,
 
 template <int S_ELEMS>
 void launch_subitem(const float* queries, const float* centroids, float* S, int B, int d, int m, int b, hipStream_t st) {
-    if constexpr (S_ELEMS > 0 && S_ELEMS % 4 == 0) {
-        // batches: the interleaved kernel (it needs 16-byte aligned rows of queries and centroids)
-        if (B >= kSubInterleave && (((uintptr_t)queries | (uintptr_t)centroids) & 15) == 0 && d % 4 == 0) {
+    if constexpr (S_ELEMS % 4 == 0) {
+        // batches, and any sub-dimension that is a multiple of 4 without an unrolled instance (96, 128, ...): the
+        // interleaved kernel (it needs 16-byte aligned rows of queries and centroids)
+        const bool rows_aligned = (((uintptr_t)queries | (uintptr_t)centroids) & 15) == 0 && d % 4 == 0 && (d / m) % 4 == 0;
+        if ((B >= kSubInterleave || S_ELEMS == 0) && rows_aligned) {
             dim3 grid(m * ((b + kSubThreads - 1) / kSubThreads), (B + kSubBatchTile - 1) / kSubBatchTile);
             hipLaunchKernelGGL(subitem_scores_batched_kernel<S_ELEMS>, grid, dim3(kSubThreads), 0, st, queries, centroids, S,
                                B, d, m, b);

@@ -58,16 +58,17 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float
 constexpr int kSubInterleave = 8;     // queries whose chains run interleaved
 constexpr int kSubBatchTile = 8;      // queries per workgroup
 
-template <int S_ELEMS>   // d/m, a multiple of 4
+template <int S_ELEMS>   // d/m (a multiple of 4) when it is one of the unrolled sizes, else 0: d/m (a multiple of 4) at run time
 __global__ __launch_bounds__(kSubThreads) void subitem_scores_batched_kernel(const float* __restrict__ queries,
                                                                              const float* __restrict__ centroids,
                                                                              float* __restrict__ S, int B, int d, int m, int b) {
+    const int s = S_ELEMS ? S_ELEMS : d / m;
     const int jblocks = (b + kSubThreads - 1) / kSubThreads;
     const int k = blockIdx.x / jblocks;                              // the same for the whole workgroup
     const int j = (blockIdx.x % jblocks) * kSubThreads + threadIdx.x;
     const bool live = j < b;
     const int kj = k * b + (live ? j : 0);
-    const float4* psi4 = reinterpret_cast<const float4*>(centroids + (size_t)kj * S_ELEMS);
+    const float4* psi4 = reinterpret_cast<const float4*>(centroids + (size_t)kj * s);
     const int q0 = blockIdx.y * kSubBatchTile;
     int q1 = q0 + kSubBatchTile;
     if (q1 > B) q1 = B;
@@ -77,11 +78,11 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_batched_kernel(con
 #pragma unroll
         for (int i = 0; i < kSubInterleave; ++i) {
             const int qi = (q + i < q1) ? q + i : q1 - 1;            // past the tile: a repeat, computed and not stored
-            phi4[i] = reinterpret_cast<const float4*>(queries + (size_t)qi * d + (size_t)k * S_ELEMS);
+            phi4[i] = reinterpret_cast<const float4*>(queries + (size_t)qi * d + (size_t)k * s);
             acc[i] = 0.0f;
         }
 #pragma unroll 4
-        for (int t4 = 0; t4 < S_ELEMS / 4; ++t4) {                   // four elements of every chain per step
+        for (int t4 = 0; t4 < s / 4; ++t4) {                         // four elements of every chain per step
             const float4 wv = psi4[t4];
 #pragma unroll
             for (int i = 0; i < kSubInterleave; ++i) {

@@ -43,7 +43,9 @@ def assert_same_topk(pq, oracle, G, S, K, tag=""):
 @pytest.mark.parametrize("B,d,m,b", [(1, 64, 4, 256), (1, 512, 8, 256), (5, 512, 16, 256), (3, 96, 3, 7),
                                      (2, 8, 8, 256), (64, 512, 8, 256), (2, 640, 5, 100), (1, 33, 1, 1),
                                      (9, 512, 8, 256), (70, 512, 16, 256), (17, 64, 4, 256), (33, 512, 8, 100),
-                                     (1024, 512, 8, 256), (12, 96, 3, 7)])
+                                     (1024, 512, 8, 256), (12, 96, 3, 7), (1, 768, 8, 256), (64, 768, 8, 256),
+                                     (300, 1024, 8, 256), (3, 1536, 12, 256), (5, 72, 6, 100), (9, 40, 8, 256),
+                                     (2, 768, 64, 256), (70, 768, 16, 256)])
 def test_subitem_scores_bit_exact(pq, oracle, B, d, m, b):
     print(f"case subitem B={B} d={d} m={m} b={b}", flush=True)
     cent = W.centroids(m, b, d, seed=B + d)
