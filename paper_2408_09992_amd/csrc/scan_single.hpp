@@ -282,8 +282,23 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
 #pragma unroll 4
             for (int e = tid; e < m * (kLutStride / 4); e += NT) dst[e] = src[e];
         }
+    } else if constexpr (M > 0) {
+        // fewer than 256 sub-ids per split (or a table that is not 16-byte aligned): element by element, rows padded
+        // with zeros to 256 entries; all values requested before the first is stored
+        constexpr int kPer = (M * kLutStride + NT - 1) / NT;
+        float tv[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = tid + i * NT, k = e / kLutStride, j = e % kLutStride;
+            tv[i] = (e < M * kLutStride && j < b) ? Sq[k * b + j] : 0.0f;
+        }
+        fetch_first();
+#pragma unroll
+        for (int i = 0; i < kPer; ++i)
+            if (tid + i * NT < M * kLutStride) lut_base[tid + i * NT] = tv[i];
     } else {
         fetch_first();
+#pragma unroll 4
         for (int e = tid; e < m * kLutStride; e += NT) {
             int k = e / kLutStride, j = e % kLutStride;
             lut_base[e] = (j < b) ? Sq[k * b + j] : 0.0f;
