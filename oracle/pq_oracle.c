@@ -8,7 +8,8 @@
  *
  * Notation as in the paper, 0-based here:
  *   N = |I| items, d embedding dim, m splits, s = d/m, b sub-ids per split, B queries, K results.
- *   codes      uint8 [N][m]       codebook G, Eq. 1
+ *   codes      uint8 [N][m]       codebook G, Eq. 1 (uint16 in the *_u16 functions: the paper's G holds natural
+ *                                 numbers and leaves b open; one byte per sub-id is the b <= 256 case)
  *   centroids  float [m][b][s]    sub-item embeddings Psi_k (Section 2, "Sub-Id based recommendation")
  *   queries    float [B][d]       sequence embeddings phi; phi_k is the k-th contiguous chunk of length s (Section 3)
  *   S          float [B][m][b]    sub-id score matrix, Eq. 4
@@ -301,3 +302,70 @@ int pq_oracle_default_scores(const float* W, const float* queries, long long N, 
     return 0;
 }
 
+
+/* ---- sub-ids wider than a byte (b up to 65536): the same definitions over uint16 codes ---- */
+
+/* Eq. 5 / Algorithm 1, the loop over items, for ONE query (S is [m][b]), codes uint16 [N][m]. */
+int pq_oracle_item_scores_u16(const uint16_t* codes, const float* S, float* score, long long N, int m, int b) {
+    if (!codes || !S || !score || N < 1 || m < 1 || b < 1 || b > 65536) return -1;
+    for (long long i = 0; i < N; ++i)
+        for (int k = 0; k < m; ++k)
+            if (codes[i * m + k] >= b) return -1;
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < N; ++i) {
+        const uint16_t* g = codes + i * m;
+        float acc = S[g[0]];
+        for (int k = 1; k < m; ++k) acc = acc + S[(size_t)k * b + g[k]];
+        score[i] = acc + 0.0f;
+    }
+    return 0;
+}
+
+/* Algorithm 1 with V = I for a batch, codes uint16 [N][m]: score all items from the query's S, then TopK. */
+int pq_oracle_score_topk_u16(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                             int* out_ids, float* out_scores) {
+    if (!codes || !S || !out_ids || !out_scores || N < 1 || B < 1 || m < 1 || b < 1 || b > 65536 || K < 1 ||
+        K > N || N >= 2147483648LL)
+        return -1;
+    float* score = (float*)malloc((size_t)N * sizeof(float));
+    if (!score) return -1;
+    int rc = 0;
+    for (int q = 0; q < B && rc == 0; ++q) {
+        rc = pq_oracle_item_scores_u16(codes, S + (size_t)q * m * b, score, N, m, b);
+        if (rc == 0) rc = pq_oracle_topk(score, N, K, out_ids + (size_t)q * K, out_scores + (size_t)q * K);
+    }
+    free(score);
+    return rc;
+}
+
+/* Exhaustive scoring by reconstruction in float64 (Eq. 2, Eq. 3, full sort), codes uint16 [N][m]. */
+int pq_oracle_bruteforce_topk_u16(const uint16_t* codes, const float* centroids, const float* queries,
+                                  long long N, int B, int d, int m, int b, int K, int* out_ids, double* out_scores) {
+    if (!codes || !centroids || !queries || !out_ids || !out_scores || N < 1 || B < 1 || d < 1 || m < 1 ||
+        b < 1 || b > 65536 || d % m != 0 || K < 1 || K > N || N >= 2147483648LL)
+        return -1;
+    const int s = d / m;
+    dpair_t* all = (dpair_t*)malloc((size_t)N * sizeof(dpair_t));
+    if (!all) return -1;
+    for (int q = 0; q < B; ++q) {
+        const float* phi = queries + (size_t)q * d;
+        for (long long i = 0; i < N; ++i) {
+            double r = 0.0;                                     /* Eq. 3 over the concatenation of Eq. 2, in place */
+            for (int k = 0; k < m; ++k) {
+                int g = codes[i * m + k];
+                if (g >= b) { free(all); return -1; }
+                const float* psi = centroids + ((size_t)k * b + g) * s;
+                for (int t = 0; t < s; ++t) r += (double)psi[t] * (double)phi[k * s + t];
+            }
+            all[i].score = r;
+            all[i].id = (int)i;
+        }
+        qsort(all, (size_t)N, sizeof(dpair_t), dpair_cmp);
+        for (int r = 0; r < K; ++r) {
+            out_ids[(size_t)q * K + r] = all[r].id;
+            out_scores[(size_t)q * K + r] = all[r].score;
+        }
+    }
+    free(all);
+    return 0;
+}

@@ -46,6 +46,9 @@ def _load():
         lib.pq_oracle_bruteforce_topk.argtypes = [P, P, P, LL, I, I, I, I, I, P, P]
         lib.pq_oracle_reconstruct.argtypes = [P, P, LL, I, I, I, P]
         lib.pq_oracle_default_scores.argtypes = [P, P, LL, I, I, P]
+        lib.pq_oracle_item_scores_u16.argtypes = [P, P, P, LL, I, I]
+        lib.pq_oracle_score_topk_u16.argtypes = [P, P, LL, I, I, I, I, P, P]
+        lib.pq_oracle_bruteforce_topk_u16.argtypes = [P, P, P, LL, I, I, I, I, I, P, P]
         _lib = lib
     return _lib
 
@@ -199,3 +202,47 @@ def default_scores(W: np.ndarray, queries: np.ndarray) -> np.ndarray:
     _check(_load().pq_oracle_default_scores(_p(W), _p(queries), N, B, d, _p(out)), "default_scores")
     return out
 
+
+
+def item_scores_u16(codes: np.ndarray, S1: np.ndarray) -> np.ndarray:
+    """Eq. 5 for one query over uint16 codes (S1 is [m][b], b up to 65536) -> fp32 [N]."""
+    codes = _c(codes, np.uint16)
+    S1 = _c(S1, np.float32)
+    N, m = codes.shape
+    if S1.shape[0] != m:
+        raise ValueError("S does not match m")
+    out = np.empty(N, dtype=np.float32)
+    _check(_load().pq_oracle_item_scores_u16(_p(codes), _p(S1), _p(out), N, m, S1.shape[1]), "item_scores_u16")
+    return out
+
+
+def score_topk_u16(codes: np.ndarray, S: np.ndarray, K: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 1 (V = I) over uint16 codes for a batch -> (ids int32 [B][K], scores fp32 [B][K])."""
+    codes = _c(codes, np.uint16)
+    S = _c(S, np.float32)
+    N, m = codes.shape
+    B, m2, b = S.shape
+    if m2 != m:
+        raise ValueError("S does not match m")
+    ids = np.empty((B, K), dtype=np.int32)
+    sc = np.empty((B, K), dtype=np.float32)
+    _check(_load().pq_oracle_score_topk_u16(_p(codes), _p(S), N, B, m, b, K, _p(ids), _p(sc)), "score_topk_u16")
+    return ids, sc
+
+
+def bruteforce_topk_u16(codes: np.ndarray, centroids: np.ndarray, queries: np.ndarray, K: int):
+    """Reconstruction (Eq. 2) and full dot products in float64 (Eq. 3) over uint16 codes, sorted.
+    -> (ids int32 [B][K], scores float64 [B][K])."""
+    codes = _c(codes, np.uint16)
+    centroids = _c(centroids, np.float32)
+    queries = _c(queries, np.float32)
+    N, m = codes.shape
+    B, d = queries.shape
+    m2, b, s = centroids.shape
+    if m2 != m or m * s != d:
+        raise ValueError("shape mismatch")
+    ids = np.empty((B, K), dtype=np.int32)
+    sc = np.empty((B, K), dtype=np.float64)
+    _check(_load().pq_oracle_bruteforce_topk_u16(_p(codes), _p(centroids), _p(queries), N, B, d, m, b, K,
+                                                 _p(ids), _p(sc)), "bruteforce_topk_u16")
+    return ids, sc

@@ -120,6 +120,20 @@ def codes_uniform(N: int, m: int, b: int = 256, seed: int = 0) -> np.ndarray:
     return out.reshape(N, m)
 
 
+def codes_uniform_u16(N: int, m: int, b: int, seed: int = 0) -> np.ndarray:
+    """G as uint16 [N][m] for alphabets of up to 65536 sub-ids per split, each sub-id uniform on [0, b)."""
+    if not 1 <= b <= 65536:
+        raise ValueError("b must be in 1..65536")
+    key = stream_key(seed, STREAM_CODES)
+    total = N * m
+    out = np.empty(total, dtype=np.uint16)
+    for lo in range(0, total, _CHUNK):
+        n = min(_CHUNK, total - lo)
+        u = u64_at(key, lo, n) >> np.uint64(32)
+        out[lo:lo + n] = ((u * np.uint64(b)) >> np.uint64(32)).astype(np.uint16)
+    return out.reshape(N, m)
+
+
 def zipf_cdf(b: int, s: float) -> np.ndarray:
     """Cumulative distribution of P(rank r) proportional to r**-s over ranks 1..b."""
     w = np.arange(1, b + 1, dtype=np.float64) ** (-s)

@@ -515,3 +515,90 @@ def test_default_scores_linear_and_exact_on_integers(oracle):
     assert np.array_equal(r, (Wm.astype(np.int64) @ Q.astype(np.int64).T).T.astype(np.float64))
     assert np.array_equal(oracle.default_scores(Wm, Q[:1] + Q[1:]), r[:1] + r[1:])
 
+
+
+# ---------------------------------------------------------------- sub-ids wider than a byte (uint16 codes)
+
+def test_u16_closed_form_integer_scores(oracle):
+    # s = 1, psi_0[j] = j, psi_1[j] = 1000 - j, phi = (1, 2): the score of an item with sub-ids (g0, g1) is the integer
+    # g0 + 2 (1000 - g1), exact in fp32; sub-ids above 255 and the last one (b - 1) take part
+    b = 300
+    cent = np.stack([np.arange(b), 1000 - np.arange(b)]).astype(np.float32).reshape(2, b, 1)
+    phi = np.array([[1.0, 2.0]], dtype=np.float32)
+    S = oracle.subitem_scores(phi, cent)
+    G = np.array([[299, 0], [256, 257], [0, 299], [255, 255], [43, 0], [299, 128], [258, 258], [1, 1]], dtype=np.uint16)
+    want = G[:, 0].astype(np.int64) + 2 * (1000 - G[:, 1].astype(np.int64))
+    got = oracle.item_scores_u16(G, S[0])
+    assert got.tolist() == want.astype(np.float64).tolist()
+    order = np.lexsort((np.arange(len(G)), -want))
+    assert want[6] == want[1] == 1742                          # a tie between sub-ids above 255: lower id first
+    ids, sc = oracle.score_topk_u16(G, S, 7)
+    # 2299 | 2043 twice (items 4, 5) | 1999 | 1745 | 1742 twice (items 1, 6) | 402 is left out
+    assert ids[0].tolist() == order[:7].tolist() == [0, 4, 5, 7, 3, 1, 6]
+    assert sc[0].tolist() == want[order[:7]].astype(np.float64).tolist()
+    bid, bsc = oracle.bruteforce_topk_u16(G, cent, phi, 7)
+    assert bid[0].tolist() == order[:7].tolist() and bsc[0].tolist() == want[order[:7]].astype(np.float64).tolist()
+
+
+def test_u16_with_byte_sized_sub_ids_equals_the_uint8_functions(oracle):
+    rng = np.random.default_rng(5)
+    for (N, m, B, K) in ((500, 8, 2, 20), (77, 3, 1, 77), (1000, 16, 3, 1)):
+        G8 = W.codes_uniform(N, m, 256, seed=N)
+        S = rng.standard_normal((B, m, 256)).astype(np.float32)
+        G16 = G8.astype(np.uint16)
+        assert np.array_equal(oracle.item_scores_u16(G16, S[0]).view(np.uint32), oracle.item_scores(G8, S[0]).view(np.uint32))
+        i8, s8 = oracle.score_topk(G8, S, K)
+        i16, s16 = oracle.score_topk_u16(G16, S, K)
+        assert np.array_equal(i8, i16) and np.array_equal(s8.view(np.uint32), s16.view(np.uint32))
+
+
+def test_u16_random_shapes_vs_reconstruction(oracle):
+    rng = np.random.default_rng(4321)
+    n_cases = 0
+    for m in (1, 2, 3, 4, 8):
+        for b in (257, 1000, 4096, 65536):
+            for rep in range(4):
+                s = int(rng.integers(1, 5))
+                d = m * s
+                N = int(rng.integers(1, 301))
+                K = int(rng.integers(1, min(N, 20) + 1))
+                B = int(rng.integers(1, 3))
+                seed = 1000 * m + b + rep
+                G = W.codes_uniform_u16(N, m, b, seed=seed)
+                assert G.dtype == np.uint16 and int(G.max()) < b
+                cent = W.centroids(m, b, d, seed=seed)
+                Q = W.queries(B, d, seed=seed)
+                S = oracle.subitem_scores(Q, cent)
+                ids, sc = oracle.score_topk_u16(G, S, K)
+                Wf = reconstruct(G, cent)
+                bid, bsc = oracle.bruteforce_topk_u16(G, cent, Q, K)
+                for q in range(B):
+                    ref = Wf @ Q[q].astype(np.float64)
+                    assert_topk_matches_f64(ids[q], sc[q], ref, K)
+                    assert_topk_matches_f64(bid[q], bsc[q], ref, K, rel=1e-9)
+                n_cases += 1
+    assert n_cases == 80
+
+
+def test_u16_left_to_right_fp32_and_high_byte_matters(oracle):
+    # the chain's order shows in the last bit: (1e8 + 1) - 1e8 is 0 in fp32 left to right, 1 right to left;
+    # and sub-ids that differ only above bit 7 must read different table entries
+    b = 600
+    S1 = np.zeros((3, b), dtype=np.float32)
+    S1[0, 513] = 1e8
+    S1[1, 300] = 1.0
+    S1[2, 599] = -1e8
+    S1[0, 1] = 7.0                                             # 513 & 0xFF
+    G = np.array([[513, 300, 599], [1, 300, 599], [513, 44, 87]], dtype=np.uint16)
+    got = oracle.item_scores_u16(G, S1)
+    assert got.tolist() == [0.0, float(np.float32(np.float32(7.0 + 1.0) + np.float32(-1e8))), 1e8]
+
+
+def test_u16_argument_errors(oracle):
+    S = np.zeros((1, 2, 300), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.score_topk_u16(np.array([[300, 0]], dtype=np.uint16), S, 1)            # sub-id out of range
+    with pytest.raises(ValueError):
+        oracle.score_topk_u16(np.array([[1, 0]], dtype=np.uint16), S, 2)              # K > N
+    with pytest.raises(ValueError):
+        oracle.item_scores_u16(np.array([[1, 0]], dtype=np.uint16), np.zeros((2, 65537), dtype=np.float32))
