@@ -37,7 +37,7 @@ extern "C" {
 
 #define PQ_OK                0
 #define PQ_ERR_NULL         -1   /* a required pointer is NULL */
-#define PQ_ERR_SHAPE        -2   /* B, d, m, b, K or N < 1; d % m != 0; b > 256; K > N; N >= 2^31 */
+#define PQ_ERR_SHAPE        -2   /* B, d, m, b, K or N < 1; d % m != 0; b > 256 (65536 for 16-bit sub-ids); K > N; N >= 2^31 */
 #define PQ_ERR_UNSUPPORTED  -3   /* valid problem, but outside what the kernels cover (see PQ_MAX_*) */
 #define PQ_ERR_WORKSPACE    -4   /* workspace smaller than pq_score_topk_workspace_bytes() */
 #define PQ_ERR_ALIGN        -5   /* a pointer is not aligned as required */
@@ -52,6 +52,7 @@ extern "C" {
  *   queries    in   float [B][d]        sequence embeddings; chunk k is elements k*d/m .. (k+1)*d/m - 1
  *   centroids  in   float [m][b][d/m]   Psi_k, row j is psi_{k,j}
  *   S          out  float [B][m][b]
+ * b may be as large as 65536 here (S does not depend on how the codebook stores its sub-ids).
  * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (B > PQ_MAX_B), PQ_ERR_ALIGN, PQ_ERR_HIP.
  */
 int pq_subitem_scores(const float* queries, const float* centroids, float* S,
@@ -80,6 +81,23 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K);
  */
 int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
                   int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Algorithm 1 with V = I for codebooks whose sub-ids do not fit a byte.  The paper's codebook G holds natural numbers
+ * and leaves b, the number of sub-ids per split, open (Section 2, Eq. 1); pq_score_topk() covers b <= 256 with one
+ * byte per sub-id, this entry point b <= 65536 with two.  Same arithmetic, order and output as pq_score_topk().
+ *   codes       in   uint16 [N][m]    codebook G, sub-ids < b (16-byte aligned)
+ *   S           in   float [B][m][b]
+ *   workspace        at least pq_score_topk_u16_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned
+ * The query's whole m x b table is held in LDS: m * b * 4 bytes plus the candidate lists (about 80 *
+ * nextpow2(K + 64) bytes) must fit 160 KB, e.g. m * b <= 36864 at K = 10 (m = 8: b <= 4608).  Rows of 8, 16 or 32
+ * bytes (m = 4, 8, 16) are scanned as 16-byte vectors; any other m row by row.  Every query of a batch scans the
+ * codebook by itself (no shared pass).  A sub-id >= b reads an unspecified LDS word (never device memory).
+ * Errors: as pq_score_topk(), with PQ_ERR_SHAPE for b > 65536 and PQ_ERR_UNSUPPORTED when the table does not fit LDS.
+ */
+size_t pq_score_topk_u16_workspace_bytes(long long N, int B, int m, int b, int K);
+int pq_score_topk_u16(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                      int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Bytes of device workspace pq_score_topk_subset() needs for a candidate list of n_subset items.  Pure host
@@ -167,6 +185,11 @@ int pq_default_scores(const float* W, const float* queries, long long N, int B, 
 int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
                           int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
                           void* stream, int iters, float* scan_ms);
+
+/* pq_score_topk_profile() for 16-bit sub-ids: times the scan kernel of pq_score_topk_u16(). */
+int pq_score_topk_u16_profile(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                              int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
+                              void* stream, int iters, float* scan_ms);
 
 /*
  * Measurement aid: a plain streaming-read kernel (16-byte loads and nothing else) over `bytes` bytes at `data`

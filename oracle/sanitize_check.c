@@ -18,6 +18,10 @@ int pq_oracle_bruteforce_topk(const uint8_t*, const float*, const float*, long l
                               double*);
 int pq_oracle_reconstruct(const uint8_t*, const float*, long long, int, int, int, float*);
 int pq_oracle_default_scores(const float*, const float*, long long, int, int, double*);
+int pq_oracle_item_scores_u16(const uint16_t*, const float*, float*, long long, int, int);
+int pq_oracle_score_topk_u16(const uint16_t*, const float*, long long, int, int, int, int, int*, float*);
+int pq_oracle_bruteforce_topk_u16(const uint16_t*, const float*, const float*, long long, int, int, int, int, int, int*,
+                                  double*);
 
 static uint64_t state = 0x9E3779B97F4A7C15ull;
 static uint32_t rnd(void) {
@@ -61,6 +65,15 @@ int main(void) {
         CHECK(pq_oracle_bruteforce_topk(G, cent, Q, N, B, d, m, b, K, ids, dout));
         CHECK(pq_oracle_reconstruct(G, cent, N, d, m, b, W));
         CHECK(pq_oracle_default_scores(W, Q, N, B, d, r));
+        {   /* the same catalogue with its sub-ids held in 16 bits */
+            uint16_t* G16 = malloc(sizeof(uint16_t) * (size_t)N * m);
+            if (!G16) return 2;
+            for (long long i = 0; i < N * m; ++i) G16[i] = G[i];
+            CHECK(pq_oracle_item_scores_u16(G16, S, sc, N, m, b));
+            CHECK(pq_oracle_score_topk_u16(G16, S, N, B, m, b, K, ids, out));
+            CHECK(pq_oracle_bruteforce_topk_u16(G16, cent, Q, N, B, d, m, b, K, ids, dout));
+            free(G16);
+        }
         free(G); free(cent); free(Q); free(S); free(sc); free(W); free(r); free(ids); free(out); free(dout); free(sub);
     }
     puts("sanitized oracle run: ok");

@@ -5,7 +5,8 @@ C-ABI library on first use and raise if it has not been built (there is no CPU f
 """
 from __future__ import annotations
 
-__all__ = ["workloads", "pq_subitem_scores", "pq_score_topk", "pq_score_topk_workspace_bytes", "pq_score_topk_subset",
+__all__ = ["workloads", "pq_subitem_scores", "pq_score_topk", "pq_score_topk_workspace_bytes", "pq_score_topk_u16",
+           "pq_score_topk_u16_workspace_bytes", "pq_score_topk_subset",
            "pq_score_topk_subset_workspace_bytes", "pq_topk_scores", "pq_topk_scores_workspace_bytes", "pq_recjpq_scores",
            "pq_reconstruct_items", "pq_default_scores", "pq_strerror"]
 

@@ -43,6 +43,12 @@ def lib() -> ctypes.CDLL:
         L.pq_score_topk.restype = I
         L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
         L.pq_score_topk_profile.restype = I
+        L.pq_score_topk_u16_workspace_bytes.argtypes = [LL, I, I, I, I]
+        L.pq_score_topk_u16_workspace_bytes.restype = SZ
+        L.pq_score_topk_u16.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
+        L.pq_score_topk_u16.restype = I
+        L.pq_score_topk_u16_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
+        L.pq_score_topk_u16_profile.restype = I
         L.pq_score_topk_subset_workspace_bytes.argtypes = [LL, I, I, I, I]
         L.pq_score_topk_subset_workspace_bytes.restype = SZ
         L.pq_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P, P, SZ, P]
@@ -101,14 +107,14 @@ def pq_score_topk_workspace_bytes(N: int, B: int, m: int, b: int, K: int) -> int
     return int(lib().pq_score_topk_workspace_bytes(N, B, m, b, K))
 
 
-def _topk_args(codes, S, K, workspace, out_ids, out_scores):
-    _dev(codes, torch.uint8, "codes")
+def _topk_args(codes, S, K, workspace, out_ids, out_scores, wide=False):
+    _dev(codes, torch.uint16 if wide else torch.uint8, "codes")
     _dev(S, torch.float32, "S")
     N, m = codes.shape
     B, m2, b = S.shape
     if m2 != m:
         raise PQError(PQ_ERR_SHAPE, "pq_score_topk")
-    need = pq_score_topk_workspace_bytes(N, B, m, b, K)
+    need = (pq_score_topk_u16_workspace_bytes if wide else pq_score_topk_workspace_bytes)(N, B, m, b, K)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=codes.device)
     if out_ids is None:
@@ -130,6 +136,36 @@ def pq_score_topk(codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optio
     if rc != PQ_OK:
         raise PQError(rc, "pq_score_topk")
     return out_ids, out_scores
+
+
+def pq_score_topk_u16_workspace_bytes(N: int, B: int, m: int, b: int, K: int) -> int:
+    return int(lib().pq_score_topk_u16_workspace_bytes(N, B, m, b, K))
+
+
+def pq_score_topk_u16(codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optional[torch.Tensor] = None,
+                      out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None
+                      ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Algorithm 1 (V = I) over 16-bit sub-ids: codes uint16 [N][m], S fp32 [B][m][b], b <= 65536
+    -> (ids int32 [B][K], scores fp32 [B][K])."""
+    N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores, wide=True)
+    rc = lib().pq_score_topk_u16(codes.data_ptr(), S.data_ptr(), N, B, m, b, K, out_ids.data_ptr(),
+                                 out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_score_topk_u16")
+    return out_ids, out_scores
+
+
+def pq_score_topk_u16_profile(codes: torch.Tensor, S: torch.Tensor, K: int, iters: int,
+                              workspace: Optional[torch.Tensor] = None) -> float:
+    """Mean duration (ms) of pq_score_topk_u16's scan kernel over `iters` launches, from HIP events on the stream."""
+    N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, None, None, wide=True)
+    ms = ctypes.c_float(0.0)
+    rc = lib().pq_score_topk_u16_profile(codes.data_ptr(), S.data_ptr(), N, B, m, b, K, out_ids.data_ptr(),
+                                         out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(),
+                                         iters, ctypes.byref(ms))
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_score_topk_u16_profile")
+    return float(ms.value)
 
 
 def pq_score_topk_subset_workspace_bytes(n_subset: int, B: int, m: int, b: int, K: int) -> int:
@@ -318,6 +354,23 @@ class PreparedScoreTopK:
         if rc != PQ_OK:
             raise PQError(rc, "pq_score_topk")
         return self.ids, self.scores
+
+
+class PreparedScoreTopKU16(PreparedScoreTopK):
+    """pq_score_topk_u16 with its arguments marshalled once."""
+
+    def __init__(self, codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optional[torch.Tensor] = None,
+                 out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
+                 stream: Optional[int] = None):
+        N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores, wide=True)
+        self.ids, self.scores, self.workspace = out_ids, out_scores, workspace
+        self._keep = (codes, S)
+        st = _stream() if stream is None else stream
+        c = ctypes
+        self._fn = lib().pq_score_topk_u16
+        self._args = (c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_longlong(N), c.c_int(B), c.c_int(m),
+                      c.c_int(b), c.c_int(K), c.c_void_p(out_ids.data_ptr()), c.c_void_p(out_scores.data_ptr()),
+                      c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), c.c_void_p(st))
 
 
 class PreparedScoreTopKSubset:

@@ -76,12 +76,17 @@ struct ScanPlan {
 
 bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32 || m == 64; }
 
+bool is_vec_m16(int m) { return m == 4 || m == 8 || m == 16; }   // 16-bit sub-ids: rows of 8, 16 or 32 bytes
+
 // `generic`: plan for the generic kernel whatever m is (candidate-list scans use it: their rows are gathered)
-ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
+// `cw`, `b`: bytes per sub-id (1 or 2) and, for two-byte sub-ids, the alphabet size (it sizes the tables in LDS)
+ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int cw = 1, int b = kLutStride) {
     ScanPlan p;
-    p.vec = !generic && is_vec_m(m) && N * m >= 16;            // (the vector kernels need one whole code vector at least)
-    const long long units = (p.vec && m <= 16) ? (N * m) / 16 : N;   // whole code vectors (the few items after them are extra)
-    const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
+    const int row = m * cw;                                    // bytes of an item's row
+    const size_t lut_floats = cw == 1 ? (size_t)m * kLutStride : (size_t)m * b;
+    p.vec = !generic && (cw == 1 ? is_vec_m(m) : is_vec_m16(m)) && N * row >= 16;   // (one whole code vector at least)
+    const long long units = (p.vec && row <= 16) ? (N * row) / 16 : N;   // whole code vectors (the few items after them are extra)
+    const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(row) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
     if (most < 8) most = 8;
@@ -102,7 +107,7 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
     // A long scan for few queries is bound by LDS bank conflicts of the random lookups: with kTableCopies copies of
     // the tables, lanes l and l' collide only if l % kTableCopies == l' % kTableCopies.  Worth its LDS and fill time
     // only when every workgroup streams many rounds; one workgroup per CU then (the tables take 128 KB at m = 8).
-    if (p.vec && m <= 8) {
+    if (cw == 1 && p.vec && m <= 8) {
         const long long nb = kAssumedCUs / B;                  // one workgroup (of kBigThreads) per CU over the whole grid
         const long long big_round = (long long)kBigThreads * vec_per_thread(m);
         const long long big_rounds = (units + big_round - 1) / big_round;
@@ -113,17 +118,18 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
             p.nblk = (int)nb;
         }
     }
-    // A generic scan whose tables leave room for only one 512-thread workgroup per CU (m > 36 or so) runs 1024-thread
-    // workgroups instead, one per CU: the same tables then serve sixteen waves, which is what hides the latency of
-    // the row loads.  Only when there is more than one workgroup's worth of work per CU.
+    // A scan whose tables leave room for only one 512-thread workgroup per CU (generic: m > 36 or so; m = 64; large
+    // alphabets of two-byte sub-ids) runs 1024-thread workgroups instead, one per CU: the same tables then serve
+    // sixteen waves, which is what hides the latency of the row loads.  Only when there is more than one workgroup's
+    // worth of work per CU.
     p.big = p.copies > 1;
-    if (!p.vec || m == 64) {
-        const size_t small = scan_lds_bytes((size_t)m * kLutStride, p.cap, p.candmax, K, kWaves);
-        const size_t big = scan_lds_bytes((size_t)m * kLutStride, p.cap, p.candmax, K, kMaxWaves);
+    if (!p.vec || m == 64 || cw == 2) {
+        const size_t small = scan_lds_bytes(lut_floats, p.cap, p.candmax, K, kWaves);
+        const size_t big = scan_lds_bytes(lut_floats, p.cap, p.candmax, K, kMaxWaves);
         long long nb = kAssumedCUs / B;
         if (nb < 8) nb = 8;
         if (2 * small > kMaxLdsBytes && big <= kMaxLdsBytes && rounds > nb) {
-            const long long big_round = (long long)kBigThreads * (p.vec ? vec_per_thread(m) : kGenericItemsPerThread);
+            const long long big_round = (long long)kBigThreads * (p.vec ? vec_per_thread(row) : kGenericItemsPerThread);
             const long long big_rounds = (units + big_round - 1) / big_round;
             if (big_rounds < nb) nb = big_rounds;
             if (B > 1 && nb >= 8) nb &= ~7LL;
@@ -131,14 +137,15 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false) {
             p.nblk = (int)nb;
         }
     }
-    const size_t lut_dyn = p.copies > 1 ? (size_t)m * kLutStride * p.copies : (p.vec ? 0 : (size_t)m * kLutStride);
+    const bool static_lut = p.vec && p.copies == 1 && cw == 1;   // tables in the kernel's static LDS array
+    const size_t lut_dyn = p.copies > 1 ? lut_floats * p.copies : (static_lut ? 0 : lut_floats);
     p.scan_dyn_lds = scan_lds_bytes(lut_dyn, p.cap, p.candmax, K, p.big ? kMaxWaves : kWaves);
-    p.scan_lds = p.scan_dyn_lds + ((p.vec && p.copies == 1) ? (size_t)m * kLutStride * sizeof(float) : 0);
+    p.scan_lds = p.scan_dyn_lds + (static_lut ? lut_floats * sizeof(float) : 0);
     p.tiled = false;
     // (a small batch over a small catalogue is faster as B single-query scans side by side: the batched kernel's
     // fixed costs, about 15 us of table fill, first-round cuts and final merge, are not yet paid back)
     const bool small_job = B <= 2 || (double)B * (double)N * m <= kTiledMinLookups;
-    if (!generic && !small_job && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
+    if (cw == 1 && !generic && !small_job && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
         if (all <= kMaxLdsBytes) {
@@ -172,12 +179,19 @@ size_t workspace_bytes(const ScanPlan& p, int B, int K) {
     return keys_bytes(p, B, K) + ((fold_area_keys(p.nblk, B, K) * sizeof(uint64_t) + 255) & ~(size_t)255);
 }
 
-int check_topk_args(const void* codes, const void* S, long long N, int B, int m, int b, int K, const void* out_ids,
-                    const void* out_scores, const void* workspace, size_t workspace_bytes_given) {
-    if (!codes || !S || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
-    if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return PQ_ERR_SHAPE;
+int check_topk_shape(long long N, int B, int m, int b, int K, int cw) {
+    if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > (cw == 1 ? 256 : 65536) || K > N || N >= 2147483648LL)
+        return PQ_ERR_SHAPE;
     if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return PQ_ERR_UNSUPPORTED;
-    const ScanPlan p = make_plan(N, B, m, K);
+    return PQ_OK;
+}
+
+int check_topk_args(const void* codes, const void* S, long long N, int B, int m, int b, int K, const void* out_ids,
+                    const void* out_scores, const void* workspace, size_t workspace_bytes_given, int cw = 1) {
+    if (!codes || !S || !out_ids || !out_scores || !workspace) return PQ_ERR_NULL;
+    const int rc = check_topk_shape(N, B, m, b, K, cw);
+    if (rc != PQ_OK) return rc;
+    const ScanPlan p = make_plan(N, B, m, K, false, cw, b);
     if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)codes & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)S & 3) || ((uintptr_t)out_ids & 3) ||
         ((uintptr_t)out_scores & 3))
@@ -193,9 +207,9 @@ hipError_t allow_lds(KernelT kernel, size_t bytes) {
                                (int)bytes);
 }
 
-template <int M>
+template <int M, int CW = 1>
 hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
-    if constexpr (M >= 1 && M <= 8) {
+    if constexpr (CW == 1 && M >= 1 && M <= 8) {
         if (p.copies == kTableCopies) {
             hipError_t e = allow_lds(scan_topk_kernel<M, kTableCopies, kBigThreads>, p.scan_dyn_lds);
             if (e != hipSuccess) return e;
@@ -204,25 +218,26 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
             return hipGetLastError();
         }
     }
-    if constexpr (M == 0 || M == 64) {
+    if constexpr (M == 0 || M == 64 || CW == 2) {
         if (p.big) {
-            hipError_t e = allow_lds(scan_topk_kernel<M, 1, kBigThreads>, p.scan_dyn_lds);
+            hipError_t e = allow_lds(scan_topk_kernel<M, 1, kBigThreads, CW>, p.scan_dyn_lds);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL((scan_topk_kernel<M, 1, kBigThreads>), dim3(p.nblk, B), dim3(kBigThreads),
+            hipLaunchKernelGGL((scan_topk_kernel<M, 1, kBigThreads, CW>), dim3(p.nblk, B), dim3(kBigThreads),
                                p.scan_dyn_lds, st, a);
             return hipGetLastError();
         }
     }
-    hipError_t e = allow_lds(scan_topk_kernel<M>, p.scan_dyn_lds);
+    hipError_t e = allow_lds(scan_topk_kernel<M, 1, kThreads, CW>, p.scan_dyn_lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(scan_topk_kernel<M>, dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
+    hipLaunchKernelGGL((scan_topk_kernel<M, 1, kThreads, CW>), dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
     return hipGetLastError();
 }
 
 // Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
 // `subset` / `n_items`: candidate list (then N is its length and the plan is a generic one) or nullptr / N
+// `cw`: bytes per sub-id (2: `codes` holds uint16 values)
 int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                 void* workspace, hipStream_t st, const int* subset = nullptr, long long n_items = 0) {
+                 void* workspace, hipStream_t st, const int* subset = nullptr, long long n_items = 0, int cw = 1) {
     ScanArgs a;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
     a.subset = subset; a.n_items = (uint32_t)(subset ? n_items : N);
@@ -240,6 +255,15 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
             if (e == hipSuccess) hipLaunchKernelGGL(scan_topk_tiled_kernel<16>, grid, dim3(kThreads), p.scan_dyn_lds, st, a, B);
         }
         return record_hip(e == hipSuccess ? hipGetLastError() : e);
+    }
+    if (cw == 2) {
+        switch (p.vec ? m : 0) {
+            case 4: e = launch_scan<4, 2>(p, a, B, st); break;
+            case 8: e = launch_scan<8, 2>(p, a, B, st); break;
+            case 16: e = launch_scan<16, 2>(p, a, B, st); break;
+            default: e = launch_scan<0, 2>(p, a, B, st); break;
+        }
+        return record_hip(e);
     }
     switch (p.vec ? m : 0) {
         case 1: e = launch_scan<1>(p, a, B, st); break;
@@ -319,7 +343,7 @@ extern "C" {
 int pq_subitem_scores(const float* queries, const float* centroids, float* S, int B, int d, int m, int b,
                       void* stream) {
     if (!queries || !centroids || !S) return PQ_ERR_NULL;
-    if (B < 1 || d < 1 || m < 1 || b < 1 || b > 256 || d % m != 0) return PQ_ERR_SHAPE;
+    if (B < 1 || d < 1 || m < 1 || b < 1 || b > 65536 || d % m != 0) return PQ_ERR_SHAPE;
     if (B > PQ_MAX_B || m > PQ_MAX_M) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)S & 3)) return PQ_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -335,8 +359,7 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
 }
 
 size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K) {
-    if (N < 1 || B < 1 || m < 1 || b < 1 || K < 1 || b > 256 || K > N || N >= 2147483648LL) return 0;
-    if (K > PQ_MAX_K || m > PQ_MAX_M || B > PQ_MAX_B) return 0;
+    if (check_topk_shape(N, B, m, b, K, 1) != PQ_OK) return 0;
     const ScanPlan p = make_plan(N, B, m, K);
     if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
     return workspace_bytes(p, B, K);
@@ -353,23 +376,28 @@ int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int 
     return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
 }
 
-int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                          int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes_given,
-                          void* stream, int iters, float* scan_ms) {
+}  // extern "C"
+
+namespace {
+// scan launches of a pq_score_topk / pq_score_topk_u16 call timed between two events (one untimed launch first)
+int profile_scan(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
+                 float* out_scores, void* workspace, size_t workspace_bytes_given, void* stream, int iters,
+                 float* scan_ms, int cw) {
     if (!scan_ms) return PQ_ERR_NULL;
-    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
+    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given, cw);
     if (rc != PQ_OK) return rc;
     if (iters < 1) return PQ_ERR_SHAPE;
-    const ScanPlan p = make_plan(N, B, m, K);
+    const ScanPlan p = make_plan(N, B, m, K, false, cw, b);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     hipError_t e = hipEventCreate(&ev0);
     if (e != hipSuccess) return record_hip(e);
     e = hipEventCreate(&ev1);
     if (e != hipSuccess) { (void)hipEventDestroy(ev0); return record_hip(e); }
-    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);           // untimed warm-up launch
+    auto scan = [&]() { return enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st, nullptr, 0, cw); };
+    rc = scan();                                                            // untimed warm-up launch
     if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev0, st));
-    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
+    for (int it = 0; it < iters && rc == PQ_OK; ++it) rc = scan();
     if (rc == PQ_OK) rc = record_hip(hipEventRecord(ev1, st));
     if (rc == PQ_OK) rc = enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
     if (rc == PQ_OK) rc = record_hip(hipStreamSynchronize(st));
@@ -379,6 +407,41 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
     (void)hipEventDestroy(ev1);
     if (rc == PQ_OK) *scan_ms = ms / (float)iters;
     return rc;
+}
+}  // namespace
+
+extern "C" {
+
+int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                          int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes_given,
+                          void* stream, int iters, float* scan_ms) {
+    return profile_scan(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given, stream, iters,
+                        scan_ms, 1);
+}
+
+size_t pq_score_topk_u16_workspace_bytes(long long N, int B, int m, int b, int K) {
+    if (check_topk_shape(N, B, m, b, K, 2) != PQ_OK) return 0;
+    const ScanPlan p = make_plan(N, B, m, K, false, 2, b);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return 0;
+    return workspace_bytes(p, B, K);
+}
+
+int pq_score_topk_u16(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
+                      float* out_scores, void* workspace, size_t workspace_bytes_given, void* stream) {
+    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given, 2);
+    if (rc != PQ_OK) return rc;
+    const ScanPlan p = make_plan(N, B, m, K, false, 2, b);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = enqueue_scan(p, reinterpret_cast<const uint8_t*>(codes), S, N, B, m, b, K, workspace, st, nullptr, 0, 2);
+    if (rc != PQ_OK) return rc;
+    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+}
+
+int pq_score_topk_u16_profile(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                              int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes_given,
+                              void* stream, int iters, float* scan_ms) {
+    return profile_scan(reinterpret_cast<const uint8_t*>(codes), S, N, B, m, b, K, out_ids, out_scores, workspace,
+                        workspace_bytes_given, stream, iters, scan_ms, 2);
 }
 
 size_t pq_score_topk_subset_workspace_bytes(long long n_subset, int B, int m, int b, int K) {
@@ -551,8 +614,8 @@ const char* pq_strerror(int code) {
         case PQ_OK: return "ok";
         case PQ_ERR_NULL: return "a required pointer is NULL";
         case PQ_ERR_SHAPE:
-            return "bad shape: need B,d,m,b,K,N >= 1, d % m == 0, b <= 256, K <= N (K <= |V| <= N with a candidate list), "
-                   "N < 2^31";
+            return "bad shape: need B,d,m,b,K,N >= 1, d % m == 0, b <= 256 (65536 with 16-bit sub-ids), K <= N (K <= |V| <= N with a "
+                   "candidate list), N < 2^31";
         case PQ_ERR_UNSUPPORTED:
             return "unsupported: K > 512, m > 128, B > 65535, or score tables plus candidate lists exceed LDS";
         case PQ_ERR_WORKSPACE: return "workspace smaller than pq_score_topk_workspace_bytes()";

@@ -16,8 +16,9 @@ struct ScanArgs {
     uint32_t n_items;    // items in the catalogue (bounds the ids read from `subset`)
 };
 
-// Items a thread holds per round.  M > 0: m is M and one 16-byte vector carries 16/M items; M == 0: any m, one item
-// per slot, row loads sized by m's alignment.
+// Items a thread holds per round.  M > 0: an item's row of sub-ids takes M bytes (m sub-ids of one byte, or m / 2 of
+// two bytes) and one 16-byte vector carries 16/M items; M == 0: any row, one item per slot, row loads sized by the
+// row's alignment.
 template <int M>
 struct Round {
     static constexpr int kUnitsPerThread = M ? vec_per_thread(M) : kGenericItemsPerThread;   // lane-sized units of work
@@ -120,6 +121,81 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
     return acc;
 }
 
+// ---- sub-ids of two bytes (alphabets of up to 65536 sub-ids per split): tables of `stride` = b entries per split
+
+// Eq. 5 for the 8/M items packed in one 16-byte vector of 16-bit sub-ids (M = 1, 2, 4 or 8 splits).
+template <int M>
+__device__ __forceinline__ void score_vector16(const float* lut, int stride, const uint32_t* w, float* sc) {
+    float v[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+        const uint32_t code = (h & 1) ? (w[h >> 1] >> 16) : (w[h >> 1] & 0xFFFFu);
+        v[h] = lut[(h % M) * stride + code];
+    }
+    __builtin_amdgcn_sched_barrier(0);                // keep the reads ahead of the sums
+#pragma unroll
+    for (int e = 0; e < 8 / M; ++e) {
+        float acc = v[e * M];
+#pragma unroll
+        for (int k = 1; k < M; ++k) acc = acc + v[e * M + k];
+        sc[e] = acc;
+    }
+}
+
+// Eq. 5 for one item of M = 16 or 32 sub-ids of 16 bits (M/8 vectors): one left-to-right chain over all M values.
+template <int M>
+__device__ __forceinline__ float score_wide16(const float* lut, int stride, const uint32_t* w) {
+    float acc = 0.0f;
+#pragma unroll
+    for (int j = 0; j < M / 8; ++j) {
+        float v[8];
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+            const uint32_t word = w[4 * j + (h >> 1)];
+            const uint32_t code = (h & 1) ? (word >> 16) : (word & 0xFFFFu);
+            v[h] = lut[(j * 8 + h) * stride + code];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int h = 0; h < 8; ++h) acc = (j == 0 && h == 0) ? v[0] : acc + v[h];
+    }
+    return acc;
+}
+
+// Eq. 5 for one row of m 16-bit sub-ids that starts at any even address.
+__device__ float score_row16(const float* lut, int stride, const uint8_t* row, int m) {
+    float acc = 0.0f;
+    if ((m & 7) == 0) {
+        const uint4* p = reinterpret_cast<const uint4*>(row);
+        for (int v = 0; v < (m >> 3); ++v) {
+            const uint4 x = p[v];
+            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int h = 0; h < 8; ++h) {
+                const uint32_t code = (h & 1) ? (w[h >> 1] >> 16) : (w[h >> 1] & 0xFFFFu);
+                const float t = lut[(v * 8 + h) * stride + code];
+                acc = (v == 0 && h == 0) ? t : acc + t;
+            }
+        }
+    } else if ((m & 1) == 0) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(row);
+        for (int v = 0; v < (m >> 1); ++v) {
+            const uint32_t w = p[v];
+            const float t0 = lut[(2 * v) * stride + (w & 0xFFFFu)];
+            const float t1 = lut[(2 * v + 1) * stride + (w >> 16)];
+            acc = (v == 0) ? t0 : acc + t0;
+            acc = acc + t1;
+        }
+    } else {
+        const uint16_t* g = reinterpret_cast<const uint16_t*>(row);
+        for (int k = 0; k < m; ++k) {
+            const float t = lut[k * stride + g[k]];
+            acc = (k == 0) ? t : acc + t;
+        }
+    }
+    return acc;
+}
+
 // Unit (code vector, or item in the generic kernel) that thread `tid` of workgroup `blk` owns in slot u of its
 // round rr: ((rr * kUnits + u) * nblk + blk) * NT + tid.  Slot u of one round of all workgroups together is one
 // contiguous stretch of the catalogue, so the grid sweeps memory front to back.  32-bit arithmetic: there are fewer
@@ -157,19 +233,26 @@ __device__ __forceinline__ void load_round(const ScanArgs& a, uint32_t rr, int n
 // Scores of the items this thread owns in that round (slots past the catalogue's end get arbitrary finite values).
 // `inside`: the round lies wholly inside the scanned units (n_units of them); otherwise vectors past the end are not
 // looked up at all (a wave whose lanes are all past the end skips the vector's table reads).
-template <int M, int C = 1, int NT = kThreads>
-__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, uint32_t rr, int nblk, int blk, int tid,
-                                            bool inside, uint32_t n_units, const uint32_t (&w)[Round<M>::kWords],
-                                            float (&sc)[Round<M>::kItems]) {
+// M: splits (0: any, at run time); CW: bytes per sub-id; `stride`: table entries per split in LDS.
+template <int M, int C = 1, int NT = kThreads, int CW = 1>
+__device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, int stride, uint32_t rr, int nblk, int blk,
+                                            int tid, bool inside, uint32_t n_units,
+                                            const uint32_t (&w)[Round<M * CW>::kWords], float (&sc)[Round<M * CW>::kItems]) {
+    constexpr int P = M * CW;                                  // bytes of an item's row
     if constexpr (M > 0) {
 #pragma unroll
-        for (int u = 0; u < Round<M>::kUnitsPerThread; ++u) {
-            if (inside || unit_of<M, NT>(rr, u, nblk, blk, tid) < n_units) {
-                if constexpr (M > 16) sc[u] = score_wide<M>(lut, &w[4 * Round<M>::kVPU * u]);
-                else score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
+        for (int u = 0; u < Round<P>::kUnitsPerThread; ++u) {
+            if (inside || unit_of<P, NT>(rr, u, nblk, blk, tid) < n_units) {
+                if constexpr (CW == 2) {
+                    if constexpr (P > 16) sc[u] = score_wide16<M>(lut, stride, &w[4 * Round<P>::kVPU * u]);
+                    else score_vector16<M>(lut, stride, &w[4 * u], &sc[u * Round<P>::kIPV]);
+                } else {
+                    if constexpr (M > 16) sc[u] = score_wide<M>(lut, &w[4 * Round<M>::kVPU * u]);
+                    else score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
+                }
             } else {
 #pragma unroll
-                for (int e = 0; e < Round<M>::kIPV; ++e) sc[u * Round<M>::kIPV + e] = 0.0f;
+                for (int e = 0; e < Round<P>::kIPV; ++e) sc[u * Round<P>::kIPV + e] = 0.0f;
             }
         }
     } else {
@@ -183,7 +266,8 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
                     item = (uint32_t)a.subset[unit];
                     item = item < a.n_items ? item : a.n_items - 1;
                 }
-                v = score_row(lut, a.codes + (size_t)item * a.m, a.m);
+                if constexpr (CW == 2) v = score_row16(lut, stride, a.codes + (size_t)item * a.m * 2, a.m);
+                else v = score_row(lut, a.codes + (size_t)item * a.m, a.m);
             }
             sc[u] = v;
         }
@@ -202,26 +286,32 @@ __device__ __forceinline__ uint32_t item_of_slot(uint32_t rr, int nblk, int blk,
 // constant, which lets sub-id extraction and address arithmetic fold into one instruction per lookup); the rest is
 // dynamic: [tables if M == 0] | hist | ctl | wave lists | cand | sorted.
 // C > 1 (long single-query scans): C copies of the tables, in dynamic LDS, cut the bank conflicts of the lookups.
-template <int M, int C = 1, int NT = kThreads>
+// CW: bytes per sub-id.  CW = 2 (alphabets of up to 65536 sub-ids per split): rows of m 16-bit sub-ids, the m x b
+// table in dynamic LDS as it lies in memory (b entries per split); the vector instances are those whose rows take
+// 8, 16 or 32 bytes (m = 4, 8, 16).
+template <int M, int C = 1, int NT = kThreads, int CW = 1>
 __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     constexpr int NW = NT / kWave;
-    static_assert(C == 1 || M > 0, "replicated tables need a compile-time m");
-    __shared__ __align__(16) float lut_static[(M && C == 1) ? M * kLutStride : 4];
+    constexpr int P = M * CW;                                  // bytes of an item's row (0: known at run time only)
+    constexpr bool kStaticLut = M && C == 1 && CW == 1;
+    static_assert(C == 1 || (M > 0 && CW == 1), "replicated tables need a compile-time m and one-byte sub-ids");
+    __shared__ __align__(16) float lut_static[kStaticLut ? M * kLutStride : 4];
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = M ? M : a.m;
-    const ScanLds L = carve_scan(smem, (M && C == 1) ? 0 : (size_t)m * kLutStride * C, a.cap, a.candmax, NW);
-    float* const lut_base = (M && C == 1) ? lut_static : L.lut;
-    Ctl* ctl = L.ctl;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q = blockIdx.y, nblk = gridDim.x, K = a.K, b = a.b;
-    constexpr int kItems = Round<M>::kItems;
-    constexpr int kUnits = Round<M>::kUnitsPerThread;
-    constexpr int kWords = Round<M>::kWords;
+    const int stride = CW == 1 ? kLutStride : b;               // table entries per split in LDS
+    const ScanLds L = carve_scan(smem, kStaticLut ? 0 : (size_t)m * stride * C, a.cap, a.candmax, NW);
+    float* const lut_base = kStaticLut ? lut_static : L.lut;
+    Ctl* ctl = L.ctl;
+    constexpr int kItems = Round<P>::kItems;
+    constexpr int kUnits = Round<P>::kUnitsPerThread;
+    constexpr int kWords = Round<P>::kWords;
 
     // Vector kernels scan the code vectors that lie wholly inside the catalogue; the fewer than 16 / M items after
     // them (when N * M is not a multiple of 16) are scored one by one at the end.  The generic kernel scans items.
-    const uint32_t total_units = (uint32_t)((M && M <= 16) ? (a.N * M) / 16 : a.N);
-    const uint32_t n_scan = M ? total_units * Round<M>::kIPV : total_units;   // items the rounds cover
+    const uint32_t total_units = (uint32_t)((P && P <= 16) ? (a.N * P) / 16 : a.N);
+    const uint32_t n_scan = M ? total_units * Round<P>::kIPV : total_units;   // items the rounds cover
     const uint32_t last_vec = total_units - 1;                                // (total_units >= 1: the host sees to it)
     const uint32_t round_units = (uint32_t)NT * kUnits * nblk;                // units all workgroups take per round
     const uint32_t rounds = (total_units + round_units - 1) / round_units;    // every workgroup runs them all
@@ -237,7 +327,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     const uint32_t own_vec = (uint32_t)(blk * NW + wave) * 4u;
     const uint32_t spare_vec = own_vec < last_vec ? own_vec : last_vec;
     auto fetch = [&](uint32_t rr, int vt, uint32_t (&buf)[kWords]) {
-        load_round<M, NT>(a, rr, nblk, blk, last_vec, spare_vec, vt, buf);
+        load_round<P, NT>(a, rr, nblk, blk, last_vec, spare_vec, vt, buf);
     };
     // (the host sends catalogues with no whole code vector, N * M < 16, to the generic kernel: rounds >= 1 here)
     auto fetch_first = [&]() {                                // no branch: the loads can be counted, so what follows
@@ -245,7 +335,20 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         for (int i = 0; i < kRing; ++i) fetch(r + i, tid, w[i]);
     };
     const float* Sq = a.S + (size_t)q * m * b;
-    if constexpr (C > 1) {
+    if constexpr (CW == 2) {
+        // the query's m x b table as it lies in memory, in 16-byte pieces when its size and address allow
+        const int total = m * b;
+        fetch_first();
+        if ((total & 3) == 0 && ((uintptr_t)Sq & 15) == 0) {
+            const float4* src = reinterpret_cast<const float4*>(Sq);
+            float4* dst = reinterpret_cast<float4*>(lut_base);
+#pragma unroll 4
+            for (int e = tid; e < (total >> 2); e += NT) dst[e] = src[e];
+        } else {
+#pragma unroll 4
+            for (int e = tid; e < total; e += NT) lut_base[e] = Sq[e];
+        }
+    } else if constexpr (C > 1) {
         // thread t writes the 16-byte pieces t, t + NT, ... of the replicated tables (piece p is a quarter of the C
         // copies of entry p / (C / 4)): consecutive lanes write consecutive LDS addresses.  Values requested first.
         constexpr int kPieces = M * kLutStride * (C / 4);
@@ -330,7 +433,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         const bool inside = rr < inside_rounds;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const uint32_t item = item_of_slot<M, NT>(rr, nblk, blk, vt, e);
+            const uint32_t item = item_of_slot<P, NT>(rr, nblk, blk, vt, e);
             const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
             if (mask != 0) top.append(mask, take, sc[e], take ? id_of(item) : 0u, lane);
@@ -340,25 +443,25 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     // one streamed round
     auto process = [&](const uint32_t (&w)[kWords], uint32_t rr, int vt) {
         float sc[kItems];
-        score_round<M, C, NT>(a, lut, rr, nblk, blk, vt, rr < inside_rounds, total_units, w, sc);
+        score_round<M, C, NT, CW>(a, lut, stride, rr, nblk, blk, vt, rr < inside_rounds, total_units, w, sc);
         offer(sc, rr, vt);
     };
 
     {
         // ---- 2. first round: scores in registers, histogram over their range, cut
         float sc[kItems];
-        score_round<M, C, NT>(a, lut, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
+        score_round<M, C, NT, CW>(a, lut, stride, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
-            if (item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
+            if (item_of_slot<P, NT>(r, nblk, blk, tid, e) < n_scan) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
         float lo, scale;
         set_range<NW>(mn, mx, ctl, tid, lo, scale);
         int bk[kItems];
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
             bk[e] = bucket_of(sc[e], lo, scale);
-            if (item_of_slot<M, NT>(r, nblk, blk, tid, e) < n_scan) atomicAdd(&L.hist[bk[e]], 1u);
+            if (item_of_slot<P, NT>(r, nblk, blk, tid, e) < n_scan) atomicAdd(&L.hist[bk[e]], 1u);
         }
         __syncthreads();
         if (tid < kWave) find_cut(L.hist, K, ctl, lane);
@@ -367,7 +470,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const uint32_t item = item_of_slot<M, NT>(r, nblk, blk, tid, e);
+            const uint32_t item = item_of_slot<P, NT>(r, nblk, blk, tid, e);
             const bool take = item < n_scan && bk[e] >= bstar;
             const uint64_t mask = __ballot(take);
             if (mask != 0) top.append(mask, take, sc[e], take ? id_of(item) : 0u, lane);
@@ -408,17 +511,24 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             }
         }
     }
-    if constexpr (M > 0 && M <= 16) {
-        // the fewer than 16 / M items after the last whole code vector, one per lane of one wave
+    if constexpr (P > 0 && P <= 16) {
+        // the fewer than 16 / P items after the last whole code vector, one per lane of one wave
         if (blockIdx.x == 0 && wave == 0) {
             const uint32_t item = n_scan + lane;
             float sc = 0.0f;
             bool take = false;
             if (item < (uint32_t)a.N) {
-                const uint8_t* row = a.codes + (size_t)item * M;
-                sc = lut[(size_t)row[0] * C];
+                const uint8_t* row = a.codes + (size_t)item * P;
+                if constexpr (CW == 2) {
+                    const uint16_t* g = reinterpret_cast<const uint16_t*>(row);
+                    sc = lut[g[0]];
 #pragma unroll
-                for (int k = 1; k < M; ++k) sc = sc + lut[((size_t)k * kLutStride + row[k]) * C];
+                    for (int k = 1; k < M; ++k) sc = sc + lut[(size_t)k * stride + g[k]];
+                } else {
+                    sc = lut[(size_t)row[0] * C];
+#pragma unroll
+                    for (int k = 1; k < M; ++k) sc = sc + lut[((size_t)k * kLutStride + row[k]) * C];
+                }
                 take = sc >= top.floor_ge;
             }
             const uint64_t mask = __ballot(take);

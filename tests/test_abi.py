@@ -21,6 +21,10 @@ def lib(pqlib_path):
     L.pq_score_topk_workspace_bytes.restype = SZ
     L.pq_score_topk.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
     L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, P]
+    L.pq_score_topk_u16_workspace_bytes.argtypes = [LL, I, I, I, I]
+    L.pq_score_topk_u16_workspace_bytes.restype = SZ
+    L.pq_score_topk_u16.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
+    L.pq_score_topk_u16_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, P]
     L.pq_score_topk_subset_workspace_bytes.argtypes = [LL, I, I, I, I]
     L.pq_score_topk_subset_workspace_bytes.restype = SZ
     L.pq_score_topk_subset.argtypes = [P, P, P, LL, LL, I, I, I, I, P, P, P, SZ, P]
@@ -89,7 +93,7 @@ def test_subitem_scores_argument_errors(lib):
     assert f(p, p, p, 1, 0, 4, 256, None) == SHAPE
     assert f(p, p, p, 1, 64, 0, 256, None) == SHAPE
     assert f(p, p, p, 1, 64, 4, 0, None) == SHAPE
-    assert f(p, p, p, 1, 64, 4, 257, None) == SHAPE
+    assert f(p, p, p, 1, 64, 4, 65537, None) == SHAPE        # (Eq. 4 itself serves alphabets of up to 65536 sub-ids)
     assert f(p, p, p, 1, 66, 4, 256, None) == SHAPE          # d % m != 0
     assert f(p, p, p, 65536, 64, 4, 256, None) == UNSUPPORTED
     assert f(p + 2, p, p, 1, 64, 4, 256, None) == ALIGN
@@ -122,6 +126,36 @@ def test_score_topk_argument_errors(lib):
     out = ctypes.c_float(0)
     assert g(p, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 0, ctypes.addressof(out)) == SHAPE
     assert g(None, p, 1000, 1, 8, 256, 10, p, p, p, big, None, 3, ctypes.addressof(out)) == NULL
+
+
+def test_score_topk_u16_argument_errors(lib):
+    f = lib.pq_score_topk_u16
+    ws = lib.pq_score_topk_u16_workspace_bytes
+    p = 0x10000
+    big = 1 << 30
+    good = dict(codes=p, S=p, N=100000, B=1, m=8, b=1024, K=10, ids=p, sc=p, ws=p, wsb=big, st=None)
+
+    def call(**kw):
+        a = dict(good, **kw)
+        return f(a["codes"], a["S"], a["N"], a["B"], a["m"], a["b"], a["K"], a["ids"], a["sc"], a["ws"], a["wsb"],
+                 a["st"])
+
+    for name in ("codes", "S", "ids", "sc", "ws"):
+        assert call(**{name: None}) == NULL, name
+    assert call(N=0) == SHAPE and call(B=0) == SHAPE and call(m=0) == SHAPE and call(b=0) == SHAPE and call(K=0) == SHAPE
+    assert call(b=65537) == SHAPE and call(K=100001) == SHAPE and call(N=2 ** 31) == SHAPE
+    assert call(K=513) == UNSUPPORTED and call(m=129) == UNSUPPORTED and call(B=65536) == UNSUPPORTED
+    # the whole m x b table has to fit LDS next to the candidate lists
+    assert call(m=8, b=8192) == UNSUPPORTED and call(m=2, b=65536) == UNSUPPORTED and call(m=64, b=1024) == UNSUPPORTED
+    assert ws(100000, 1, 8, 8192, 10) == 0 and ws(100000, 1, 8, 65537, 10) == 0
+    assert ws(100000, 1, 8, 4096, 10) > 0 and ws(100000, 1, 1, 32768, 10) > 0 and ws(100000, 3, 5, 300, 100) > 0
+    assert call(codes=p + 8) == ALIGN and call(ws=p + 4) == ALIGN and call(S=p + 1) == ALIGN
+    assert call(wsb=ws(100000, 1, 8, 1024, 10) - 1) == WORKSPACE
+    g = lib.pq_score_topk_u16_profile
+    out = ctypes.c_float(0)
+    assert g(p, p, 1000, 1, 8, 1024, 10, p, p, p, big, None, 3, None) == NULL
+    assert g(p, p, 1000, 1, 8, 1024, 10, p, p, p, big, None, 0, ctypes.addressof(out)) == SHAPE
+    assert g(p, p, 1000, 1, 8, 65537, 10, p, p, p, big, None, 3, ctypes.addressof(out)) == SHAPE
 
 
 def test_score_topk_subset_argument_errors(lib):

@@ -313,6 +313,125 @@ def test_errors_reach_python(pq):
     assert e.value.code == pq.PQ_ERR_WORKSPACE
 
 
+# ---------------------------------------------------------------- Algorithm 1 over 16-bit sub-ids (b up to 65536)
+
+def tables(seed, B, m, b):
+    return W.normal_f32(W.stream_key(seed, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+
+
+def assert_same_topk_u16(pq, oracle, G, S, K, tag=""):
+    print(f"case u16 {tag} N={G.shape[0]} m={G.shape[1]} B={S.shape[0]} b={S.shape[2]} K={K}", flush=True)
+    assert G.dtype == np.uint16
+    ids, sc = pq.pq_score_topk_u16(dev(G), dev(S), K)
+    torch.cuda.synchronize()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    rid, rsc = oracle.score_topk_u16(G, S, K)
+    assert np.array_equal(ids, rid), tag
+    check_scores(sc, rsc)
+    assert np.array_equal(sc.view(np.uint32), rsc.view(np.uint32)), tag
+    return ids, sc
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 12, 16, 24])
+def test_u16_small_shapes(pq, oracle, m):
+    for N in (1, 2, 3, 5, 63, 64, 65, 1000, 4099, 70_001):
+        for b in (257, 1000):
+            for B in (1, 3):
+                G = W.codes_uniform_u16(N, m, b, seed=N + m)
+                S = tables(N + m, B, m, b)
+                for K in sorted({1, min(N, 10), min(N, 100)}):
+                    assert_same_topk_u16(pq, oracle, G, S, K, "small")
+
+
+@pytest.mark.parametrize("N,m,b,B,K", [(3_000_001, 8, 1024, 1, 10), (2_000_003, 4, 4096, 2, 10), (1_500_001, 4, 8192, 1, 100),
+                                       (1_000_001, 16, 2048, 1, 10), (2_000_001, 8, 4096, 1, 10), (700_001, 5, 6000, 2, 10),
+                                       (900_001, 16, 300, 3, 100), (5_000_001, 2, 16384, 1, 10), (3_000_001, 1, 32768, 1, 10),
+                                       (400_001, 8, 1000, 64, 10), (300_001, 8, 600, 1, 512), (1_000_001, 3, 257, 1, 10),
+                                       (200_001, 32, 1024, 2, 10), (20_000_001, 8, 1024, 1, 10)])
+def test_u16_long_scans(pq, oracle, N, m, b, B, K):
+    # many rounds per workgroup; tables from 5 KB to 128 KB (the larger ones run 1024-thread workgroups); vector rows
+    # (m = 4, 8, 16) and row-by-row ones; sub-ids up to b - 1 are present
+    G = W.codes_uniform_u16(N, m, b, seed=N % 1000 + m)
+    G[N // 2] = b - 1
+    assert_same_topk_u16(pq, oracle, G, tables(N % 1000 + b, B, m, b), K, "long")
+
+
+def test_u16_with_byte_sized_sub_ids_equals_the_uint8_path(pq, oracle):
+    for (N, m, B, K) in ((100_003, 8, 2, 10), (50_001, 4, 1, 100), (30_001, 16, 1, 10), (20_001, 3, 2, 10)):
+        G8 = W.codes_uniform(N, m, 256, seed=N)
+        S = tables(N, B, m, 256)
+        ids, sc = assert_same_topk_u16(pq, oracle, G8.astype(np.uint16), S, K, "bytes")
+        ids8, sc8 = run_topk(pq, G8, S, K)
+        assert np.array_equal(ids, ids8) and np.array_equal(sc.view(np.uint32), sc8.view(np.uint32))
+
+
+def test_u16_high_byte_selects_the_table_entry(pq, oracle):
+    # score == item id exactly, spelled in base 1000 over three splits: any sub-id read modulo 256 breaks the order
+    N, m, b = 400_000, 4, 1000
+    i = np.arange(N, dtype=np.int64)
+    G = np.stack([i % 1000, (i // 1000) % 1000, np.zeros(N, dtype=np.int64), (i * 7) % 1000], axis=1).astype(np.uint16)
+    S = np.zeros((1, m, b), dtype=np.float32)
+    S[0, 0] = np.arange(b)
+    S[0, 1] = np.arange(b) * 1000.0
+    ids, sc = assert_same_topk_u16(pq, oracle, G, S, 100, "digits")
+    assert ids[0].tolist() == list(range(N - 1, N - 101, -1)) and sc[0].tolist() == [float(x) for x in range(N - 1, N - 101, -1)]
+
+
+def test_u16_ties(pq, oracle):
+    N, m, b, K = 200_000, 8, 700, 20
+    G = np.full((N, m), 699, dtype=np.uint16)
+    S = tables(7, 1, m, b)
+    ids, _ = assert_same_topk_u16(pq, oracle, G, S, K, "all-equal")
+    assert ids[0].tolist() == list(range(K))
+    # K + 3 copies of the best row at seeded ids: the K lowest of them, in id order
+    G = W.codes_uniform_u16(N, m, b, seed=11)
+    planted = W.plant_ids(N, K + 3, seed=2)
+    G[planted] = S[0].argmax(axis=1).astype(np.uint16)
+    ids, _ = assert_same_topk_u16(pq, oracle, G, S, K, "straddle")
+    assert ids[0].tolist() == planted[:K].tolist()
+    # coarse tables: heavy ties everywhere
+    Sc = (np.round(tables(9, 2, 4, 300) * 2) / 2).astype(np.float32)
+    assert_same_topk_u16(pq, oracle, W.codes_uniform_u16(300_000, 4, 300, seed=5), Sc, 100, "coarse")
+
+
+@pytest.mark.parametrize("N,m,b,B", [(100_000, 8, 1000, 1), (100_000, 3, 257, 2), (60_000, 4, 4096, 1)])
+def test_u16_tables_that_are_only_four_byte_aligned(pq, oracle, N, m, b, B):
+    G = W.codes_uniform_u16(N, m, b, seed=m)
+    S = tables(N + m, B, m, b)
+    flat = torch.empty(S.size + 1, dtype=torch.float32, device="cuda")
+    Sd = flat[1:].view(B, m, b)
+    Sd.copy_(torch.from_numpy(S))
+    assert Sd.data_ptr() % 16 == 4 and Sd.is_contiguous()
+    ids, sc = pq.pq_score_topk_u16(dev(G), Sd, 10)
+    torch.cuda.synchronize()
+    rid, rsc = oracle.score_topk_u16(G, S, 10)
+    assert np.array_equal(ids.cpu().numpy(), rid)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), rsc.view(np.uint32))
+
+
+def test_u16_from_embeddings(pq, oracle):
+    # the whole path with an alphabet of 1024 sub-ids per split: Eq. 4 on the GPU, then the scan
+    N, d, m, b, B, K = 500_000, 512, 8, 1024, 3, 10
+    cent, Q = W.centroids(m, b, d, seed=3), W.queries(B, d, seed=3)
+    G = W.codes_uniform_u16(N, m, b, seed=3)
+    Sd = pq.pq_subitem_scores(dev(Q), dev(cent))
+    S = Sd.cpu().numpy()
+    assert np.array_equal(S.view(np.uint32), oracle.subitem_scores(Q, cent).view(np.uint32))
+    assert_same_topk_u16(pq, oracle, G, S, K, "embeddings")
+
+
+def test_u16_errors_reach_python(pq):
+    G = dev(W.codes_uniform_u16(1000, 8, 300))
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_score_topk_u16(G, dev(np.zeros((1, 8, 8192), dtype=np.float32)), 10)      # 256 KB of tables
+    assert e.value.code == pq.PQ_ERR_UNSUPPORTED
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_score_topk_u16(G, dev(np.zeros((1, 8, 300), dtype=np.float32)), 1001)
+    assert e.value.code == pq.PQ_ERR_SHAPE
+    with pytest.raises(ValueError):
+        pq.pq_score_topk_u16(dev(W.codes_uniform(1000, 8)), dev(np.zeros((1, 8, 300), dtype=np.float32)), 10)   # uint8 codes
+
+
 # ---------------------------------------------------------------- Algorithm 1 with a candidate list V
 
 def assert_same_subset_topk(pq, oracle, G, S, V, K, tag=""):
