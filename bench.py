@@ -235,6 +235,66 @@ def subset_mode(args):
         "subset": points}))
 
 
+def wide_mode(args):
+    """Codebooks with 16-bit sub-ids (pq_score_topk_u16): alphabets of 1024 to 8192 sub-ids per split, batch 1, K = 10,
+    catalogues from the headline size up to 5*10^7 items.  Per point: whole-step time (Eq. 4 + Eq. 5 + TopK), the scan
+    kernel's duration and its share of the HBM roofline over the 2*N*m bytes of codes; results are checked against the
+    oracle where the code matrix is at most --sweep-check-bytes."""
+    import numpy as np
+    import torch
+    from paper_2408_09992_amd import binding as pq, workloads as W
+    from oracle import pq_oracle
+
+    d, K, B = 512, 10, 1
+    points = []
+    for (m, b) in ((8, 1024), (8, 4096), (4, 8192), (16, 2048), (12, 1024)):
+        cent = W.centroids(m, b, d if d % m == 0 else 32 * m, seed=m + b)
+        Q = W.queries(B, cent.shape[0] * cent.shape[2], seed=m + b)
+        Cd, Qd = torch.from_numpy(cent).cuda(), torch.from_numpy(Q).cuda()
+        for N in (1_280_000, 10_000_000, 50_000_000):
+            if 2 * N * m > args.sweep_max_bytes:
+                continue
+            Gd = W.codes_uniform_u16_device(N, m, b, seed=N % 1000 + m)
+            sub = pq.PreparedSubitemScores(Qd, Cd)
+            top = pq.PreparedScoreTopKU16(Gd, sub.S, K)
+            for _ in range(3):
+                sub(); top()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            sub(); top()
+            torch.cuda.synchronize()
+            once = time.perf_counter() - t0
+            steps = int(max(5, min(2000, 0.25 / max(once, 1e-6))))
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                sub(); top()
+            torch.cuda.synchronize()
+            el = (time.perf_counter() - t0) / steps
+            scan_ms = pq.pq_score_topk_u16_profile(Gd, sub.S, K, max(3, min(50, steps)), workspace=top.workspace)
+            parity = None
+            if 2 * N * m <= args.sweep_check_bytes:
+                rid, rsc = pq_oracle.score_topk_u16(Gd.cpu().numpy(), sub.S.cpu().numpy(), K)
+                parity = bool(np.array_equal(top.ids.cpu().numpy(), rid) and
+                              np.array_equal(top.scores.cpu().numpy().view(np.uint32), rsc.view(np.uint32)))
+            gbs = 2 * N * m / (scan_ms * 1e-3) / 1e9
+            pt = {"N": N, "m": m, "b": b, "us_per_step": el * 1e6, "items_per_s": N / el, "scan_kernel_us": scan_ms * 1e3,
+                  "scan_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS, "parity_vs_oracle": parity}
+            points.append(pt)
+            print(f"m={m:2d} b={b:5d} N={N:>10d}  step {el * 1e6:9.1f} us  {N / el / 1e9:7.3f} Gitem/s  scan {scan_ms * 1e3:9.1f} us "
+                  f"{gbs:7.0f} GB/s ({100 * gbs / HBM_PEAK_GBS:4.1f} % of HBM peak)  parity {parity}", file=sys.stderr,
+                  flush=True)
+            del sub, top, Gd
+            torch.cuda.empty_cache()
+    best = max(points, key=lambda p: p["items_per_s"])
+    print(json.dumps({
+        "metric": "items scored/sec (PQTopK over 16-bit sub-ids, whole path incl. top-K)", "value": best["items_per_s"],
+        "unit": "items/s", "n_gpus": 1, "higher_is_better": True, "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "config": {"workload": f"16-bit sub-ids: K={K} batch={B}, (m, b) in (8, 1024), (8, 4096), (4, 8192), "
+                                                    "(16, 2048), (12, 1024), N = 1.28M, 10^7, 5*10^7, uniform codes drawn on "
+                                                    "the device"},
+        "wide": points}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -255,6 +315,8 @@ def main():
                     "(Algorithm 2 and the default matrix-vector product) on --config at batch 1")
     ap.add_argument("--subset", action="store_true", help="time candidate-list scoring (pq_score_topk_subset) over "
                     "list sizes on --config at batch 1")
+    ap.add_argument("--wide", action="store_true", help="time codebooks with 16-bit sub-ids (pq_score_topk_u16) over "
+                    "alphabet and catalogue sizes at batch 1")
     ap.add_argument("--sweep-max-bytes", type=float, default=16e9, help="largest code matrix the sweep allocates")
     ap.add_argument("--sweep-check-bytes", type=float, default=1e9,
                     help="largest code matrix whose result the sweep checks against the oracle")
@@ -270,6 +332,9 @@ def main():
         return
     if args.subset:
         subset_mode(args)
+        return
+    if args.wide:
+        wide_mode(args)
         return
 
     import numpy as np

@@ -225,6 +225,19 @@ def codes_uniform_device(N: int, m: int, b: int = 256, seed: int = 0):
     return torch.randint(0, b, (N, m), dtype=torch.uint8, device="cuda", generator=g)
 
 
+def codes_uniform_u16_device(N: int, m: int, b: int, seed: int = 0):
+    """codes_uniform_device() for alphabets of up to 65536 sub-ids: a uint16 [N][m] device tensor."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    out = torch.empty((N, m), dtype=torch.uint16, device="cuda")
+    step = max(1, (1 << 26) // m)                              # drawn in slices: the int32 staging stays small
+    for lo in range(0, N, step):
+        n = min(step, N - lo)
+        out[lo:lo + n] = torch.randint(0, b, (n, m), dtype=torch.int32, device="cuda", generator=g).to(torch.uint16)
+    return out
+
+
 def plant_rows(codes: np.ndarray, ids: np.ndarray, row: np.ndarray) -> np.ndarray:
     """Overwrite the code rows of `ids` with `row` (in place); the caller decides which row to plant."""
     codes[np.asarray(ids, dtype=np.int64)] = np.asarray(row, dtype=np.uint8)[None, :]
