@@ -155,11 +155,22 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
             const long long tiles = (B + kQ - 1) / kQ;
             const long long t_round = (long long)kThreads * kTileVecs;
             const long long t_rounds = (units + t_round - 1) / t_round;
-            long long want = ((long long)kAssumedCUs) / tiles;
-            if (want < 1) want = 1;                           // enough tiles to fill the machine: one workgroup each
-            long long nb = t_rounds < want ? t_rounds : want;
-            if (nb >= 8) nb &= ~7LL;                          // every tile's item block x lands on XCD x % 8
-            if (nb < 1) nb = 1;
+            // Item blocks per tile: as many as fill the CUs once, or twice or three times over when a single filling
+            // would leave many CUs idle (96 tiles: 2 blocks = 192 workgroups, 5 blocks = 480).  The LDS is the bound, so
+            // L workgroups on a CU take L times a workgroup's streaming time, plus fixed costs per workgroup (tables,
+            // first-round cuts, final merge; measured: 28 us, and 20 + 0.75 K us for every further workgroup on the CU;
+            // streaming: 1.3 ns per code vector and tile).
+            const double stream_us = 1.3e-3 * (double)units;
+            double best_us = 0.0;
+            long long nb = 1;
+            for (int fill = 1; fill <= 3; ++fill) {
+                long long cand = ((long long)kAssumedCUs * fill) / tiles;
+                if (cand > t_rounds) cand = t_rounds;
+                if (cand < 1) cand = 1;
+                const long long per_cu = (tiles * cand + kAssumedCUs - 1) / kAssumedCUs;   // workgroups on the busiest CU
+                const double us = (double)per_cu * stream_us / (double)cand + 28.0 + (20.0 + 0.75 * K) * (double)(per_cu - 1);
+                if (fill == 1 || us < best_us) { best_us = us; nb = cand; }
+            }
             p.nblk = (int)nb;
         }
     }

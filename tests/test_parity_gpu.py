@@ -140,10 +140,13 @@ def test_score_topk_wide_items(pq, oracle, N, m, B, K):
 
 @pytest.mark.parametrize("N,m,B,K,b", [(700_001, 8, 64, 10, 256), (700_002, 8, 65, 1, 256), (700_003, 8, 66, 100, 256),
                                        (350_001, 16, 67, 10, 256), (350_000, 16, 64, 512, 256),
-                                       (1_400_000, 8, 33, 300, 256), (700_005, 8, 64, 10, 16), (2_000_003, 16, 13, 28, 256)])
+                                       (1_400_000, 8, 33, 300, 256), (700_005, 8, 64, 10, 16), (2_000_003, 16, 13, 28, 256),
+                                       (300_007, 8, 48, 10, 256), (300_009, 8, 96, 10, 256), (200_003, 8, 384, 10, 256),
+                                       (200_005, 8, 383, 100, 256), (150_001, 16, 1100, 10, 256)])
 def test_score_topk_batched_kernel_shapes(pq, oracle, N, m, B, K, b):
     # B * N * m is large enough for the four-queries-per-workgroup kernel: ragged ends of the catalogue, partly filled
-    # tiles, the K range and a short code alphabet
+    # tiles, the K range, a short code alphabet, and batches whose tiles share the CUs unevenly (21, 10 or 5 item
+    # blocks per tile; more tiles than CUs)
     G = W.codes_uniform(N, m, b, seed=B)
     S = W.normal_f32(W.stream_key(N + B, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
     assert_same_topk(pq, oracle, G, S, K, "batched")
