@@ -60,6 +60,15 @@ int next_pow2(int x) {
     return p;
 }
 
+// Keys per wave list: a power of two (the overflow path sorts it) with room for K kept keys plus a wave's worth of
+// new ones, and at least K / 4: a list that holds K of its `cap` keys for good is sorted every cap - K appends
+// (K = 448 in 512 slots sorted every 64 keys: twice as slow as K = 449 in 1024).
+int list_capacity(int K) {
+    const int spare = K / 4 > kWave ? K / 4 : kWave;
+    const int cap = next_pow2(K + spare);
+    return cap < 128 ? 128 : cap;
+}
+
 struct ScanPlan {
     int copies;      // single-query kernel: copies of the score tables in LDS (1 or kTableCopies)
     bool tiled;      // batched kernel: kQ queries per workgroup
@@ -97,8 +106,7 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     if (nblk < 1) nblk = 1;
     if (B > 1 && nblk >= 32) nblk &= ~7LL;                     // same item block of every query on the same XCD
     p.nblk = (int)nblk;
-    p.cap = next_pow2(K + kWave);
-    if (p.cap < 128) p.cap = 128;
+    p.cap = list_capacity(K);
     p.candmax = next_pow2(2 * K);
     if (p.candmax < 512) p.candmax = 512;
     p.stage_keys = next_pow2(2 * K);
@@ -527,8 +535,7 @@ ScanPlan make_topk_scores_plan(long long N, int B, int K) {
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;
     if (most < 8) most = 8;
     p.nblk = (int)(rounds < most ? rounds : most);
-    p.cap = next_pow2(K + kWave);
-    if (p.cap < 128) p.cap = 128;
+    p.cap = list_capacity(K);
     p.candmax = next_pow2(2 * K);
     if (p.candmax < 512) p.candmax = 512;
     p.stage_keys = next_pow2(2 * K);
