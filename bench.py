@@ -401,6 +401,10 @@ def main():
     pq.pq_read_bandwidth_profile(Gd, args.profile_iters)
     read_ms = sorted(pq.pq_read_bandwidth_profile(Gd, args.profile_iters) for _ in range(5))[2]
     read_gbs = algo_bytes / (read_ms * 1e-3) / 1e9
+    # ... and on 16 bytes: what one launch costs on this machine when it has nothing to do (back-to-back launches)
+    tiny = Gd.view(-1)[:16]
+    pq.pq_read_bandwidth_profile(tiny, 200)
+    floor_us = sorted(pq.pq_read_bandwidth_profile(tiny, 200) for _ in range(5))[2] * 1e3
 
     # stage times (HIP events on the stream the kernels run on, back-to-back launches of one stage)
     def stage_us(fn, iters=200):
@@ -452,7 +456,8 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(workload),
                      "kernel": "catalogue scan (Eq. 5 + per-workgroup top-K)", "kernel_ms": scan_ms,
                      "algorithmic_bytes_per_launch": algo_bytes,
-                     "read_kernel_GBps": read_gbs, "frac_of_read_kernel": achieved / read_gbs},
+                     "read_kernel_GBps": read_gbs, "frac_of_read_kernel": achieved / read_gbs,
+                     "empty_launch_us": floor_us},
         "stage_us": {"pq_subitem_scores": t_sub, "pq_score_topk": t_top, "scan_kernel": scan_ms * 1e3},
         "latency_us": {"what": "one step at a time, host enqueue to completion", "median": float(np.median(lat)),
                        "mean": float(lat.mean()), "p99": float(np.percentile(lat, 99)),
