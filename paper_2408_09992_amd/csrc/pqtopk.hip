@@ -87,6 +87,31 @@ bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 ||
 
 bool is_vec_m16(int m) { return m == 4 || m == 8 || m == 16; }   // 16-bit sub-ids: rows of 8, 16 or 32 bytes
 
+// With a multiple of 8 blocks per query, block x of every query runs on XCD x % 8 and the queries share that XCD's L2
+// (worth about 5 %): taken when it costs at most a sixteenth of the blocks.
+long long xcd_aligned(long long nb, int B) {
+    return (B > 1 && (nb & 7) * 16 <= nb) ? (nb & ~7LL) : nb;
+}
+
+// Item blocks per query when B single-query scans run side by side on `slots` workgroup slots (CUs times resident
+// workgroups) and B is too large for eight blocks each: as many as fill the slots once, or a few times over when one
+// filling would leave many idle.  Cost of a choice: (fillings) x (a block's share of the query's streaming time, which
+// the table lookups bound at 9.1 per clock and CU, plus some 8 us per workgroup for tables, first cut and selection).
+long long blocks_for_many_queries(long long slots, long long B, long long rounds, double lookups_per_query) {
+    const double stream_us = lookups_per_query / (9.1 * 2400.0);
+    long long best_nb = 1;
+    double best_us = 0.0;
+    for (int fill = 1; fill <= 8; ++fill) {
+        long long nb = slots * fill / B;
+        if (nb > rounds) nb = rounds;
+        if (nb < 1) nb = 1;
+        const long long fillings = (B * nb + slots - 1) / slots;
+        const double us = (double)fillings * (stream_us / (double)nb + 8.0);
+        if (fill == 1 || us < best_us) { best_us = us; best_nb = nb; }
+    }
+    return best_nb;
+}
+
 // `generic`: plan for the generic kernel whatever m is (candidate-list scans use it: their rows are gathered)
 // `cw`, `b`: bytes per sub-id (1 or 2) and, for two-byte sub-ids, the alphabet size (it sizes the tables in LDS)
 ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int cw = 1, int b = kLutStride) {
@@ -97,14 +122,15 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     const long long units = (p.vec && row <= 16) ? (N * row) / 16 : N;   // whole code vectors (the few items after them are extra)
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(row) : kGenericItemsPerThread);
     long long rounds = (units + per_round - 1) / per_round;
+    const double lookups = (double)N * m;                           // table lookups of one query's scan
     long long most = (kBlocksPerCU * (long long)kAssumedCUs) / B;   // workgroups over the whole grid
-    if (most < 8) most = 8;
+    if (most < 8) most = blocks_for_many_queries(kBlocksPerCU * (long long)kAssumedCUs, B, rounds, lookups);
     long long nblk = rounds < most ? rounds : most;
     long long one_per_cu = kAssumedCUs / B;                    // a short scan is spread evenly: one workgroup per CU, which
     if (one_per_cu < 8) one_per_cu = 8;                        // then takes two or three (possibly ragged) rounds
     if (rounds > one_per_cu && rounds <= most) nblk = one_per_cu;
     if (nblk < 1) nblk = 1;
-    if (B > 1 && nblk >= 32) nblk &= ~7LL;                     // same item block of every query on the same XCD
+    nblk = xcd_aligned(nblk, B);
     p.nblk = (int)nblk;
     p.cap = list_capacity(K);
     p.candmax = next_pow2(2 * K);
@@ -134,13 +160,13 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     if (!p.vec || m == 64 || cw == 2) {
         const size_t small = scan_lds_bytes(lut_floats, p.cap, p.candmax, K, kWaves);
         const size_t big = scan_lds_bytes(lut_floats, p.cap, p.candmax, K, kMaxWaves);
+        const long long big_round = (long long)kBigThreads * (p.vec ? vec_per_thread(row) : kGenericItemsPerThread);
+        const long long big_rounds = (units + big_round - 1) / big_round;
         long long nb = kAssumedCUs / B;
-        if (nb < 8) nb = 8;
+        if (nb < 8) nb = blocks_for_many_queries(kAssumedCUs, B, big_rounds, lookups);
         if (2 * small > kMaxLdsBytes && big <= kMaxLdsBytes && rounds > nb) {
-            const long long big_round = (long long)kBigThreads * (p.vec ? vec_per_thread(row) : kGenericItemsPerThread);
-            const long long big_rounds = (units + big_round - 1) / big_round;
             if (big_rounds < nb) nb = big_rounds;
-            if (B > 1 && nb >= 8) nb &= ~7LL;
+            nb = xcd_aligned(nb, B);
             p.big = true;
             p.nblk = (int)nb;
         }

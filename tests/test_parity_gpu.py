@@ -152,6 +152,17 @@ def test_score_topk_batched_kernel_shapes(pq, oracle, N, m, B, K, b):
     assert_same_topk(pq, oracle, G, S, K, "batched")
 
 
+@pytest.mark.parametrize("N,m,B,K", [(300_001, 64, 17, 10), (200_003, 64, 40, 100), (150_001, 64, 100, 10), (300_005, 4, 100, 10),
+                                     (100_003, 4, 1024, 100), (200_001, 32, 100, 10), (150_007, 5, 100, 10), (120_001, 48, 40, 10),
+                                     (100_001, 64, 300, 10)])
+def test_score_topk_many_queries_side_by_side(pq, oracle, N, m, B, K):
+    # batches that run as B single-query scans with few item blocks each: 15, 6, 5 or 2 blocks per query, one block
+    # per query, 1024-thread workgroups for the large tables
+    G = W.codes_uniform(N, m, 256, seed=B + m)
+    S = W.normal_f32(W.stream_key(N + B, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    assert_same_topk(pq, oracle, G, S, K, "side-by-side")
+
+
 @pytest.mark.parametrize("N,m,b,B,K", [(300, 8, 256, 2000, 10), (40, 16, 256, 5000, 40), (5000, 8, 1, 7, 50),
                                        (1_200_000, 128, 256, 1, 10), (900, 4, 256, 65535, 1)])
 def test_score_topk_odd_corners(pq, oracle, N, m, b, B, K):
