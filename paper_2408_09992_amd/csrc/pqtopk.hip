@@ -178,7 +178,8 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     p.tiled = false;
     // (a small batch over a small catalogue is faster as B single-query scans side by side: the batched kernel's
     // fixed costs, about 15 us of table fill, first-round cuts and final merge, are not yet paid back)
-    const bool small_job = B <= 2 || (double)B * (double)N * m <= kTiledMinLookups;
+    // (... and its final merge grows with K: the measured crossover is 2.0e8 lookups at K = 10, 2.5e8 at K = 100)
+    const bool small_job = B <= 2 || (double)B * (double)N * m <= kTiledMinLookups * (1.0 + K / 400.0);
     if (cw == 1 && !generic && !small_job && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);

@@ -131,6 +131,8 @@ struct TileLds {
     uint64_t* best;          // [kQ][kpad]: per query, a superset of the workgroup's K best so far (ctl->keep keys)
     int kpad;
     float* sfloor;           // [kQ] workgroup-wide floors
+    uint32_t* fhist;         // [kQ][kFloorBins] histograms of the scores appended to the lists
+    FloorState* fstate;      // [kQ]
 };
 
 // Final merge of the batched kernel.  Per query it merges the eight waves' lists (and whatever best[q] already holds:
@@ -138,7 +140,7 @@ struct TileLds {
 //   - few keys everywhere: wave q ranks query q by counting, no workgroup barrier inside;
 //   - otherwise: ranking / sorting by the whole workgroup, one query at a time.
 // Every thread of the workgroup calls it.  Out of line: the streaming loop stays small.
-__device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, int tid) {
+__device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, bool filter, int tid) {
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(L.pctl + (size_t)q * align16(sizeof(Ctl))); };
     auto reset_lists = [&](int q, int wv, float floor_ge) {   // one thread per (query, wave)
@@ -149,6 +151,32 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
         if (wv == 0) L.sfloor[q] = fmaxf(L.sfloor[q], floor_ge);
     };
     __syncthreads();                                          // every wave's list state in LDS is final
+    // `filter` (lists that are only cut back when full, K > 28): the floors once more, from the finished histograms;
+    // then every wave drops from its lists what lies below them (keys appended while the floors were still low: with
+    // K = 100 they are most of what the lists hold).  At least K scanned items reach a query's floor, so none of
+    // its K best is dropped.
+    if (filter && wave < nq) {
+        const float f = floor_from_hist(L.fhist + wave * kFloorBins, K, L.fstate[wave].lo, L.fstate[wave].scale, lane);
+        if (lane == 0 && f > L.sfloor[wave]) L.sfloor[wave] = f;
+    }
+    if (filter) __syncthreads();
+    for (int q = 0; filter && q < nq; ++q) {
+        WaveQ* st = L.states + wave * kQ + q;
+        uint64_t* buf = L.lists + ((size_t)q * kWaves + wave) * cap;
+        const float f = L.sfloor[q];
+        const int n = st->cnt;
+        int out = 0;
+        for (int base = 0; base < n; base += kWave) {         // in place: a chunk is in registers before its survivors
+            const uint64_t key = base + lane < n ? buf[base + lane] : 0ull;   // are written at or below its start
+            const bool take = key != 0ull && score_of_key(key) >= f;
+            const uint64_t mask = __ballot(take);
+            if (take) buf[out + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+            out += __popcll(mask);
+        }
+        wave_sync();
+        if (lane == 0) st->cnt = out;
+    }
+    if (filter) __syncthreads();
     int total[kQ], keep[kQ];
     bool all_small = true;
 #pragma unroll
@@ -234,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     FloorState* fstate = reinterpret_cast<FloorState*>(fhist + kQ * kFloorBins);             // [kQ]
     float* sfloor = reinterpret_cast<float*>(fstate + kQ);                                   // [kQ]
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(pctl + (size_t)q * align16(sizeof(Ctl))); };
-    const TileLds tl{hist, pctl, states, lists, cand, sorted, best, kpad, sfloor};
+    const TileLds tl{hist, pctl, states, lists, cand, sorted, best, kpad, sfloor, fhist, fstate};
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q0 = blockIdx.y * kQ, nblk = gridDim.x, K = a.K, b = a.b;
@@ -520,7 +548,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
 
     // ---- 4. last checkpoint, then the workgroup's exact K best per query go to the workspace, sorted
     publish_counts();
-    tile_checkpoint(tl, nq, K, a.cap, a.candmax, tid);
+    tile_checkpoint(tl, nq, K, a.cap, a.candmax, a.prune_at == 0, tid);
     for (int i = tid; i < nq * K; i += kThreads) {
         const int q = i / K, t = i % K;
         a.ws_keys[((size_t)(q0 + q) * nblk + blockIdx.x) * K + t] = best[(size_t)q * kpad + t];

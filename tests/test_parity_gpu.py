@@ -225,6 +225,26 @@ def test_coarse_tables_many_ties(pq, oracle):
     assert_same_topk(pq, oracle, G, S.reshape(2, 4, 16), 100, "coarse")
 
 
+def test_batched_kernel_heavy_ties_at_larger_k(pq, oracle):
+    # the four-queries-per-workgroup kernel with K = 100 (lists cut by the final floors before the merge): coarse
+    # tables (few distinct scores, ties everywhere), every item equal, and a monotone table
+    N, m, B = 700_001, 8, 64
+    G = W.codes_uniform(N, m, 16, seed=9)
+    S = (np.round(W.normal_f32(W.stream_key(9, W.STREAM_QUERIES), B * m * 16) * 2) / 2).astype(np.float32).reshape(B, m, 16)
+    assert_same_topk(pq, oracle, G, S, 100, "batched coarse")
+    G = np.full((N, m), 7, dtype=np.uint8)
+    ids, _ = assert_same_topk(pq, oracle, G, W.normal_f32(W.stream_key(10, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256), 100,
+                              "batched all-equal")
+    assert all(row.tolist() == list(range(100)) for row in ids)
+    G = digits_codes(N, m)
+    S = np.zeros((B, m, 256), dtype=np.float32)
+    for q in range(B):
+        for k in range(3):
+            S[q, k] = (1.0 if q % 2 else -1.0) * np.arange(256, dtype=np.float32) * (256.0 ** k)
+    ids, _ = assert_same_topk(pq, oracle, G, S, 100, "batched monotone")
+    assert ids[0].tolist() == list(range(100)) and ids[1].tolist() == list(range(N - 1, N - 101, -1))
+
+
 def digits_codes(N, m):
     i = np.arange(N, dtype=np.int64)
     return np.stack([(i >> (8 * k)) & 255 for k in range(m)], axis=1).astype(np.uint8)
