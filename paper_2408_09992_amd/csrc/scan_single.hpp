@@ -408,7 +408,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         }
     }
     for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
-    if (tid == 0) ctl->next_unit = kRing * NW;
+    if (tid == 0) { ctl->next_unit = kRing * NW; ctl->shared_floor = -__builtin_inff(); }
     __syncthreads();
     const float* const lut = lut_base + (C > 1 ? lane % C : 0);   // this lane's copy
 
@@ -424,8 +424,26 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         }
         return unit;
     };
+    // Lists that are only cut back when full (K > 28) share a workgroup-wide floor: the first round's histogram
+    // lives on, every score appended to a list is counted in it, and the waves take turns deriving the floor it
+    // allows (at least K counted scores lie above it).  A wave alone sees a sixteenth of the workgroup's items and
+    // its own K-th best is a far lower floor: with K = 100 nearly every round of a long scan would offer something.
+    // (In a scan of a few rounds the floor has no time to pay for its counting: 5 % slower at two rounds.)
+    const bool wide_floor = a.prune_at == 0 && rounds >= kSharedFloorMinRounds;
+    float hlo = 0.0f, hscale = 0.0f;                          // the histogram's range (set in the first round)
+    int turn = wave, gap = NW;                                // units until this wave's next turn; grows by a quarter
     // what a round's scores offer to the wave's list: everything at or above its floor
     auto offer = [&](const float (&sc)[kItems], uint32_t rr, int vt) {
+        if (wide_floor) {
+            top.floor_ge = fmaxf(top.floor_ge, ctl->shared_floor);
+            if (--turn < 0) {
+                gap += gap >> 2;
+                turn = gap;
+                const float f = floor_of_hist<kBins>(L.hist, K, hlo, hscale, lane);
+                if (lane == 0 && f > ctl->shared_floor) ctl->shared_floor = f;   // (a racing lower store is still a floor)
+                top.floor_ge = fmaxf(top.floor_ge, f);
+            }
+        }
         float best = sc[0];
 #pragma unroll
         for (int e = 1; e < kItems; ++e) best = fmaxf(best, sc[e]);
@@ -436,7 +454,10 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             const uint32_t item = item_of_slot<P, NT>(rr, nblk, blk, vt, e);
             const bool take = sc[e] >= top.floor_ge && (inside || item < n_scan);
             const uint64_t mask = __ballot(take);
-            if (mask != 0) top.append(mask, take, sc[e], take ? id_of(item) : 0u, lane);
+            if (mask != 0) {
+                if (wide_floor && take) atomicAdd(&L.hist[bucket_of(sc[e], hlo, hscale)], 1u);
+                top.append(mask, take, sc[e], take ? id_of(item) : 0u, lane);
+            }
         }
         if (top.prune_at != 0 && top.cnt >= top.prune_at) top.tighten(lane);
     };
@@ -456,7 +477,9 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         for (int e = 0; e < kItems; ++e)
             if (item_of_slot<P, NT>(r, nblk, blk, tid, e) < n_scan) { mn = fminf(mn, sc[e]); mx = fmaxf(mx, sc[e]); }
         float lo, scale;
-        set_range<NW>(mn, mx, ctl, tid, lo, scale);
+        set_range<NW>(mn, mx, ctl, tid, lo, scale, wide_floor ? 1.25f : 1.0f);
+        hlo = lo;
+        hscale = scale;
         int bk[kItems];
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
@@ -464,7 +487,10 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             if (item_of_slot<P, NT>(r, nblk, blk, tid, e) < n_scan) atomicAdd(&L.hist[bk[e]], 1u);
         }
         __syncthreads();
-        if (tid < kWave) find_cut(L.hist, K, ctl, lane);
+        if (tid < kWave) {
+            find_cut(L.hist, K, ctl, lane);
+            if (lane == 0) ctl->shared_floor = next_up(ctl->cut);
+        }
         __syncthreads();
         const int bstar = ctl->bstar;
         top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut

@@ -13,6 +13,7 @@ struct Ctl {
     int ncand;           // candidates collected for an exact selection
     int keep;            // batched kernel: keys currently held in the workgroup's best[] array of this query
     int next_unit;       // single-query kernel: next unit of work to hand to a wave
+    float shared_floor;  // single-query kernel, K > 28: workgroup-wide score floor from the running histogram
     int wave_cnt[kMaxWaves];
     float wave_min[kMaxWaves];
     float wave_max[kMaxWaves];
@@ -28,8 +29,10 @@ __device__ __forceinline__ int bucket_of(float score, float lo, float scale) {
 
 // Range of the scores held by the workgroup -> bucket mapping.  Every thread passes the min / max of its own valid
 // scores (+inf / -inf if it has none).  One barrier; lo / scale come back in registers and in ctl.
+// `extend`: factor on the range (room on top for later scores when the histogram lives on as a running one).
 template <int NW = kWaves>
-__device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid, float& lo_out, float& scale_out) {
+__device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid, float& lo_out, float& scale_out,
+                                          float extend = 1.0f) {
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     wave_minmax(mn, mx);
     if (lane == 0) { ctl->wave_min[wave] = mn; ctl->wave_max[wave] = mx; }
@@ -37,7 +40,7 @@ __device__ __forceinline__ void set_range(float mn, float mx, Ctl* ctl, int tid,
     float lo = ctl->wave_min[0], hi = ctl->wave_max[0];
 #pragma unroll
     for (int w = 1; w < NW; ++w) { lo = fminf(lo, ctl->wave_min[w]); hi = fmaxf(hi, ctl->wave_max[w]); }
-    float range = hi - lo;
+    float range = (hi - lo) * extend;
     float scale = (range > 0.0f) ? (float)kBins / range : 0.0f;
     if (!(scale > 0.0f) || scale > 3.0e38f) scale = 0.0f;
     if (tid == 0) {                                          // read by find_cut / block_select after a later barrier
@@ -112,6 +115,42 @@ __device__ __forceinline__ float next_up(float x) {
     if (x == 0.0f) return __uint_as_float(1u);
     uint32_t u = __float_as_uint(x);
     return __uint_as_float(x > 0.0f ? u + 1u : u - 1u);
+}
+
+// One wave: the score floor a running histogram allows: at least K counted scores lie in the buckets from b* up, so
+// the K-th best of everything counted exceeds every score of a lower bucket.  -inf if fewer than K are counted or the
+// range is degenerate.  Same value in all lanes; nothing is written.
+template <int BINS = kBins>
+__device__ __forceinline__ float floor_of_hist(const uint32_t* hist, int K, float lo, float scale, int lane) {
+    constexpr int per = BINS / kWave;                        // buckets per lane; lane 0 owns the top ones
+    const int first = BINS - per * (lane + 1);
+    uint32_t c[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < per; i += 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(hist + first + i);
+        c[i] = v.x; c[i + 1] = v.y; c[i + 2] = v.z; c[i + 3] = v.w;
+        mine += v.x + v.y + v.z + v.w;
+    }
+    const uint32_t upto = wave_prefix_sum(mine);
+    const uint64_t has = __ballot(upto >= (uint32_t)K);
+    if (has == 0 || !(scale > 0.0f)) return -__builtin_inff();
+    const int owner = __builtin_ctzll(has);
+    uint32_t above = upto - mine;
+    int found = 0;
+    bool hit = false;
+#pragma unroll
+    for (int i = per - 1; i >= 0; --i) {
+        above += c[i];
+        if (!hit && above >= (uint32_t)K) { found = i; hit = true; }
+    }
+    const int bstar = __builtin_amdgcn_readlane(first + found, owner);
+    if (bstar <= 0) return -__builtin_inff();
+    const float width = 1.0f / scale;
+    float cut = lo + ((float)bstar - 0.5f) * width;          // a score with bucket(cut) < b*
+    for (int guard = 0; guard < 8 && bucket_of<BINS>(cut, lo, scale) >= bstar; ++guard) cut -= width;
+    if (bucket_of<BINS>(cut, lo, scale) >= bstar) return -__builtin_inff();
+    return next_up(cut);
 }
 
 // Per-wave candidate list in LDS.  A batch of at most one key per lane is appended by ballot compaction (no LDS

@@ -104,6 +104,32 @@ def test_score_topk_many_rounds(pq, oracle, N, m, B, K):
         assert ids[B - 1][0] == N - 1
 
 
+@pytest.mark.parametrize("N,m,B,K", [(30_000_001, 8, 1, 512), (20_000_003, 4, 2, 200), (12_000_001, 16, 1, 300),
+                                     (9_000_001, 8, 3, 100), (3_000_001, 64, 1, 100), (8_000_001, 5, 1, 64)])
+def test_score_topk_long_scans_at_larger_k(pq, oracle, N, m, B, K):
+    """Single-query scans of six or more rounds with K > 28: the waves share a floor from the running histogram."""
+    G = W.codes_uniform(N, m, 256, seed=m + K)
+    S = W.normal_f32(W.stream_key(N + K, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    assert_same_topk(pq, oracle, G, S, K, "long-scan-K")
+
+
+@pytest.mark.parametrize("sign", [1.0, -1.0])
+def test_long_monotone_scan_at_larger_k(pq, oracle, sign):
+    """score == +-id over 16.7M items at K = 100: ascending, every item beats everything before it (all of them pass
+    any floor and the lists overflow over and over); descending, nothing after the first K does.  Then a coarse table:
+    a handful of distinct scores, so whole buckets of the running histogram tie."""
+    N, m = 16_700_000, 4
+    i = np.arange(N, dtype=np.int64)
+    G = np.stack([(i >> (8 * k)) & 255 for k in range(m)], axis=1).astype(np.uint8)
+    S = np.zeros((1, m, 256), dtype=np.float32)
+    for k in range(3):
+        S[0, k] = sign * np.arange(256, dtype=np.float32) * (256.0 ** k)
+    ids, _ = assert_same_topk(pq, oracle, G, S, 100, "long monotone")
+    assert ids[0].tolist() == (list(range(N - 1, N - 101, -1)) if sign > 0 else list(range(100)))
+    Sc = (np.round(W.normal_f32(W.stream_key(5, W.STREAM_QUERIES), m * 256) * 2) / 2).astype(np.float32).reshape(1, m, 256)
+    assert_same_topk(pq, oracle, G, Sc, 100, "long coarse")
+
+
 def test_subset_long_list(pq, oracle):
     N, m = 20_000_000, 8
     G = W.codes_uniform(N, m, 256, seed=9)
