@@ -16,7 +16,7 @@ constexpr int kBins = 1024;                       // score buckets of the prunin
 __host__ __device__ constexpr int vec_per_thread(int m) { return m == 64 ? 1 : (m == 32 ? 2 : (m >= 8 ? 4 : (m == 4 ? 2 : 1))); }
 constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
 constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
-constexpr int kSharedFloorMinRounds = 6;          // single-query scan, K > 28: rounds per workgroup from which the waves share a floor
+constexpr int kSharedFloorMinRounds = 6;          // single-query scan: rounds per workgroup from which the waves share a floor
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950

@@ -142,12 +142,12 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     // the tables, lanes l and l' collide only if l % kTableCopies == l' % kTableCopies.  Worth its LDS and fill time
     // only when every workgroup streams many rounds; one workgroup per CU then (the tables take 128 KB at m = 8).
     if (cw == 1 && p.vec && m <= 8) {
-        const long long nb = kAssumedCUs / B;                  // one workgroup (of kBigThreads) per CU over the whole grid
         const long long big_round = (long long)kBigThreads * vec_per_thread(m);
         const long long big_rounds = (units + big_round - 1) / big_round;
+        long long nb = kAssumedCUs / B;                        // one workgroup (of kBigThreads) per CU over the whole grid
+        if (nb < 8) nb = blocks_for_many_queries(kAssumedCUs, B, big_rounds, lookups);
         const size_t dyn = scan_lds_bytes((size_t)m * kLutStride * kTableCopies, p.cap, p.candmax, K, kMaxWaves);
-        if (nb >= 8 && big_rounds >= kTableCopiesMinRounds * nb && dyn <= kMaxLdsBytes) {   // (nb < 8: more queries than
-                                                                                            // the grid has room for)
+        if (big_rounds >= kTableCopiesMinRounds * nb && dyn <= kMaxLdsBytes) {
             p.copies = kTableCopies;
             p.nblk = (int)nb;
         }
@@ -288,7 +288,11 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
     a.subset = subset; a.n_items = (uint32_t)(subset ? n_items : N);
     a.cap = p.cap; a.candmax = p.candmax;
-    a.prune_at = (K <= 28) ? 2 * K + 8 : 0;                 // small K: keep lists short enough to rank in one pass
+    // Batched kernel, small K: lists are cut back to their K best once they pass 2K + 8 keys, short enough to rank in
+    // one pass; from K = 13 on its shared floors and final filter do better without (K = 16: 53 -> 48 us, K = 28:
+    // 63 -> 52 us at batch 24).  The single-query kernel never cuts early: lists are sorted when full, and the shared
+    // floor of long scans keeps them from filling (K = 10: 50M items 79.7 -> 77.5 us, m = 4 at batch 64 57 -> 49 us).
+    a.prune_at = (p.tiled && K <= 12) ? 2 * K + 8 : 0;
     a.ws_keys = static_cast<uint64_t*>(workspace);
     hipError_t e;
     if (p.tiled) {

@@ -151,7 +151,7 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
         if (wv == 0) L.sfloor[q] = fmaxf(L.sfloor[q], floor_ge);
     };
     __syncthreads();                                          // every wave's list state in LDS is final
-    // `filter` (lists that are only cut back when full, K > 28): the floors once more, from the finished histograms;
+    // `filter` (lists that are only cut back when full: K > 12 in this kernel): the floors once more, from the finished histograms;
     // then every wave drops from its lists what lies below them (keys appended while the floors were still low: with
     // K = 100 they are most of what the lists hold).  At least K scanned items reach a query's floor, so none of
     // its K best is dropped.

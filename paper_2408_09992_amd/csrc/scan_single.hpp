@@ -424,11 +424,12 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         }
         return unit;
     };
-    // Lists that are only cut back when full (K > 28) share a workgroup-wide floor: the first round's histogram
+    // In scans of several rounds the waves share a workgroup-wide floor: the first round's histogram
     // lives on, every score appended to a list is counted in it, and the waves take turns deriving the floor it
     // allows (at least K counted scores lie above it).  A wave alone sees a sixteenth of the workgroup's items and
     // its own K-th best is a far lower floor: with K = 100 nearly every round of a long scan would offer something.
     // (In a scan of a few rounds the floor has no time to pay for its counting: 5 % slower at two rounds.)
+    // (`prune_at`: another kernel that shares these lists cuts them back early instead; never set for this one.)
     const bool wide_floor = a.prune_at == 0 && rounds >= kSharedFloorMinRounds;
     float hlo = 0.0f, hscale = 0.0f;                          // the histogram's range (set in the first round)
     int turn = wave, gap = NW;                                // units until this wave's next turn; grows by a quarter
