@@ -13,7 +13,7 @@ struct Ctl {
     int ncand;           // candidates collected for an exact selection
     int keep;            // batched kernel: keys currently held in the workgroup's best[] array of this query
     int next_unit;       // single-query kernel: next unit of work to hand to a wave
-    float shared_floor;  // single-query kernel, K > 28: workgroup-wide score floor from the running histogram
+    float shared_floor;  // single-query kernel, scans of several rounds: workgroup-wide score floor from the running histogram
     int wave_cnt[kMaxWaves];
     float wave_min[kMaxWaves];
     float wave_max[kMaxWaves];
