@@ -112,6 +112,20 @@ long long blocks_for_many_queries(long long slots, long long B, long long rounds
     return best_nb;
 }
 
+// Lookups (B * N * m) from which the batched kernel beats B single-query scans side by side.  Measured on catalogues
+// of 3e5 to 2e7 items: its fixed costs (about 15 us of tables, first cuts and final merge, more with K) are paid back
+// from 2e8 lookups on at K = 10.  At m = 8 the side-by-side scans run with replicated tables as long as their lists
+// leave room for them (K <= 64) and then stay ahead up to 8e8 lookups; for K > 128 their shared floors do.
+double tiled_min_lookups(int m, int K) {
+    if (m == 8) {
+        if (K <= 12) return kTiledMinLookups * (1.0 + K / 400.0);
+        if (K <= 64) return 8.5e8;
+        if (K <= 128) return 3.5e8;
+        return 9.0e8;
+    }
+    return K <= 128 ? kTiledMinLookups * (1.0 + K / 400.0) : 5.0e8;
+}
+
 // `generic`: plan for the generic kernel whatever m is (candidate-list scans use it: their rows are gathered)
 // `cw`, `b`: bytes per sub-id (1 or 2) and, for two-byte sub-ids, the alphabet size (it sizes the tables in LDS)
 ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int cw = 1, int b = kLutStride) {
@@ -178,8 +192,7 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     p.tiled = false;
     // (a small batch over a small catalogue is faster as B single-query scans side by side: the batched kernel's
     // fixed costs, about 15 us of table fill, first-round cuts and final merge, are not yet paid back)
-    // (... and its final merge grows with K: the measured crossover is 2.0e8 lookups at K = 10, 2.5e8 at K = 100)
-    const bool small_job = B <= 2 || (double)B * (double)N * m <= kTiledMinLookups * (1.0 + K / 400.0);
+    const bool small_job = B <= 2 || (double)B * (double)N * m <= tiled_min_lookups(m, K);
     if (cw == 1 && !generic && !small_job && (m == 8 || m == 16) && N * m >= 16) {   // batched kernel, if its tables and lists fit in LDS
         const size_t dyn = tiled_lds_bytes(p.cap, p.candmax, K);
         const size_t all = dyn + (size_t)kQ * m * kLutStride * sizeof(float);
