@@ -18,6 +18,7 @@ constexpr int kGenericItemsPerThread = 4;         // items a thread holds per ro
 constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
 constexpr int kSharedFloorMinRounds = 6;          // single-query scan: rounds per workgroup from which the waves share a floor
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
+constexpr int kFoldWideRegs = 13;                 // ... and of the 1024-thread fold (13,312 keys)
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
 constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace

@@ -20,7 +20,11 @@ __host__ __device__ inline size_t fold_lds_bytes(int stage_keys, int candmax, in
            (size_t)candmax * sizeof(uint64_t) + align16((size_t)K * sizeof(uint64_t));
 }
 
-__global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
+// NT threads, REGS keys per thread held in registers: <kThreads, kFoldRegs> is the usual instance; <kBigThreads,
+// kFoldWideRegs> takes a query's lists in one go when they are too many for the first (many workgroups times a
+// larger K at a small batch), instead of a level of several smaller folds.
+template <int NT, int REGS>
+__global__ __launch_bounds__(NT) void fold_topk_kernel(FoldArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
     Ctl* ctl = reinterpret_cast<Ctl*>(smem + kBins * sizeof(uint32_t));
@@ -34,7 +38,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     const long long nkeys = (long long)my_lists * K;
     auto key_at = [&](long long i) { return all[i]; };
     auto emit = [&](const uint64_t* sorted_keys) {
-        for (int t = tid; t < K; t += kThreads) {
+        for (int t = tid; t < K; t += NT) {
             const uint64_t key = sorted_keys[t];
             if (a.out_keys != nullptr) {
                 a.out_keys[((size_t)q * gridDim.x + group) * K + t] = key;
@@ -47,22 +51,22 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
 
     // score range of all the keys (empty slots of short lists are 0); a modest number of keys stays in registers
     const int lane = tid & (kWave - 1);
-    const bool in_regs = nkeys <= (long long)kThreads * kFoldRegs;
-    uint64_t keys[kFoldRegs];
+    const bool in_regs = nkeys <= (long long)NT * REGS;
+    uint64_t keys[REGS];
     float mn = __builtin_inff(), mx = -__builtin_inff();
     if (in_regs) {
 #pragma unroll
-        for (int r = 0; r < kFoldRegs; ++r) {
-            const long long i = (long long)r * kThreads + tid;
+        for (int r = 0; r < REGS; ++r) {
+            const long long i = (long long)r * NT + tid;
             keys[r] = (i < nkeys) ? key_at(i) : 0ull;
             if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
     } else {
-        for (long long i0 = tid; i0 < nkeys; i0 += 8LL * kThreads) {          // eight loads in flight per thread
+        for (long long i0 = tid; i0 < nkeys; i0 += 8LL * NT) {          // eight loads in flight per thread
             uint64_t kk[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const long long i = i0 + (long long)j * kThreads;
+                const long long i = i0 + (long long)j * NT;
                 kk[j] = i < nkeys ? key_at(i) : 0ull;
             }
 #pragma unroll
@@ -70,15 +74,15 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
                 if (kk[j]) { float s = score_of_key(kk[j]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
         }
     }
-    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+    for (int i = tid; i < kBins; i += NT) hist[i] = 0;
     float lo, scale;
-    set_range(mn, mx, ctl, tid, lo, scale);
+    set_range<NT / kWave>(mn, mx, ctl, tid, lo, scale);
 
     if (in_regs) {
         // one pass: histogram, cut, collect the few keys at or above the cut, rank them
-        int bk[kFoldRegs];
+        int bk[REGS];
 #pragma unroll
-        for (int r = 0; r < kFoldRegs; ++r) {
+        for (int r = 0; r < REGS; ++r) {
             bk[r] = -1;
             if (keys[r]) { bk[r] = bucket_of(score_of_key(keys[r]), lo, scale); atomicAdd(&hist[bk[r]], 1u); }
         }
@@ -87,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
         __syncthreads();
         const int bstar = ctl->bstar;
 #pragma unroll
-        for (int r = 0; r < kFoldRegs; ++r) {
+        for (int r = 0; r < REGS; ++r) {
             if (bk[r] >= bstar) {
                 int pos = atomicAdd(&ctl->ncand, 1);
                 if (pos < a.candmax) cand[pos] = keys[r];
@@ -96,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
         __syncthreads();
         const int C = ctl->ncand;
         if (C <= a.candmax) {
-            rank_select(cand, C, K, sorted, tid);
+            rank_select<NT>(cand, C, K, sorted, tid);
             emit(sorted);
             return;
         }
@@ -106,11 +110,11 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
         // (they sit in L2) instead of held in registers: histogram, cut, collect, rank
         constexpr int kBatch = 8;                            // loads in flight per thread (the passes are latency-bound)
         auto for_each_key = [&](auto&& f) {
-            for (long long i0 = tid; i0 < nkeys; i0 += (long long)kBatch * kThreads) {
+            for (long long i0 = tid; i0 < nkeys; i0 += (long long)kBatch * NT) {
                 uint64_t kk[kBatch];
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j) {
-                    const long long i = i0 + (long long)j * kThreads;
+                    const long long i = i0 + (long long)j * NT;
                     kk[j] = i < nkeys ? key_at(i) : 0ull;
                 }
 #pragma unroll
@@ -123,11 +127,11 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
         if (tid < kWave) find_cut(hist, K, ctl, lane);
         __syncthreads();
         const int bstar = ctl->bstar;
-        for (long long i0 = tid; i0 - tid < nkeys; i0 += (long long)kBatch * kThreads) {   // (whole waves stay in the loop)
+        for (long long i0 = tid; i0 - tid < nkeys; i0 += (long long)kBatch * NT) {   // (whole waves stay in the loop)
             uint64_t kk[kBatch];
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
-                const long long i = i0 + (long long)j * kThreads;
+                const long long i = i0 + (long long)j * NT;
                 kk[j] = i < nkeys ? key_at(i) : 0ull;
             }
 #pragma unroll
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
         __syncthreads();
         const int C = ctl->ncand;
         if (C <= a.candmax) {
-            rank_select(cand, C, K, sorted, tid);
+            rank_select<NT>(cand, C, K, sorted, tid);
             emit(sorted);
             return;
         }
@@ -157,13 +161,13 @@ __global__ __launch_bounds__(kThreads) void fold_topk_kernel(FoldArgs a) {
     while (done < nkeys) {
         long long take = nkeys - done;
         if (take > a.stage_keys - keep) take = a.stage_keys - keep;
-        for (int t = tid; t < a.stage_keys - keep; t += kThreads) stage[keep + t] = (t < take) ? key_at(done + t) : 0ull;
+        for (int t = tid; t < a.stage_keys - keep; t += NT) stage[keep + t] = (t < take) ? key_at(done + t) : 0ull;
         __syncthreads();
-        block_select(stage, a.stage_keys, K, sorted, cand, a.candmax, hist, ctl, tid);
+        block_select<NT>(stage, a.stage_keys, K, sorted, cand, a.candmax, hist, ctl, tid);
         done += take;
         keep = K;
         if (done < nkeys) {
-            for (int t = tid; t < K; t += kThreads) stage[t] = sorted[t];
+            for (int t = tid; t < K; t += NT) stage[t] = sorted[t];
             __syncthreads();
         }
     }

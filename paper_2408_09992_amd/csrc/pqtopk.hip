@@ -341,9 +341,15 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     return record_hip(e);
 }
 
-// Enqueue the fold of the workspace's lists into the outputs.
-// Lists one fold workgroup takes: as many as it can hold in registers (kThreads * kFoldRegs keys), at least two.
-int fold_lists_per_group(int K) {
+// Lists one fold workgroup takes at a level with `nlists` lists per query.  All of them when their keys fit the usual
+// fold's registers (kThreads * kFoldRegs keys), or the wide fold's (kBigThreads * kFoldWideRegs keys, `wide` set: one
+// launch of one larger workgroup instead of two levels).  More keys than that are split into groups of the usual size:
+// several small folds side by side and one more level beat one workgroup that reads everything (256 lists of
+// K = 100: 14 us in two levels, 16-24 us in one workgroup of 1024 threads holding 26 keys each).
+int fold_lists_per_group(int nlists, int K, bool* wide) {
+    const long long nkeys = (long long)nlists * K;
+    *wide = nkeys > (long long)kThreads * kFoldRegs && nkeys <= (long long)kBigThreads * kFoldWideRegs;
+    if (nkeys <= (long long)kBigThreads * kFoldWideRegs) return nlists;
     const int fit = kThreads * kFoldRegs / K;
     return fit < 2 ? 2 : fit;
 }
@@ -351,7 +357,8 @@ int fold_lists_per_group(int K) {
 // Keys of the second key area of the workspace: what the first fold level writes when the lists of a query do not fit
 // one workgroup's registers (later levels alternate between the two areas, each needing less than the one before).
 size_t fold_area_keys(int nblk, int B, int K) {
-    const int per = fold_lists_per_group(K);
+    bool wide;
+    const int per = fold_lists_per_group(nblk, K, &wide);
     if (nblk <= per) return 0;
     return (size_t)B * ((nblk + per - 1) / per) * K;
 }
@@ -359,13 +366,15 @@ size_t fold_area_keys(int nblk, int B, int K) {
 // Enqueue the fold of the workspace's lists into the outputs: one launch when a query's lists fit one workgroup's
 // registers, else levels of launches that each fold groups of lists into one list per group.
 int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
-    hipError_t e = allow_lds(fold_topk_kernel, p.fold_lds);
+    hipError_t e = allow_lds(fold_topk_kernel<kThreads, kFoldRegs>, p.fold_lds);
+    if (e == hipSuccess) e = allow_lds(fold_topk_kernel<kBigThreads, kFoldWideRegs>, p.fold_lds);
     if (e != hipSuccess) return record_hip(e);
     uint64_t* area[2] = {static_cast<uint64_t*>(workspace),
                          reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + keys_bytes(p, B, K))};
-    const int per = fold_lists_per_group(K);
     int nlists = p.nblk, src = 0;
     for (;;) {
+        bool wide;
+        const int per = fold_lists_per_group(nlists, K, &wide);
         const int groups = nlists <= per ? 1 : (nlists + per - 1) / per;
         FoldArgs f;
         f.ws_keys = area[src];
@@ -373,7 +382,11 @@ int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids,
         f.stage_keys = p.stage_keys; f.candmax = p.candmax;
         f.out_keys = groups == 1 ? nullptr : area[1 - src];
         f.out_ids = out_ids; f.out_scores = out_scores;
-        hipLaunchKernelGGL(fold_topk_kernel, dim3(groups, B), dim3(kThreads), p.fold_lds, st, f);
+        if (wide)
+            hipLaunchKernelGGL((fold_topk_kernel<kBigThreads, kFoldWideRegs>), dim3(groups, B), dim3(kBigThreads), p.fold_lds,
+                               st, f);
+        else
+            hipLaunchKernelGGL((fold_topk_kernel<kThreads, kFoldRegs>), dim3(groups, B), dim3(kThreads), p.fold_lds, st, f);
         e = hipGetLastError();
         if (e != hipSuccess) return record_hip(e);
         if (groups == 1) return PQ_OK;

@@ -79,13 +79,27 @@ def test_score_topk_large_k(pq, oracle):
 
 
 def test_score_topk_single_query_mid_k(pq, oracle):
-    """K between the sizes the wave-level paths treat differently (pruned lists up to K = 28, floors by bisection
-    up to K = 64, histogram cut above), one query, several rounds per workgroup and a ragged tail."""
+    """K around the sizes at which paths change (lists cut back early up to K = 12 in the batched kernel, the fold of
+    256 lists in one 512-thread workgroup up to K = 24, in one 1024-thread workgroup up to K = 52, in two levels
+    above), one query, several rounds per workgroup and a ragged tail."""
     for N, m in ((1_500_001, 8), (700_003, 4), (300_001, 16)):
         G = W.codes_uniform(N, m, 256, seed=N)
         S = W.normal_f32(W.stream_key(N, W.STREAM_QUERIES), m * 256).reshape(1, m, 256)
-        for K in (28, 29, 50, 64, 65):
+        for K in (12, 13, 24, 25, 28, 29, 50, 52, 53, 64, 65):
             assert_same_topk(pq, oracle, G, S, K, "midK")
+
+
+@pytest.mark.parametrize("N,m,B,K", [(1_280_000, 8, 1, 400), (1_280_000, 8, 1, 512), (1_280_000, 8, 3, 52), (1_280_000, 8, 4, 100),
+                                     (600_001, 4, 2, 300), (1_280_000, 8, 1, 350)])
+def test_score_topk_fold_levels(pq, oracle, N, m, B, K):
+    """Folds of more keys than one 512-thread workgroup holds: one 1024-thread workgroup (up to 13,312 keys), groups of
+    lists side by side and a second level, and a second level that is itself a 1024-thread fold (K = 400, 512)."""
+    G = W.codes_uniform(N, m, 256, seed=K)
+    S = W.normal_f32(W.stream_key(N + K, W.STREAM_QUERIES), B * m * 256).reshape(B, m, 256)
+    assert_same_topk(pq, oracle, G, S, K, "fold-levels")
+    # heavy ties: the wide fold's staged fallback
+    Sc = (np.round(S * 2) / 2).astype(np.float32)
+    assert_same_topk(pq, oracle, G, Sc, K, "fold-levels-coarse")
 
 
 @pytest.mark.parametrize("N,m,B,K", [(40_000_003, 4, 1, 10), (30_000_001, 8, 2, 10), (18_000_001, 16, 1, 100),
