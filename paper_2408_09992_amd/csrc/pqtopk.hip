@@ -145,6 +145,13 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     if (rounds > one_per_cu && rounds <= most) nblk = one_per_cu;
     if (nblk < 1) nblk = 1;
     nblk = xcd_aligned(nblk, B);
+    {
+        // A fold of one launch instead of two levels is worth a slightly coarser grid (K = 53 .. 69 at batch 1: 256
+        // lists of K = 64 take two fold levels, 208 lists one launch: 22.1 -> 19.1 us per call); not a much coarser one
+        // (K = 100 on 133 workgroups instead of 256: 24.7 -> 26.9 us).
+        const long long one_fold = (long long)kBigThreads * kFoldWideRegs / K;   // lists one fold launch takes
+        if (nblk > one_fold && 4 * one_fold >= 3 * nblk) nblk = one_fold;
+    }
     p.nblk = (int)nblk;
     p.cap = list_capacity(K);
     p.candmax = next_pow2(2 * K);
