@@ -144,6 +144,26 @@ def test_long_monotone_scan_at_larger_k(pq, oracle, sign):
     assert_same_topk(pq, oracle, G, Sc, 100, "long coarse")
 
 
+def test_long_scan_with_late_outliers_and_tiny_ranges(pq, oracle):
+    """Shared floors under score distributions the first round does not announce: a few hundred items far above the
+    first round's range, all of them late in the catalogue (they land in the histogram's top bucket); and tables of
+    denormal entries (the range is too small for a histogram: every score is a candidate)."""
+    N, m, K = 12_000_001, 8, 100
+    G = W.codes_uniform(N, m, 255, seed=21)                       # sub-id 255 of split 0 is never drawn ...
+    S = W.normal_f32(W.stream_key(21, W.STREAM_QUERIES), m * 256).reshape(1, m, 256)
+    S[0, 0, 255] = 1.0e6                                          # ... and is worth a million
+    late = N - 1 - W.plant_ids(N // 10, 300, seed=3)              # 300 distinct ids in the last tenth
+    G[late, 0] = 255
+    ids, sc = assert_same_topk(pq, oracle, G, S, K, "late outliers")
+    assert set(ids[0].tolist()) <= set(late.tolist()) and sc[0].min() > 9.0e5
+    ids, _ = assert_same_topk(pq, oracle, G, S, 10, "late outliers K=10")
+    assert set(ids[0].tolist()) <= set(late.tolist())
+    Sd = (np.abs(S) * np.float32(1e-41)).astype(np.float32)       # denormals: 0 .. ~4e-41
+    Sd[0, 0, 255] = 0.0
+    assert Sd.max() < 1.2e-38 and Sd.max() > 0
+    assert_same_topk(pq, oracle, G[:3_000_001], Sd, 50, "denormal tables")
+
+
 def test_subset_long_list(pq, oracle):
     N, m = 20_000_000, 8
     G = W.codes_uniform(N, m, 256, seed=9)
