@@ -249,3 +249,28 @@ def test_product_does_not_reach_the_oracle():
         for fn in files:
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 assert not pat.search(open(os.path.join(dirpath, fn)).read()), fn
+
+
+def test_workspace_bytes_over_a_grid_of_shapes(lib):
+    """The launch planner behind the workspace size (pure host arithmetic) over a grid of shapes: every supported
+    problem gets a workspace that holds at least one list of K keys per query and stays small next to the codes."""
+    ws, ws16, wsub = lib.pq_score_topk_workspace_bytes, lib.pq_score_topk_u16_workspace_bytes, lib.pq_score_topk_subset_workspace_bytes
+    n_checked = 0
+    for N in (1, 7, 1000, 123_457, 1_280_000, 50_000_000, 2 ** 31 - 1):
+        for B in (1, 2, 3, 5, 17, 48, 64, 100, 384, 1024, 65535):
+            for m in (1, 3, 4, 8, 12, 16, 32, 64, 128):
+                for K in (1, 10, 12, 13, 28, 29, 64, 100, 192, 193, 448, 512):
+                    if K > N:
+                        continue
+                    need = ws(N, B, m, 256, K)
+                    if m == 128 and K > 64:
+                        continue                              # (may exceed LDS: allowed to be unsupported)
+                    assert need >= B * K * 8 and need % 16 == 0, (N, B, m, K, need)
+                    assert need <= 64 * B * K * 8 * 64 + (1 << 20), (N, B, m, K, need)   # at most a few thousand lists per query
+                    sub = wsub(N, B, m, 256, K)
+                    assert sub >= B * K * 8, (N, B, m, K, sub)
+                    if m <= 16:
+                        need16 = ws16(N, B, m, 1024, K)
+                        assert need16 >= B * K * 8 and need16 % 16 == 0, (N, B, m, K, need16)
+                    n_checked += 1
+    assert n_checked > 5000
