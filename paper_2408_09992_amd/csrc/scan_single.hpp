@@ -564,7 +564,9 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     }
 
     // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
-    workgroup_select<NT>(L, ctl, top, K, a.cap, a.candmax, tid);
+    // (the running histogram's floor joins the final selection from K = 32 on: below, the waves' own floors leave few
+    // enough keys, and deriving it would cost more than it saves)
+    workgroup_select<NT>(L, ctl, top, K, a.cap, a.candmax, tid, wide_floor && K >= 32, hlo, hscale);
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
     for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
 }

@@ -383,9 +383,10 @@ __device__ inline ScanLds carve_scan(unsigned char* smem, size_t lut_floats, int
 
 // The end of a single-query scan: the waves' lists -> the workgroup's exact K best, sorted, in L.sorted (zero where
 // fewer than K exist).  Every thread of the workgroup calls it once its wave has offered everything.
+// `running`: L.hist is the scan's running histogram (range hlo / hscale): its floor joins the waves' own.
 template <int NT>
 __device__ __forceinline__ void workgroup_select(const ScanLds& L, Ctl* ctl, WaveTopK& top, int K, int cap, int candmax,
-                                                 int tid) {
+                                                 int tid, bool running = false, float hlo = 0.0f, float hscale = 0.0f) {
     constexpr int NW = NT / kWave;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     if (lane == 0) {
@@ -402,10 +403,14 @@ __device__ __forceinline__ void workgroup_select(const ScanLds& L, Ctl* ctl, Wav
     int total = __builtin_amdgcn_readlane((int)upto, kWave - 1);
     const int before = __builtin_amdgcn_readlane((int)(upto - cnt_w), wave);
     wave_minmax(fl_lo, wg_floor);
-    if (total <= candmax) {
+    // (every wave derives the histogram's floor by itself; nothing counts into it any more)
+    if (running && total > kFilterMin) wg_floor = fmaxf(wg_floor, floor_of_hist<kBins>(L.hist, K, hlo, hscale, lane));
+    bool ranked = false;
+    if (total <= candmax || (running && wg_floor > -__builtin_inff())) {
         if (total > kFilterMin) {
             // a long scan leaves every wave with its own K best and more: only keys that reach the best of the waves'
-            // K-th scores can be among the workgroup's K best (that score is a lower bound of the workgroup's K-th)
+            // K-th scores, or the floor of the running histogram, can be among the workgroup's K best (both are lower
+            // bounds of the workgroup's K-th)
             for (int t0 = 0; t0 < top.cnt; t0 += kWave) {
                 const uint64_t key = t0 + lane < top.cnt ? top.buf[t0 + lane] : 0ull;
                 const bool take = key != 0ull && score_of_key(key) >= wg_floor;
@@ -413,15 +418,20 @@ __device__ __forceinline__ void workgroup_select(const ScanLds& L, Ctl* ctl, Wav
                 int base = 0;
                 if (lane == 0 && mask != 0) base = atomicAdd(&ctl->ncand, __popcll(mask));
                 base = __builtin_amdgcn_readfirstlane(base);
-                if (take) L.cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+                const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
+                if (take && pos < candmax) L.cand[pos] = key;
             }
             __syncthreads();
-            total = ctl->ncand;
+            total = ctl->ncand;                                   // (more than candmax: the lists are intact, see below)
         } else {
             for (int t = lane; t < top.cnt; t += kWave) L.cand[before + t] = top.buf[t];
         }
-        rank_select<NT>(L.cand, total, K, L.sorted, tid);        // its first barrier orders the copies above
-    } else {
+        if (total <= candmax) {
+            rank_select<NT>(L.cand, total, K, L.sorted, tid);    // its first barrier orders the copies above
+            ranked = true;
+        }
+    }
+    if (!ranked) {
         // too many keys for one ranking (long lists, large K): histogram over the listed keys' own range, or a sort
         float mn = __builtin_inff(), mx = -__builtin_inff();
         for (int t = lane; t < top.cnt; t += kWave) {
