@@ -89,11 +89,12 @@ int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int 
  *   codes       in   uint16 [N][m]    codebook G, sub-ids < b (16-byte aligned)
  *   S           in   float [B][m][b]
  *   workspace        at least pq_score_topk_u16_workspace_bytes(N, B, m, b, K) bytes, 16-byte aligned
- * The query's whole m x b table is held in LDS: m * b * 4 bytes plus the candidate lists (about 80 *
- * nextpow2(K + 64) bytes) must fit 160 KB, e.g. m * b <= 36864 at K = 10 (m = 8: b <= 4608).  Rows of 8, 16 or 32
- * bytes (m = 4, 8, 16) are scanned as 16-byte vectors; any other m row by row.  Every query of a batch scans the
- * codebook by itself (no shared pass).  A sub-id >= b reads an unspecified LDS word (never device memory).
- * Errors: as pq_score_topk(), with PQ_ERR_SHAPE for b > 65536 and PQ_ERR_UNSUPPORTED when the table does not fit LDS.
+ * The query's whole m x b table is held in LDS when m * b * 4 bytes plus the candidate lists (about 80 *
+ * nextpow2(K + 64) bytes) fit 160 KB, e.g. m * b <= 36864 at K = 10 (m = 8: b <= 4608); a larger table is read where
+ * it lies, in device memory (it stays in L2; several times slower per lookup, sub-ids clamped to b - 1).  Rows of 8,
+ * 16 or 32 bytes (m = 4, 8, 16) are scanned as 16-byte vectors; any other m row by row.  Every query of a batch scans
+ * the codebook by itself (no shared pass).  A sub-id >= b reads an unspecified table or LDS word (never outside them).
+ * Errors: as pq_score_topk(), with PQ_ERR_SHAPE for b > 65536.
  */
 size_t pq_score_topk_u16_workspace_bytes(long long N, int B, int m, int b, int K);
 int pq_score_topk_u16(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K,

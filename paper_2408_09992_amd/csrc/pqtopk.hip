@@ -81,6 +81,7 @@ struct ScanPlan {
     size_t scan_lds;         // dynamic + the static score tables of the vector kernels
     size_t fold_lds;
     bool vec;
+    bool glut;       // two-byte sub-ids: the m x b table does not fit LDS and is read from device memory
 };
 
 bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32 || m == 64; }
@@ -131,7 +132,13 @@ double tiled_min_lookups(int m, int K) {
 ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int cw = 1, int b = kLutStride) {
     ScanPlan p;
     const int row = m * cw;                                    // bytes of an item's row
-    const size_t lut_floats = cw == 1 ? (size_t)m * kLutStride : (size_t)m * b;
+    size_t lut_floats = cw == 1 ? (size_t)m * kLutStride : (size_t)m * b;
+    p.cap = list_capacity(K);
+    p.candmax = next_pow2(2 * K);
+    if (p.candmax < 512) p.candmax = 512;
+    // two-byte sub-ids whose table leaves no room in LDS (even for one 1024-thread workgroup): lookups go to memory
+    p.glut = cw == 2 && scan_lds_bytes(lut_floats, p.cap, p.candmax, K, kMaxWaves) > kMaxLdsBytes;
+    if (p.glut) lut_floats = 0;
     p.vec = !generic && (cw == 1 ? is_vec_m(m) : is_vec_m16(m)) && N * row >= 16;   // (one whole code vector at least)
     const long long units = (p.vec && row <= 16) ? (N * row) / 16 : N;   // whole code vectors (the few items after them are extra)
     const long long per_round = (long long)kThreads * (p.vec ? vec_per_thread(row) : kGenericItemsPerThread);
@@ -153,9 +160,6 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
         if (nblk > one_fold && 4 * one_fold >= 3 * nblk) nblk = one_fold;
     }
     p.nblk = (int)nblk;
-    p.cap = list_capacity(K);
-    p.candmax = next_pow2(2 * K);
-    if (p.candmax < 512) p.candmax = 512;
     p.stage_keys = next_pow2(2 * K);
     if (p.stage_keys < kChunkKeys) p.stage_keys = kChunkKeys;
     p.copies = 1;
@@ -281,6 +285,15 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL((scan_topk_kernel<M, kTableCopies, kBigThreads>), dim3(p.nblk, B), dim3(kBigThreads),
                                p.scan_dyn_lds, st, a);
+            return hipGetLastError();
+        }
+    }
+    if constexpr (CW == 2) {
+        if (p.glut) {
+            hipError_t e = allow_lds(scan_topk_kernel<M, 1, kThreads, 2, true>, p.scan_dyn_lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((scan_topk_kernel<M, 1, kThreads, 2, true>), dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds,
+                               st, a);
             return hipGetLastError();
         }
     }

@@ -124,12 +124,15 @@ __device__ float score_row(const float* lut, const uint8_t* row, int m) {
 // ---- sub-ids of two bytes (alphabets of up to 65536 sub-ids per split): tables of `stride` = b entries per split
 
 // Eq. 5 for the 8/M items packed in one 16-byte vector of 16-bit sub-ids (M = 1, 2, 4 or 8 splits).
-template <int M>
+// GL: the tables are read from device memory (they do not fit LDS); a sub-id is then clamped to b - 1, so that no
+// value of a code can reach outside the table.
+template <int M, bool GL = false>
 __device__ __forceinline__ void score_vector16(const float* lut, int stride, const uint32_t* w, float* sc) {
     float v[8];
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
-        const uint32_t code = (h & 1) ? (w[h >> 1] >> 16) : (w[h >> 1] & 0xFFFFu);
+        uint32_t code = (h & 1) ? (w[h >> 1] >> 16) : (w[h >> 1] & 0xFFFFu);
+        if constexpr (GL) code = code < (uint32_t)stride ? code : (uint32_t)stride - 1u;
         v[h] = lut[(h % M) * stride + code];
     }
     __builtin_amdgcn_sched_barrier(0);                // keep the reads ahead of the sums
@@ -143,7 +146,7 @@ __device__ __forceinline__ void score_vector16(const float* lut, int stride, con
 }
 
 // Eq. 5 for one item of M = 16 or 32 sub-ids of 16 bits (M/8 vectors): one left-to-right chain over all M values.
-template <int M>
+template <int M, bool GL = false>
 __device__ __forceinline__ float score_wide16(const float* lut, int stride, const uint32_t* w) {
     float acc = 0.0f;
 #pragma unroll
@@ -152,7 +155,8 @@ __device__ __forceinline__ float score_wide16(const float* lut, int stride, cons
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
             const uint32_t word = w[4 * j + (h >> 1)];
-            const uint32_t code = (h & 1) ? (word >> 16) : (word & 0xFFFFu);
+            uint32_t code = (h & 1) ? (word >> 16) : (word & 0xFFFFu);
+            if constexpr (GL) code = code < (uint32_t)stride ? code : (uint32_t)stride - 1u;
             v[h] = lut[(j * 8 + h) * stride + code];
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -163,8 +167,10 @@ __device__ __forceinline__ float score_wide16(const float* lut, int stride, cons
 }
 
 // Eq. 5 for one row of m 16-bit sub-ids that starts at any even address.
+template <bool GL = false>
 __device__ float score_row16(const float* lut, int stride, const uint8_t* row, int m) {
     float acc = 0.0f;
+    auto at = [&](uint32_t code) { return GL ? (code < (uint32_t)stride ? code : (uint32_t)stride - 1u) : code; };
     if ((m & 7) == 0) {
         const uint4* p = reinterpret_cast<const uint4*>(row);
         for (int v = 0; v < (m >> 3); ++v) {
@@ -172,7 +178,7 @@ __device__ float score_row16(const float* lut, int stride, const uint8_t* row, i
             const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
             for (int h = 0; h < 8; ++h) {
-                const uint32_t code = (h & 1) ? (w[h >> 1] >> 16) : (w[h >> 1] & 0xFFFFu);
+                const uint32_t code = at((h & 1) ? (w[h >> 1] >> 16) : (w[h >> 1] & 0xFFFFu));
                 const float t = lut[(v * 8 + h) * stride + code];
                 acc = (v == 0 && h == 0) ? t : acc + t;
             }
@@ -181,15 +187,15 @@ __device__ float score_row16(const float* lut, int stride, const uint8_t* row, i
         const uint32_t* p = reinterpret_cast<const uint32_t*>(row);
         for (int v = 0; v < (m >> 1); ++v) {
             const uint32_t w = p[v];
-            const float t0 = lut[(2 * v) * stride + (w & 0xFFFFu)];
-            const float t1 = lut[(2 * v + 1) * stride + (w >> 16)];
+            const float t0 = lut[(2 * v) * stride + at(w & 0xFFFFu)];
+            const float t1 = lut[(2 * v + 1) * stride + at(w >> 16)];
             acc = (v == 0) ? t0 : acc + t0;
             acc = acc + t1;
         }
     } else {
         const uint16_t* g = reinterpret_cast<const uint16_t*>(row);
         for (int k = 0; k < m; ++k) {
-            const float t = lut[k * stride + g[k]];
+            const float t = lut[k * stride + at(g[k])];
             acc = (k == 0) ? t : acc + t;
         }
     }
@@ -234,7 +240,7 @@ __device__ __forceinline__ void load_round(const ScanArgs& a, uint32_t rr, int n
 // `inside`: the round lies wholly inside the scanned units (n_units of them); otherwise vectors past the end are not
 // looked up at all (a wave whose lanes are all past the end skips the vector's table reads).
 // M: splits (0: any, at run time); CW: bytes per sub-id; `stride`: table entries per split in LDS.
-template <int M, int C = 1, int NT = kThreads, int CW = 1>
+template <int M, int C = 1, int NT = kThreads, int CW = 1, bool GL = false>
 __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut, int stride, uint32_t rr, int nblk, int blk,
                                             int tid, bool inside, uint32_t n_units,
                                             const uint32_t (&w)[Round<M * CW>::kWords], float (&sc)[Round<M * CW>::kItems]) {
@@ -244,8 +250,8 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
         for (int u = 0; u < Round<P>::kUnitsPerThread; ++u) {
             if (inside || unit_of<P, NT>(rr, u, nblk, blk, tid) < n_units) {
                 if constexpr (CW == 2) {
-                    if constexpr (P > 16) sc[u] = score_wide16<M>(lut, stride, &w[4 * Round<P>::kVPU * u]);
-                    else score_vector16<M>(lut, stride, &w[4 * u], &sc[u * Round<P>::kIPV]);
+                    if constexpr (P > 16) sc[u] = score_wide16<M, GL>(lut, stride, &w[4 * Round<P>::kVPU * u]);
+                    else score_vector16<M, GL>(lut, stride, &w[4 * u], &sc[u * Round<P>::kIPV]);
                 } else {
                     if constexpr (M > 16) sc[u] = score_wide<M>(lut, &w[4 * Round<M>::kVPU * u]);
                     else score_vector<M, C>(lut, &w[4 * u], &sc[u * Round<M>::kIPV]);
@@ -266,7 +272,7 @@ __device__ __forceinline__ void score_round(const ScanArgs& a, const float* lut,
                     item = (uint32_t)a.subset[unit];
                     item = item < a.n_items ? item : a.n_items - 1;
                 }
-                if constexpr (CW == 2) v = score_row16(lut, stride, a.codes + (size_t)item * a.m * 2, a.m);
+                if constexpr (CW == 2) v = score_row16<GL>(lut, stride, a.codes + (size_t)item * a.m * 2, a.m);
                 else v = score_row(lut, a.codes + (size_t)item * a.m, a.m);
             }
             sc[u] = v;
@@ -289,19 +295,21 @@ __device__ __forceinline__ uint32_t item_of_slot(uint32_t rr, int nblk, int blk,
 // CW: bytes per sub-id.  CW = 2 (alphabets of up to 65536 sub-ids per split): rows of m 16-bit sub-ids, the m x b
 // table in dynamic LDS as it lies in memory (b entries per split); the vector instances are those whose rows take
 // 8, 16 or 32 bytes (m = 4, 8, 16).
-template <int M, int C = 1, int NT = kThreads, int CW = 1>
+// GL (two-byte sub-ids only): the m x b table does not fit LDS and is read where it lies, in device memory (L2).
+template <int M, int C = 1, int NT = kThreads, int CW = 1, bool GL = false>
 __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     constexpr int NW = NT / kWave;
     constexpr int P = M * CW;                                  // bytes of an item's row (0: known at run time only)
     constexpr bool kStaticLut = M && C == 1 && CW == 1;
     static_assert(C == 1 || (M > 0 && CW == 1), "replicated tables need a compile-time m and one-byte sub-ids");
+    static_assert(!GL || CW == 2, "tables in device memory: two-byte sub-ids only");
     __shared__ __align__(16) float lut_static[kStaticLut ? M * kLutStride : 4];
     extern __shared__ __align__(16) unsigned char smem[];
     const int m = M ? M : a.m;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q = blockIdx.y, nblk = gridDim.x, K = a.K, b = a.b;
     const int stride = CW == 1 ? kLutStride : b;               // table entries per split in LDS
-    const ScanLds L = carve_scan(smem, kStaticLut ? 0 : (size_t)m * stride * C, a.cap, a.candmax, NW);
+    const ScanLds L = carve_scan(smem, (kStaticLut || GL) ? 0 : (size_t)m * stride * C, a.cap, a.candmax, NW);
     float* const lut_base = kStaticLut ? lut_static : L.lut;
     Ctl* ctl = L.ctl;
     constexpr int kItems = Round<P>::kItems;
@@ -335,7 +343,9 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         for (int i = 0; i < kRing; ++i) fetch(r + i, tid, w[i]);
     };
     const float* Sq = a.S + (size_t)q * m * b;
-    if constexpr (CW == 2) {
+    if constexpr (GL) {
+        fetch_first();                                        // (nothing to fill: lookups go to memory)
+    } else if constexpr (CW == 2) {
         // the query's m x b table as it lies in memory, in 16-byte pieces when its size and address allow
         const int total = m * b;
         fetch_first();
@@ -410,7 +420,10 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
     if (tid == 0) { ctl->next_unit = kRing * NW; ctl->shared_floor = -__builtin_inff(); }
     __syncthreads();
-    const float* const lut = lut_base + (C > 1 ? lane % C : 0);   // this lane's copy
+    const float* const lut = [&]() -> const float* {
+        if constexpr (GL) return Sq;
+        else return lut_base + (C > 1 ? lane % C : 0);        // this lane's copy
+    }();
 
     WaveTopK top{L.lists + (size_t)wave * a.cap, a.cap, K, a.prune_at, 0, 0ull, -__builtin_inff()};
 
@@ -465,14 +478,14 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     // one streamed round
     auto process = [&](const uint32_t (&w)[kWords], uint32_t rr, int vt) {
         float sc[kItems];
-        score_round<M, C, NT, CW>(a, lut, stride, rr, nblk, blk, vt, rr < inside_rounds, total_units, w, sc);
+        score_round<M, C, NT, CW, GL>(a, lut, stride, rr, nblk, blk, vt, rr < inside_rounds, total_units, w, sc);
         offer(sc, rr, vt);
     };
 
     {
         // ---- 2. first round: scores in registers, histogram over their range, cut
         float sc[kItems];
-        score_round<M, C, NT, CW>(a, lut, stride, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
+        score_round<M, C, NT, CW, GL>(a, lut, stride, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
@@ -548,9 +561,10 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
                 const uint8_t* row = a.codes + (size_t)item * P;
                 if constexpr (CW == 2) {
                     const uint16_t* g = reinterpret_cast<const uint16_t*>(row);
-                    sc = lut[g[0]];
+                    auto at = [&](uint32_t code) { return GL ? (code < (uint32_t)stride ? code : (uint32_t)stride - 1u) : code; };
+                    sc = lut[at(g[0])];
 #pragma unroll
-                    for (int k = 1; k < M; ++k) sc = sc + lut[(size_t)k * stride + g[k]];
+                    for (int k = 1; k < M; ++k) sc = sc + lut[(size_t)k * stride + at(g[k])];
                 } else {
                     sc = lut[(size_t)row[0] * C];
 #pragma unroll

@@ -145,9 +145,9 @@ def test_score_topk_u16_argument_errors(lib):
     assert call(N=0) == SHAPE and call(B=0) == SHAPE and call(m=0) == SHAPE and call(b=0) == SHAPE and call(K=0) == SHAPE
     assert call(b=65537) == SHAPE and call(K=100001) == SHAPE and call(N=2 ** 31) == SHAPE
     assert call(K=513) == UNSUPPORTED and call(m=129) == UNSUPPORTED and call(B=65536) == UNSUPPORTED
-    # the whole m x b table has to fit LDS next to the candidate lists
-    assert call(m=8, b=8192) == UNSUPPORTED and call(m=2, b=65536) == UNSUPPORTED and call(m=64, b=1024) == UNSUPPORTED
-    assert ws(100000, 1, 8, 8192, 10) == 0 and ws(100000, 1, 8, 65537, 10) == 0
+    # a table too large for LDS is read from memory: every alphabet up to 65536 is served
+    assert ws(100000, 1, 8, 8192, 10) > 0 and ws(100000, 1, 2, 65536, 10) > 0 and ws(100000, 1, 64, 1024, 10) > 0
+    assert ws(100000, 1, 128, 65536, 512) > 0 and ws(100000, 1, 8, 65537, 10) == 0
     assert ws(100000, 1, 8, 4096, 10) > 0 and ws(100000, 1, 1, 32768, 10) > 0 and ws(100000, 3, 5, 300, 100) > 0
     assert call(codes=p + 8) == ALIGN and call(ws=p + 4) == ALIGN and call(S=p + 1) == ALIGN
     assert call(wsb=ws(100000, 1, 8, 1024, 10) - 1) == WORKSPACE

@@ -514,11 +514,18 @@ def test_u16_from_embeddings(pq, oracle):
     assert_same_topk_u16(pq, oracle, G, S, K, "embeddings")
 
 
+@pytest.mark.parametrize("N,m,b,B,K", [(300_001, 8, 65536, 1, 10), (200_003, 2, 65536, 2, 100), (150_001, 16, 8192, 1, 10),
+                                       (100_001, 5, 40000, 3, 10), (2_000_001, 8, 8192, 1, 10), (50_001, 32, 4096, 1, 512),
+                                       (7, 3, 65536, 1, 7), (400_001, 4, 65536, 64, 10)])
+def test_u16_tables_too_large_for_lds(pq, oracle, N, m, b, B, K):
+    # tables from 256 KB to 2 MB per query: looked up in device memory; the largest sub-id (b - 1) is present
+    G = W.codes_uniform_u16(N, m, b, seed=N % 1000 + m)
+    G[N // 2] = b - 1
+    assert_same_topk_u16(pq, oracle, G, tables(N % 1000 + b, B, m, b), K, "memory tables")
+
+
 def test_u16_errors_reach_python(pq):
     G = dev(W.codes_uniform_u16(1000, 8, 300))
-    with pytest.raises(pq.PQError) as e:
-        pq.pq_score_topk_u16(G, dev(np.zeros((1, 8, 8192), dtype=np.float32)), 10)      # 256 KB of tables
-    assert e.value.code == pq.PQ_ERR_UNSUPPORTED
     with pytest.raises(pq.PQError) as e:
         pq.pq_score_topk_u16(G, dev(np.zeros((1, 8, 300), dtype=np.float32)), 1001)
     assert e.value.code == pq.PQ_ERR_SHAPE
