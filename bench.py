@@ -459,6 +459,9 @@ def main():
                      "read_kernel_GBps": read_gbs, "frac_of_read_kernel": achieved / read_gbs,
                      "empty_launch_us": floor_us},
         "stage_us": {"pq_subitem_scores": t_sub, "pq_score_topk": t_top, "scan_kernel": scan_ms * 1e3},
+        # the whole step against the HBM peak: codes once, S written and read, results written, over the step time
+        "whole_step": {"effective_GBps": (algo_bytes + 4.0 * B * m * b + 8.0 * B * K) / (ms_per_step * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": (algo_bytes + 4.0 * B * m * b + 8.0 * B * K) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "latency_us": {"what": "one step at a time, host enqueue to completion", "median": float(np.median(lat)),
                        "mean": float(lat.mean()), "p99": float(np.percentile(lat, 99)),
                        "cold_caches_median": float(np.median(cold))},
