@@ -17,6 +17,7 @@ __host__ __device__ constexpr int vec_per_thread(int m) { return m == 64 ? 1 : (
 constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
 constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
 constexpr int kSharedFloorMinRounds = 6;          // single-query scan: rounds per workgroup from which the waves share a floor
+constexpr int kSharedFloorMinRoundsLargeK = 3;    // ... for K >= 32
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
 constexpr int kFoldWideRegs = 13;                 // ... and of the 1024-thread fold (13,312 keys)
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
