@@ -254,6 +254,29 @@ def test_score_topk_seeded_random_shapes(pq, oracle):
             assert_same_subset_topk(pq, oracle, G, S, V, K, f"random-subset#{case}")
 
 
+def test_seeded_random_shapes_larger_catalogues_and_wide_codes(pq, oracle):
+    # a second seeded walk: catalogues of 10^5 to 3*10^6 items (several rounds per workgroup, every kernel instance and
+    # both folds), one- and two-byte sub-ids, K at the values where paths change, duplicated rows and coarse tables
+    rng = np.random.default_rng(20240820)
+    for case in range(60):
+        wide = rng.random() < 0.35
+        m = int(rng.choice([1, 2, 3, 4, 5, 8, 8, 8, 12, 16, 16, 32, 64]))
+        b = int(rng.choice([257, 1000, 4096, 9000, 65536])) if wide else int(rng.choice([16, 255, 256, 256]))
+        N = int(10 ** rng.uniform(5.0, 6.5))
+        B = int(rng.choice([1, 1, 2, 3, 5, 8, 24, 33, 64]))
+        if N * m * B > 2.5e8:
+            B = max(1, int(2.5e8 // (N * m)))
+        K = int(rng.choice([1, 10, 10, 12, 13, 28, 29, 52, 53, 64, 100, 192, 193, 300, 512]))
+        G = (W.codes_uniform_u16 if wide else W.codes_uniform)(N, m, b, seed=case)
+        if rng.random() < 0.3:                              # a tenth of the rows copied from elsewhere: exact ties
+            idx, src = rng.integers(0, N, size=N // 10), rng.integers(0, N, size=N // 10)
+            G[idx] = G[src]
+        S = W.normal_f32(W.stream_key(1000 + case, W.STREAM_QUERIES), B * m * b).reshape(B, m, b)
+        if rng.random() < 0.3:
+            S = np.round(S * 2).astype(np.float32) / 2
+        (assert_same_topk_u16 if wide else assert_same_topk)(pq, oracle, G, S, K, f"random2#{case}")
+
+
 def test_score_topk_largest_catalogue(pq, oracle):
     # N = 2^31 - 1, the largest the interface takes (m = 1: 2 GB of codes): every index computation at its limit,
     # with the winner planted as the very last item
