@@ -16,6 +16,7 @@ constexpr int kBins = 1024;                       // score buckets of the prunin
 __host__ __device__ constexpr int vec_per_thread(int m) { return m == 64 ? 1 : (m == 32 ? 2 : (m >= 8 ? 4 : (m == 4 ? 2 : 1))); }
 constexpr int kGenericItemsPerThread = 4;         // items a thread holds per round when m is not 1,2,4,8,16
 constexpr int kRing = 2;                          // rounds of codes a thread has loaded or in flight
+constexpr int kRegisterSelectMinK = 32;           // scans of at most kRing rounds: K from which all scores are selected from registers at once
 constexpr int kSharedFloorMinRounds = 6;          // single-query scan: rounds per workgroup from which the waves share a floor
 constexpr int kSharedFloorMinRoundsLargeK = 3;    // ... for K >= 32
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)

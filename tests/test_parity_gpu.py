@@ -302,6 +302,25 @@ def test_all_items_equal(pq, oracle):
         assert ids[0].tolist() == list(range(25))
 
 
+def test_short_scans_with_larger_k_select_from_registers(pq, oracle):
+    # at most two rounds per workgroup and K >= 32: one selection over all the workgroup's scores; every item equal
+    # (the cut bucket holds them all: back to the lists), a last odd item that wins, and one- and two-byte sub-ids
+    for N in (100_001, 1_280_001):
+        G = np.full((N, 8), 9, dtype=np.uint8)
+        S = W.normal_f32(W.stream_key(N, W.STREAM_QUERIES), 8 * 256).reshape(1, 8, 256)
+        ids, _ = assert_same_topk(pq, oracle, G, S, 64, "short all-equal")
+        assert ids[0].tolist() == list(range(64))
+        G = W.codes_uniform(N, 8, 256, seed=N)
+        G[N - 1] = S[0].argmax(axis=1)                         # the item after the last whole code vector is the best
+        ids, _ = assert_same_topk(pq, oracle, G, S, 100, "short last-wins")
+        assert ids[0][0] == N - 1
+        G16 = W.codes_uniform_u16(N, 4, 1000, seed=N)          # rows of 8 bytes: N odd leaves one item after the vectors
+        S16 = tables(N, 2, 4, 1000)
+        G16[N - 1] = S16[1].argmax(axis=1)
+        ids, _ = assert_same_topk_u16(pq, oracle, G16, S16, 50, "short last-wins u16")
+        assert ids[1][0] == N - 1
+
+
 def test_coarse_tables_many_ties(pq, oracle):
     G = W.codes_uniform(300_000, 4, 16, seed=3)
     S = (np.round(W.normal_f32(W.stream_key(3, W.STREAM_QUERIES), 2 * 4 * 16) * 2) / 2).astype(np.float32)
