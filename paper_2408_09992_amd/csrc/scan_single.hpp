@@ -418,7 +418,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         }
     }
     for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
-    if (tid == 0) { ctl->next_unit = kRing * NW; ctl->shared_floor = -__builtin_inff(); }
+    if (tid == 0) { ctl->next_unit = kRing * NW; ctl->shared_floor = -__builtin_inff(); ctl->ncand = 0; }
     __syncthreads();
     const float* const lut = [&]() -> const float* {
         if constexpr (GL) return Sq;
@@ -483,14 +483,18 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         offer(sc, rr, vt);
     };
 
-    // ---- 1b. a scan of at most two rounds (every catalogue up to a few million items at batch 1) with a larger K:
-    // both rounds' codes are already loaded, so all of the workgroup's scores fit its registers.  One selection over
-    // them all - range, histogram, cut, the few keys at or above the cut ranked by counting - instead of a first
-    // cut, per-wave lists and their merge (1.28M items: K = 100 10.1 -> 9.0 us, K = 512 23.0 -> 18.3 us; for K = 10
-    // the lists are as fast, and faster when there is one round only).  Heavy ties (more keys in the cut bucket
-    // than the candidate array holds) fall through to the general path below, which starts over from the codes.
+    // ---- 1b. a scan of at most two rounds (every catalogue up to a few million items at batch 1): both rounds' codes
+    // are already loaded, so all of the workgroup's scores fit its registers and are selected from there, without the
+    // per-wave lists and their merge.
+    //   K < 32: every wave finds a floor that K of its lanes' best scores reach (wave operations only), compacts the
+    //   dozen or so scores at or above it into the shared candidate array, and after one barrier the workgroup ranks
+    //   them all by counting (three barriers in all, against six of the general path).
+    //   K >= 32: one selection by the whole workgroup - range, histogram, cut, the few keys at or above the cut ranked
+    //   by counting (1.28M items: K = 100 10.1 -> 9.0 us, K = 512 23.0 -> 18.3 us).
+    // Heavy ties (more candidates than the array holds) fall through to the general path below, which starts over
+    // from the codes.
     bool done = false;
-    if (rounds <= (uint32_t)kRing && K >= kRegisterSelectMinK) {
+    if (rounds <= (uint32_t)kRing) {
         float sc2[kRing][kItems];
         bool ok2[kRing][kItems];
         float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -533,36 +537,80 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
                 }
             }
         }
-        float lo, scale;
-        set_range<NW>(mn, mx, ctl, tid, lo, scale);
+        int ncand = 0;
+        if (K < kRegisterSelectMinK) {
+            // (mx: the lane's best score, -inf if it holds no item; at least K of the wave's items reach the floor, and
+            // so does every one of the wave's K best)
+            const float f = wave_floor_for_k(mx, K);
+            uint64_t masks[kRing * kItems + 1];
+            int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < kRing; ++i)
+            for (int i = 0; i < kRing; ++i)
 #pragma unroll
-            for (int e = 0; e < kItems; ++e)
-                if (ok2[i][e]) atomicAdd(&L.hist[bucket_of(sc2[i][e], lo, scale)], 1u);
-        if (tail_ok) atomicAdd(&L.hist[bucket_of(tail_sc, lo, scale)], 1u);
-        __syncthreads();
-        if (tid < kWave) find_cut(L.hist, K, ctl, lane);
-        __syncthreads();
-        const int bstar = ctl->bstar;
-        auto collect = [&](float score, uint32_t item) {      // few threads get here: a counter update each
-            const int pos = atomicAdd(&ctl->ncand, 1);
-            if (pos < a.candmax) L.cand[pos] = make_key(score + 0.0f, id_of(item));
-        };
+                for (int e = 0; e < kItems; ++e) {
+                    masks[i * kItems + e] = __ballot(ok2[i][e] && sc2[i][e] >= f);
+                    cnt += __popcll(masks[i * kItems + e]);
+                }
+            masks[kRing * kItems] = __ballot(tail_ok && tail_sc >= f);
+            cnt += __popcll(masks[kRing * kItems]);
+            int base = 0;
+            if (lane == 0 && cnt != 0) base = atomicAdd(&ctl->ncand, cnt);
+            base = __builtin_amdgcn_readfirstlane(base);
+            const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-        for (int i = 0; i < kRing; ++i)
+            for (int i = 0; i < kRing; ++i)
 #pragma unroll
-            for (int e = 0; e < kItems; ++e)
-                if (ok2[i][e] && bucket_of(sc2[i][e], lo, scale) >= bstar) collect(sc2[i][e], item_of_slot<P, NT>(i, nblk, blk, tid, e));
-        if (tail_ok && bucket_of(tail_sc, lo, scale) >= bstar) collect(tail_sc, tail_item);
-        __syncthreads();
-        const int ncand = ctl->ncand;
-        if (ncand <= a.candmax) {
-            rank_select<NT>(L.cand, ncand, K, L.sorted, tid);
-            done = true;
-        } else {
-            for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;   // start over with the general path
+                for (int e = 0; e < kItems; ++e) {
+                    const uint64_t mk = masks[i * kItems + e];
+                    if (mk == 0) continue;
+                    const int pos = base + __popcll(mk & below);
+                    if (((mk >> lane) & 1ull) && pos < a.candmax)
+                        L.cand[pos] = make_key(sc2[i][e] + 0.0f, id_of(item_of_slot<P, NT>(i, nblk, blk, tid, e)));
+                    base += __popcll(mk);
+                }
+            {
+                const uint64_t mk = masks[kRing * kItems];
+                const int pos = base + __popcll(mk & below);
+                if (((mk >> lane) & 1ull) && pos < a.candmax) L.cand[pos] = make_key(tail_sc + 0.0f, id_of(tail_item));
+            }
             __syncthreads();
+            ncand = ctl->ncand;
+        } else {
+            float lo, scale;
+            set_range<NW>(mn, mx, ctl, tid, lo, scale);
+#pragma unroll
+            for (int i = 0; i < kRing; ++i)
+#pragma unroll
+                for (int e = 0; e < kItems; ++e)
+                    if (ok2[i][e]) atomicAdd(&L.hist[bucket_of(sc2[i][e], lo, scale)], 1u);
+            if (tail_ok) atomicAdd(&L.hist[bucket_of(tail_sc, lo, scale)], 1u);
+            __syncthreads();
+            if (tid < kWave) find_cut(L.hist, K, ctl, lane);
+            __syncthreads();
+            const int bstar = ctl->bstar;
+            auto collect = [&](float score, uint32_t item) {      // few threads get here: a counter update each
+                const int pos = atomicAdd(&ctl->ncand, 1);
+                if (pos < a.candmax) L.cand[pos] = make_key(score + 0.0f, id_of(item));
+            };
+#pragma unroll
+            for (int i = 0; i < kRing; ++i)
+#pragma unroll
+                for (int e = 0; e < kItems; ++e)
+                    if (ok2[i][e] && bucket_of(sc2[i][e], lo, scale) >= bstar) collect(sc2[i][e], item_of_slot<P, NT>(i, nblk, blk, tid, e));
+            if (tail_ok && bucket_of(tail_sc, lo, scale) >= bstar) collect(tail_sc, tail_item);
+            __syncthreads();
+            ncand = ctl->ncand;
+            if (ncand > a.candmax) {
+                for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;   // (the general path starts from an empty histogram)
+            }
+        }
+        if (!done) {
+            if (ncand <= a.candmax) {
+                rank_select<NT>(L.cand, ncand, K, L.sorted, tid);
+                done = true;
+            } else {
+                __syncthreads();                                  // start over with the general path
+            }
         }
     }
 
