@@ -1,5 +1,5 @@
 // Constants, cross-lane helpers (DPP), wave-level reductions and the bitonic sort shared by every kernel.
-// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
 // common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
 #pragma once
 

@@ -1,5 +1,5 @@
 // Kernels of the paper's two comparison scorers, TopK over score rows, and the streaming-read yardstick.
-// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
 // common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
 #pragma once
 

@@ -1,5 +1,5 @@
 // The second launch of every TopK call: the workgroups' lists -> the final sorted K per query (fold_topk_kernel).
-// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
 // common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
 #pragma once
 

@@ -24,23 +24,19 @@
 // Floors and histograms only ever prune; every decision that picks a winner compares full keys, so the result is
 // exact for any input, including heavy ties (which merely take slower paths).
 //
-// This file holds the host side (plans, launches, the extern "C" entry points); the device code is in the .hpp parts
-// included below, which together with this file form one translation unit.
+// This file holds the host side (plans, launches, the extern "C" entry points).  The device code is in the .hpp parts
+// that kernels.hpp gathers in namespace pqk; the large scan kernels are compiled in the inst_*.hip translation units
+// and only launched from here.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
 
 #include "pqtopk.h"
+#include "kernels.hpp"
 
 namespace {
 
-#include "common.hpp"
-#include "subitem_scores.hpp"
-#include "topk_parts.hpp"
-#include "scan_single.hpp"
-#include "scan_batched.hpp"
-#include "fold.hpp"
-#include "comparison.hpp"
+using namespace pqk;
 
 // ---------------------------------------------------------------------------------------------------------------
 // host side

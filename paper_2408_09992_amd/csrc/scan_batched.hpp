@@ -1,5 +1,5 @@
 // Eq. 5 + TopK for a tile of four queries per workgroup (scan_topk_tiled_kernel).
-// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
 // common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
 #pragma once
 

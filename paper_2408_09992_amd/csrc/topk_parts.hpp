@@ -1,5 +1,5 @@
 // What the TopK side of every kernel is made of: keys, histogram cuts, per-wave candidate lists, exact selection.
-// Part of pqtopk.hip (one translation unit): included there inside its unnamed namespace, in this order:
+// Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
 // common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
 #pragma once
 
