@@ -42,10 +42,12 @@ extern "C" {
 #define PQ_ERR_WORKSPACE    -4   /* workspace smaller than pq_score_topk_workspace_bytes() */
 #define PQ_ERR_ALIGN        -5   /* a pointer is not aligned as required */
 #define PQ_ERR_HIP          -6   /* a HIP call (kernel launch) failed; pq_strerror() gives HIP's text */
+#define PQ_ERR_TOO_LARGE    -7   /* pq_score_topk_static(): the problem needs more than PQ_STATIC_SCRATCH_BYTES of scratch */
 
 #define PQ_MAX_K      512        /* largest K the top-K kernels keep per query */
 #define PQ_MAX_M      128        /* largest number of splits (score tables of m*256 floats must fit LDS) */
 #define PQ_MAX_B    65535        /* largest batch per call */
+#define PQ_STATIC_SCRATCH_BYTES (8u << 20)   /* built-in scratch of pq_score_topk_static(), per GPU */
 
 /*
  * Sub-id score matrix, Eq. 4 (Section 3): S[q][k][j] = psi_{k,j} . phi_{q,k}.
@@ -81,6 +83,23 @@ size_t pq_score_topk_workspace_bytes(long long N, int B, int m, int b, int K);
  */
 int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
                   int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * pq_score_topk() for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same kernels, same
+ * result; the workgroups' partial top-K lists go to an array built into the library (PQ_STATIC_SCRATCH_BYTES = 8 MiB
+ * of device memory per GPU the library runs on, held until the process ends) instead of a caller's workspace.  The
+ * call allocates and frees nothing.
+ *   - A problem whose pq_score_topk_workspace_bytes() exceeds PQ_STATIC_SCRATCH_BYTES is rejected with
+ *     PQ_ERR_TOO_LARGE (nothing enqueued).  Every named workload fits (the largest, B = 1024 with K = 100, needs
+ *     less than 2 MiB).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race and give unspecified results; calls on one stream are ordered and safe.  Nothing in the array
+ *     has to survive from one call to the next.
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED, PQ_ERR_ALIGN, PQ_ERR_TOO_LARGE, PQ_ERR_HIP.
+ */
+int pq_score_topk_static(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
+                         int* out_ids, float* out_scores, void* stream);
 
 /*
  * Algorithm 1 with V = I for codebooks whose sub-ids do not fit a byte.  The paper's codebook G holds natural numbers

@@ -16,6 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpqtopk.so")
 
 PQ_OK, PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED, PQ_ERR_WORKSPACE, PQ_ERR_ALIGN, PQ_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+PQ_ERR_TOO_LARGE = -7
+PQ_STATIC_SCRATCH_BYTES = 8 << 20
 
 _lib = None
 
@@ -41,6 +43,8 @@ def lib() -> ctypes.CDLL:
         L.pq_score_topk_workspace_bytes.restype = SZ
         L.pq_score_topk.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P]
         L.pq_score_topk.restype = I
+        L.pq_score_topk_static.argtypes = [P, P, LL, I, I, I, I, P, P, P]
+        L.pq_score_topk_static.restype = I
         L.pq_score_topk_profile.argtypes = [P, P, LL, I, I, I, I, P, P, P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
         L.pq_score_topk_profile.restype = I
         L.pq_score_topk_u16_workspace_bytes.argtypes = [LL, I, I, I, I]
@@ -135,6 +139,24 @@ def pq_score_topk(codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optio
                              out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
     if rc != PQ_OK:
         raise PQError(rc, "pq_score_topk")
+    return out_ids, out_scores
+
+
+def pq_score_topk_static(codes: torch.Tensor, S: torch.Tensor, K: int, out_ids: torch.Tensor, out_scores: torch.Tensor
+                         ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """pq_score_topk on the library's built-in scratch: the call allocates nothing (outputs are the caller's)."""
+    _dev(codes, torch.uint8, "codes")
+    _dev(S, torch.float32, "S")
+    _dev(out_ids, torch.int32, "out_ids")
+    _dev(out_scores, torch.float32, "out_scores")
+    N, m = codes.shape
+    B, m2, b = S.shape
+    if m2 != m or tuple(out_ids.shape) != (B, K) or tuple(out_scores.shape) != (B, K):
+        raise PQError(PQ_ERR_SHAPE, "pq_score_topk_static")
+    rc = lib().pq_score_topk_static(codes.data_ptr(), S.data_ptr(), N, B, m, b, K, out_ids.data_ptr(),
+                                    out_scores.data_ptr(), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_score_topk_static")
     return out_ids, out_scores
 
 

@@ -34,6 +34,11 @@
 #include "pqtopk.h"
 #include "kernels.hpp"
 
+// Built-in scratch of pq_score_topk_static(): device memory, one copy per GPU, held until the process ends.  Host code
+// never uses this name as an address (it is a handle for hipGetSymbolAddress(), see static_scratch() below).
+constexpr size_t kStaticScratchBytes = PQ_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 using namespace pqk;
@@ -428,6 +433,28 @@ void launch_subitem(const float* queries, const float* centroids, float* S, int 
     hipLaunchKernelGGL(subitem_scores_kernel<S_ELEMS>, grid, dim3(kSubThreads), 0, st, queries, centroids, S, B, d, m, b);
 }
 
+// ---- the built-in scratch of pq_score_topk_static(): one array per GPU, held until the process ends
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle for
+// hipGetSymbolAddress(): every GPU holds its own copy at its own address, looked up once per device and kept.
+int static_scratch(void** out) {
+    static void* ptr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip(e);
+    if (dev < 0 || dev >= kMaxDevices) return PQ_ERR_UNSUPPORTED;
+    void* p = __atomic_load_n(&ptr[dev], __ATOMIC_ACQUIRE);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // (the same answer from every thread that races here)
+        if (e != hipSuccess) return record_hip(e);
+        if (p == nullptr) return PQ_ERR_HIP;
+        __atomic_store_n(&ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return PQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -466,6 +493,25 @@ int pq_score_topk(const uint8_t* codes, const float* S, long long N, int B, int 
     rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st);
     if (rc != PQ_OK) return rc;
     return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st);
+}
+
+int pq_score_topk_static(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K, int* out_ids,
+                         float* out_scores, void* stream) {
+    if (!codes || !S || !out_ids || !out_scores) return PQ_ERR_NULL;
+    int rc = check_topk_shape(N, B, m, b, K, 1);
+    if (rc != PQ_OK) return rc;
+    const ScanPlan p = make_plan(N, B, m, K);
+    if (p.scan_lds > kMaxLdsBytes || p.fold_lds > kMaxLdsBytes) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)codes & 15) || ((uintptr_t)S & 3) || ((uintptr_t)out_ids & 3) || ((uintptr_t)out_scores & 3))
+        return PQ_ERR_ALIGN;
+    if (workspace_bytes(p, B, K) > kStaticScratchBytes) return PQ_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != PQ_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = enqueue_scan(p, codes, S, N, B, m, b, K, ws, st);
+    if (rc != PQ_OK) return rc;
+    return enqueue_fold(p, B, K, ws, out_ids, out_scores, st);
 }
 
 }  // extern "C"
@@ -712,6 +758,7 @@ const char* pq_strerror(int code) {
         case PQ_ERR_WORKSPACE: return "workspace smaller than pq_score_topk_workspace_bytes()";
         case PQ_ERR_ALIGN: return "pointer alignment: codes and workspace 16 bytes, float/int arrays 4 bytes";
         case PQ_ERR_HIP: return g_hip_error;
+        case PQ_ERR_TOO_LARGE: return "problem needs more scratch than the library's built-in array holds (PQ_STATIC_SCRATCH_BYTES)";
         default: return "unknown pqtopk error code";
     }
 }
