@@ -295,6 +295,136 @@ def wide_mode(args):
         "wide": points}))
 
 
+def breakdown_mode(args):
+    """Where the time of a step goes: the three launches of a single-query step (Eq. 4, scan, fold) are run with the
+    kernels' stamping instances (wall-clock stamps at fixed points, lane 0 of every wave), back to back as in the timed
+    loop, and the last step's stamps are read; repeated --breakdown-samples times, medians over samples.  Times are
+    microseconds after the first wave of the Eq. 4 kernel started, unless noted."""
+    import numpy as np
+    import torch
+    from paper_2408_09992_amd import binding as pq, workloads as W
+
+    cfg = W.CONFIGS[args.config]
+    G, cent, Q = W.make(cfg, B=1)
+    N, m, b, K, d = cfg.N, cfg.m, cfg.b, cfg.K, cfg.d
+    Gd, Cd, Qd = torch.from_numpy(G).cuda(), torch.from_numpy(cent).cuda(), torch.from_numpy(Q).cuda()
+    S = torch.empty((1, m, b), dtype=torch.float32, device="cuda")
+    ws = torch.empty(pq.pq_score_topk_workspace_bytes(N, 1, m, b, K), dtype=torch.uint8, device="cuda")
+    ids = torch.empty((1, K), dtype=torch.int32, device="cuda")
+    sc = torch.empty((1, K), dtype=torch.float32, device="cuda")
+    stamps = torch.zeros((3, pq.PQ_STAMP_RECORDS, pq.PQ_STAMP_SLOTS), dtype=torch.int64, device="cuda")
+    tick_us = 0.01                                           # wall_clock64(): 100 MHz on MI355X
+    names = {0: "entry", 1: "requested", 2: "tables", 3: "codes", 4: "scored", 5: "offered", 6: "streamed", 7: "selected",
+             8: "end", 9: "loaded", 10: "cut", 11: "collected"}
+    rows = []
+    for _ in range(args.breakdown_samples):
+        for _ in range(args.breakdown_steps):
+            nblk, waves = pq.pq_measure_step_stamps(Qd, Cd, Gd, K, S, ids, sc, ws, stamps)
+        torch.cuda.synchronize()
+        t = stamps.cpu().numpy().astype(np.float64)
+        eq4 = t[0][t[0][:, 0] > 0]
+        scan = t[1][: nblk * waves]
+        fold = t[2][t[2][:, 0] > 0]
+        t0 = eq4[:, 0].min()
+        row = {"eq4_first_entry": 0.0, "eq4_last_end": (eq4[:, 8].max() - t0) * tick_us}
+        for slot in (0, 1, 2, 3, 4, 5, 6, 7, 8):
+            col = scan[:, slot]
+            col = col[col > 0]
+            if len(col):
+                row[f"scan_{names[slot]}_first"] = (col.min() - t0) * tick_us
+                row[f"scan_{names[slot]}_median"] = (np.median(col) - t0) * tick_us
+                row[f"scan_{names[slot]}_last"] = (col.max() - t0) * tick_us
+        for (s0, s1) in ((0, 2), (2, 3), (3, 4), (4, 5), (5, 7), (7, 8)):   # per-wave durations
+            ok = (scan[:, s0] > 0) & (scan[:, s1] > 0)
+            if ok.any():
+                dd = (scan[ok, s1] - scan[ok, s0]) * tick_us
+                row[f"scan_wave_{names.get(s0, s0)}_to_{names.get(s1, s1)}_median"] = float(np.median(dd))
+                row[f"scan_wave_{names.get(s0, s0)}_to_{names.get(s1, s1)}_max"] = float(dd.max())
+        for slot in (0, 9, 10, 11, 5, 7, 8):
+            col = fold[:, slot]
+            col = col[col > 0]
+            if len(col):
+                row[f"fold_{names[slot]}_first"] = (col.min() - t0) * tick_us
+                row[f"fold_{names[slot]}_last"] = (col.max() - t0) * tick_us
+        rows.append(row)
+        stamps.zero_()
+    keys = list(rows[0].keys())
+    med = {k: float(np.median([r[k] for r in rows if k in r])) for k in keys}
+    for k in keys:
+        print(f"{k:28s} {med[k]:8.2f} us", file=sys.stderr)
+    print(json.dumps({
+        "metric": "in-kernel wall-clock stamps of one step (Eq. 4, scan, fold), microseconds after the step's first wave",
+        "value": med["fold_end_last"], "unit": "us", "n_gpus": 1, "higher_is_better": False, "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch=1, codes {cfg.codes}, seed {cfg.seed}",
+                   "scan_workgroups": nblk, "waves_per_workgroup": waves, "samples": args.breakdown_samples,
+                   "steps_per_sample": args.breakdown_steps, "tick_us": tick_us},
+        "stamps_us": med}))
+
+
+def yardsticks_mode(args):
+    """What this machine gives: the cost of an empty launch, a plain streaming read of 10 MB and 400 MB, and random
+    gathers from LDS (4-, 8- and 16-byte words, 8 KB and 32 KB tables, 8 and 16 waves per CU) against the conflict-free
+    case.  These are the denominators the scan kernels' figures are held to."""
+    import torch
+    from paper_2408_09992_amd import binding as pq
+
+    props = torch.cuda.get_device_properties(0)
+    cus = props.multi_processor_count
+    out = {"compute_units": cus, "nominal_clock_GHz": 2.4}
+    for _ in range(3):
+        pq.pq_measure_empty_launch(256, 512, 500)
+    out["empty_launch_us"] = {f"{blocks}x{threads}": sorted(pq.pq_measure_empty_launch(blocks, threads, 1000) for _ in range(5))[2] * 1e3
+                              for (blocks, threads) in ((1, 64), (256, 512), (512, 512), (256, 1024))}
+    reads = {}
+    for nbytes in (10_240_000, 400_000_000):
+        buf = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        pq.pq_read_bandwidth_profile(buf, 20)
+        ms = sorted(pq.pq_read_bandwidth_profile(buf, 50) for _ in range(5))[2]
+        reads[str(nbytes)] = {"us": ms * 1e3, "GBps": nbytes / (ms * 1e-3) / 1e9}
+        del buf
+    out["stream_read"] = reads
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    gathers = []
+    rounds = 16 * 256
+    for width in (4, 8, 16):
+        for table in (8192, 32768):
+            for threads, blocks_per_cu in ((512, 1), (1024, 1), (512, 2)):
+                for cf in (False, True):
+                    blocks = cus * blocks_per_cu
+                    pq.pq_measure_lds_gather(width, table, rounds, cf, blocks, threads, 3, sink)
+                    ms = sorted(pq.pq_measure_lds_gather(width, table, rounds, cf, blocks, threads, 10, sink) for _ in range(5))[2]
+                    lane_reads = blocks * threads * rounds
+                    per_ns = lane_reads / (ms * 1e6)
+                    g = {"width": width, "table_bytes": table, "threads": threads, "workgroups_per_cu": blocks_per_cu,
+                         "conflict_free": cf, "us": ms * 1e3, "lane_reads_per_ns": per_ns,
+                         "lane_reads_per_clk_per_cu": per_ns / 2.4 / cus, "GBps": per_ns * width,
+                         "bytes_per_clk_per_cu": per_ns * width / 2.4 / cus}
+                    gathers.append(g)
+                    print(f"lds gather w={width:2d} table={table:6d} {threads:4d}x{blocks_per_cu} {'conflict-free' if cf else 'random       '} "
+                          f"{ms * 1e3:8.1f} us  {g['lane_reads_per_clk_per_cu']:6.2f} lane reads/clk/CU  {g['bytes_per_clk_per_cu']:6.1f} B/clk/CU  "
+                          f"{g['GBps'] / 1e3:6.1f} TB/s", file=sys.stderr, flush=True)
+    # replicated tables (the scan's layout for one query): 2048 entries of 4 bytes, C copies side by side
+    for copies in (1, 2, 4, 8, 16):
+        for threads, blocks_per_cu in ((512, 1), (1024, 1)):
+            table, blocks = 8192 * copies, cus * blocks_per_cu
+            pq.pq_measure_lds_gather(4, table, rounds, False, blocks, threads, 3, sink, copies=copies)
+            ms = sorted(pq.pq_measure_lds_gather(4, table, rounds, False, blocks, threads, 10, sink, copies=copies) for _ in range(5))[2]
+            per_ns = blocks * threads * rounds / (ms * 1e6)
+            g = {"width": 4, "table_bytes": table, "copies": copies, "threads": threads, "workgroups_per_cu": blocks_per_cu,
+                 "conflict_free": False, "us": ms * 1e3, "lane_reads_per_ns": per_ns,
+                 "lane_reads_per_clk_per_cu": per_ns / 2.4 / cus, "GBps": per_ns * 4, "bytes_per_clk_per_cu": per_ns * 4 / 2.4 / cus}
+            gathers.append(g)
+            print(f"lds gather w= 4 entries=2048 copies={copies:2d} {threads:4d}x{blocks_per_cu} random  {ms * 1e3:8.1f} us  "
+                  f"{g['lane_reads_per_clk_per_cu']:6.2f} lane reads/clk/CU", file=sys.stderr, flush=True)
+    out["lds_gather"] = gathers
+    best16 = max(g["GBps"] for g in gathers if g["width"] == 16 and not g["conflict_free"])
+    print(json.dumps({"metric": "machine yardsticks (empty launch, streaming read, random LDS gathers)", "value": best16,
+                      "unit": "GB/s (random 16-byte LDS gathers, best configuration)", "n_gpus": 1, "higher_is_better": True,
+                      "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+                      "config": {"workload": "yardsticks: no catalogue; hashed offsets into an LDS table"}, "yardsticks": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -317,6 +447,12 @@ def main():
                     "list sizes on --config at batch 1")
     ap.add_argument("--wide", action="store_true", help="time codebooks with 16-bit sub-ids (pq_score_topk_u16) over "
                     "alphabet and catalogue sizes at batch 1")
+    ap.add_argument("--breakdown", action="store_true", help="in-kernel wall-clock stamps of the three launches of one "
+                    "single-query step on --config (m = 8 only)")
+    ap.add_argument("--breakdown-samples", type=int, default=20)
+    ap.add_argument("--breakdown-steps", type=int, default=50)
+    ap.add_argument("--yardsticks", action="store_true", help="machine yardsticks: empty launch, plain streaming read, "
+                    "random gathers from LDS")
     ap.add_argument("--sweep-max-bytes", type=float, default=16e9, help="largest code matrix the sweep allocates")
     ap.add_argument("--sweep-check-bytes", type=float, default=1e9,
                     help="largest code matrix whose result the sweep checks against the oracle")
@@ -335,6 +471,12 @@ def main():
         return
     if args.wide:
         wide_mode(args)
+        return
+    if args.breakdown:
+        breakdown_mode(args)
+        return
+    if args.yardsticks:
+        yardsticks_mode(args)
         return
 
     import numpy as np

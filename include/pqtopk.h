@@ -16,6 +16,10 @@
  *     until the enqueued work has finished.  `codes` must be 16-byte aligned, every float / int array 4-byte
  *     aligned (16-byte preferred).  The library allocates nothing, frees nothing and never synchronises: it
  *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is the default stream) and returns.
+ *     (The measurement aids of pqtopk_measure.h, which are not part of the product path, are the exception: they
+ *     time their own launches and so create events and wait for the stream.)
+ *   - Grids and workspace sizes are laid out for the 256 compute units of an MI355X.  On a GPU with another number
+ *     of compute units every result is the same; only the speed differs.
  *   - Return value: PQ_OK (0) or a negative PQ_ERR_* code.  Arguments are validated on the host before any HIP
  *     call; on an argument error nothing is enqueued and no output is touched.
  *   - Arithmetic: fp32, round to nearest even, no flush to zero.  Eq. 4 is a left-to-right chain of fused
@@ -194,31 +198,6 @@ int pq_reconstruct_items(const uint8_t* codes, const float* centroids, long long
  */
 int pq_default_scores(const float* W, const float* queries, long long N, int B, int d, float* scores, long long ld,
                       void* stream);
-
-/*
- * Measurement aid: enqueues the catalogue scan kernel of pq_score_topk() (the kernel that streams `codes`) once
- * untimed and then `iters` times back to back between two HIP events on `stream`, enqueues the fold so the outputs
- * are those of pq_score_topk(), waits for the stream, and stores elapsed / iters in milliseconds in *scan_ms (host
- * pointer): the scan kernel's mean duration including its launch gap.  The one entry point that synchronises and
- * that creates / destroys HIP events.  Same errors as pq_score_topk(); PQ_ERR_SHAPE if iters < 1.
- */
-int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                          int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
-                          void* stream, int iters, float* scan_ms);
-
-/* pq_score_topk_profile() for 16-bit sub-ids: times the scan kernel of pq_score_topk_u16(). */
-int pq_score_topk_u16_profile(const uint16_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                              int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
-                              void* stream, int iters, float* scan_ms);
-
-/*
- * Measurement aid: a plain streaming-read kernel (16-byte loads and nothing else) over `bytes` bytes at `data`
- * (device pointer, 16-byte aligned), launched once untimed and then `iters` times back to back between two HIP events;
- * *read_ms (host pointer) receives elapsed / iters in milliseconds.  The yardstick for the scan's HBM rate: what this
- * machine delivers to a kernel that does nothing but read.  Synchronises; creates and destroys two HIP events.
- * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE (bytes < 16, iters < 1), PQ_ERR_ALIGN, PQ_ERR_HIP.
- */
-int pq_read_bandwidth_profile(const void* data, size_t bytes, void* stream, int iters, float* read_ms);
 
 /* Text for a PQ_* code; for PQ_ERR_HIP the text of the most recent HIP error seen by this thread. */
 const char* pq_strerror(int code);

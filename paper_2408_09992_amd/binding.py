@@ -69,6 +69,14 @@ def lib() -> ctypes.CDLL:
         L.pq_default_scores.restype = I
         L.pq_read_bandwidth_profile.argtypes = [P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
         L.pq_read_bandwidth_profile.restype = I
+        L.pq_measure_empty_launch.argtypes = [I, I, P, I, ctypes.POINTER(ctypes.c_float)]
+        L.pq_measure_empty_launch.restype = I
+        L.pq_measure_lds_gather.argtypes = [I, I, I, I, I, I, I, P, P, I, ctypes.POINTER(ctypes.c_float)]
+        L.pq_measure_lds_gather.restype = I
+        L.pq_measure_force_general.argtypes = [I]
+        L.pq_measure_force_general.restype = I
+        L.pq_measure_step_stamps.argtypes = [P, P, P, LL, I, I, I, I, I, P, P, P, P, SZ, P, SZ, ctypes.POINTER(I * 2), P]
+        L.pq_measure_step_stamps.restype = I
         L.pq_strerror.argtypes = [I]
         L.pq_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -324,6 +332,53 @@ def pq_read_bandwidth_profile(buf: torch.Tensor, iters: int) -> float:
     if rc != PQ_OK:
         raise PQError(rc, "pq_read_bandwidth_profile")
     return float(ms.value)
+
+
+def pq_measure_empty_launch(blocks: int, threads: int, iters: int) -> float:
+    """Mean cost (ms) of launching an empty kernel on that grid, back to back on the current stream."""
+    ms = ctypes.c_float(0.0)
+    rc = lib().pq_measure_empty_launch(blocks, threads, _stream(), iters, ctypes.byref(ms))
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_measure_empty_launch")
+    return float(ms.value)
+
+
+def pq_measure_lds_gather(width: int, table_bytes: int, rounds: int, conflict_free: bool, blocks: int, threads: int,
+                          iters: int, sink: torch.Tensor, copies: int = 1) -> float:
+    """Mean duration (ms) of a launch in which every lane reads `rounds` words of `width` bytes from a table in LDS."""
+    ms = ctypes.c_float(0.0)
+    rc = lib().pq_measure_lds_gather(width, table_bytes, rounds, int(conflict_free), copies, blocks, threads, sink.data_ptr(),
+                                     _stream(), iters, ctypes.byref(ms))
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_measure_lds_gather")
+    return float(ms.value)
+
+
+def pq_measure_force_general(mask: int) -> int:
+    """Bit 0: scans avoid the short kernel; bit 1: folds avoid the small-K fold; 0: the library's choice.  Returns the
+    previous mask."""
+    return int(lib().pq_measure_force_general(int(mask)))
+
+
+PQ_STAMP_SLOTS, PQ_STAMP_RECORDS = 16, 8192
+
+
+def pq_measure_step_stamps(queries: torch.Tensor, centroids: torch.Tensor, codes: torch.Tensor, K: int, S: torch.Tensor,
+                           out_ids: torch.Tensor, out_scores: torch.Tensor, workspace: torch.Tensor,
+                           stamps: torch.Tensor) -> Tuple[int, int]:
+    """One step (Eq. 4, scan, fold) with the stamping instances of the kernels; `stamps` is an int64 device tensor of
+    shape [3][PQ_STAMP_RECORDS][PQ_STAMP_SLOTS], zeroed by the caller.  Returns (scan workgroups, waves per workgroup)."""
+    N, m = codes.shape
+    B, d = queries.shape
+    b = centroids.shape[1]
+    grid = (ctypes.c_int * 2)()
+    rc = lib().pq_measure_step_stamps(queries.data_ptr(), centroids.data_ptr(), codes.data_ptr(), N, B, d, m, b, K,
+                                      S.data_ptr(), out_ids.data_ptr(), out_scores.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel(), stamps.data_ptr(), stamps.numel() * stamps.element_size(),
+                                      ctypes.byref(grid), _stream())
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_measure_step_stamps")
+    return int(grid[0]), int(grid[1])
 
 
 class PreparedSubitemScores:

@@ -1,6 +1,7 @@
 // Constants, cross-lane helpers (DPP), wave-level reductions and the bitonic sort shared by every kernel.
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// fold.hpp, comparison.hpp.
 #pragma once
 
 constexpr int kWave = 64;
@@ -21,6 +22,8 @@ constexpr int kSharedFloorMinRounds = 6;          // single-query scan: rounds p
 constexpr int kSharedFloorMinRoundsLargeK = 3;    // ... for K >= 32
 constexpr int kFoldRegs = 12;                     // keys per thread the fold keeps in registers (6144 per query)
 constexpr int kFoldWideRegs = 13;                 // ... and of the 1024-thread fold (13,312 keys)
+constexpr int kFoldSmallRegs = 6;                 // keys per thread of the small-K fold (3072 per query) ...
+constexpr int kFoldSmallRegsMax = 12;             // ... and of its larger instance (6144)
 constexpr int kChunkKeys = 2048;                  // keys the grid-level fold takes per pass (4 per thread)
 constexpr size_t kMaxLdsBytes = 160 * 1024;       // LDS per workgroup on gfx950
 constexpr int kAssumedCUs = 256;                  // MI355X; only used to size grids and the workspace
@@ -86,18 +89,47 @@ __device__ __forceinline__ void wave_minmax(float& mn, float& mx) {
     mx = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
 }
 
-// A floor for a wave's top K (K in 1..64): a value that at least K of the lanes' values v reach, found by bisection
-// between the wave's extremes with one ballot per step (so close below the K-th largest, not exactly it).  Lanes
-// with nothing to offer pass -inf; if fewer than K lanes have a value the floor is -inf.  Same result in every lane.
+// min and max over the wave of unsigned values, in every lane
+__device__ __forceinline__ void wave_minmax_u32(uint32_t& mn, uint32_t& mx) {
+    mn = min(mn, dpp_u32<kDppQuadSwap1>(mn, mn));       mx = max(mx, dpp_u32<kDppQuadSwap1>(mx, mx));
+    mn = min(mn, dpp_u32<kDppQuadSwap2>(mn, mn));       mx = max(mx, dpp_u32<kDppQuadSwap2>(mx, mx));
+    mn = min(mn, dpp_u32<kDppRowHalfMirror>(mn, mn));   mx = max(mx, dpp_u32<kDppRowHalfMirror>(mx, mx));
+    mn = min(mn, dpp_u32<kDppRowMirror>(mn, mn));       mx = max(mx, dpp_u32<kDppRowMirror>(mx, mx));
+    // every row of 16 lanes now holds its own extremes; combine the four rows through scalar reads
+    const uint32_t m0 = (uint32_t)__builtin_amdgcn_readlane((int)mn, 0), m1 = (uint32_t)__builtin_amdgcn_readlane((int)mn, 16);
+    const uint32_t m2 = (uint32_t)__builtin_amdgcn_readlane((int)mn, 32), m3 = (uint32_t)__builtin_amdgcn_readlane((int)mn, 48);
+    const uint32_t x0 = (uint32_t)__builtin_amdgcn_readlane((int)mx, 0), x1 = (uint32_t)__builtin_amdgcn_readlane((int)mx, 16);
+    const uint32_t x2 = (uint32_t)__builtin_amdgcn_readlane((int)mx, 32), x3 = (uint32_t)__builtin_amdgcn_readlane((int)mx, 48);
+    mn = min(min(m0, m1), min(m2, m3));
+    mx = max(max(x0, x1), max(x2, x3));
+}
+
+__device__ __forceinline__ float float_of_orderable(uint32_t u) { return __uint_as_float(u ^ ((u >> 31) ? 0x80000000u : 0xFFFFFFFFu)); }
+
+// A floor for a wave's top K (K in 1..64): a value that at least K of the lanes' values v reach, found by searching
+// between the wave's extremes (so close below the K-th largest, not exactly it).  Each of the STEPS steps cuts the
+// interval into four with three thresholds whose ballots are independent of one another: a wave on its own issues an
+// instruction only every seven cycles or so, dependent or not, so what counts is the number of instructions, and a
+// four-way step yields two bits for less than two halvings cost.  (The extremes are taken on the values'
+// order-preserving integer images: integer minima need no NaN handling.)  Lanes with nothing to offer pass -inf; if
+// fewer than K lanes have a value the floor is -inf.  Same result in every lane.
+template <int STEPS = 6>
 __device__ __forceinline__ float wave_floor_for_k(float v, int K) {
     const float ninf = -__builtin_inff();
     if (__popcll(__ballot(v > ninf)) < K) return ninf;
-    float lo = v > ninf ? v : __builtin_inff(), hi = v;
-    wave_minmax(lo, hi);                                      // at least K lanes reach lo
+    const uint32_t o = orderable_bits(v);
+    uint32_t olo = v > ninf ? o : 0xFFFFFFFFu, ohi = o;
+    wave_minmax_u32(olo, ohi);
+    float lo = float_of_orderable(olo), hi = float_of_orderable(ohi);   // at least K lanes reach lo
 #pragma unroll
-    for (int step = 0; step < 12; ++step) {
-        const float mid = lo + (hi - lo) * 0.5f;
-        if (__popcll(__ballot(v >= mid)) >= K) lo = mid; else hi = mid;
+    for (int step = 0; step < STEPS; ++step) {
+        const float range = hi - lo;
+        const float t1 = __builtin_fmaf(range, 0.25f, lo), t2 = __builtin_fmaf(range, 0.5f, lo), t3 = __builtin_fmaf(range, 0.75f, lo);
+        const bool r1 = __popcll(__ballot(v >= t1)) >= K, r2 = __popcll(__ballot(v >= t2)) >= K,
+                   r3 = __popcll(__ballot(v >= t3)) >= K;        // (t1 <= t2 <= t3, so r3 implies r2 implies r1)
+        const float new_lo = r3 ? t3 : (r2 ? t2 : (r1 ? t1 : lo));
+        hi = !r1 ? t1 : (!r2 ? t2 : (!r3 ? t3 : hi));
+        lo = new_lo;
     }
     return lo;
 }
@@ -128,5 +160,33 @@ __device__ void bitonic_sort_desc(uint64_t* a, int n, int tid, int nthr) {
             }
             if (BLOCK) __syncthreads(); else wave_sync();
         }
+    }
+}
+
+// Slots of a wave's stamp record (measurement instances of the kernels; wall_clock64() ticks, lane 0 of the wave).
+// A slot a kernel does not pass stays as the caller left it.
+constexpr int kStampSlots = 16;
+enum StampSlot {
+    kStampEntry = 0,        // first instruction of the wave
+    kStampRequested = 1,    // scan: table values and the first rounds of codes requested
+    kStampTables = 2,       // scan: tables in LDS (after the workgroup's barrier)
+    kStampCodes = 3,        // scan: the first rounds' codes have arrived (the stamped instance waits for them here)
+    kStampScored = 4,       // scan: short scans: all items scored; longer ones: first round scored
+    kStampOffered = 5,      // scan: short scans: the wave's candidates are in the candidate array; longer: first cut found
+    kStampStreamed = 6,     // scan: all rounds streamed (longer scans only)
+    kStampSelected = 7,     // scan: the workgroup's K best are ranked
+    kStampEnd = 8,          // last instruction before the wave ends
+    kStampLoaded = 9,       // fold: the lists' keys are in registers
+    kStampCut = 10,         // fold: histogram cut found
+    kStampCollected = 11,   // fold: candidates collected
+};
+template <bool STAMP>
+__device__ __forceinline__ void stamp(uint64_t* record, int slot, int lane) {
+    if constexpr (STAMP) {
+        // (nothing is scheduled across a stamp: what precedes it in the source has been issued, and whatever that needed
+        // from memory or LDS has arrived, when the clock is read)
+        __builtin_amdgcn_sched_barrier(0);
+        if (lane == 0) record[slot] = wall_clock64();
+        __builtin_amdgcn_sched_barrier(0);
     }
 }

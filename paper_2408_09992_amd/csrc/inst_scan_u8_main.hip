@@ -3,4 +3,5 @@
 #include "kernels.hpp"
 namespace pqk {
 PQ_SCAN_INSTANCES_U8_MAIN(PQ_SCAN_DEFINE)
+PQ_SCAN_INSTANCES_STAMPED(PQ_SCAN_DEFINE6)
 }

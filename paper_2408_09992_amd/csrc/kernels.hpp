@@ -13,7 +13,9 @@ namespace pqk {
 #include "common.hpp"
 #include "subitem_scores.hpp"
 #include "topk_parts.hpp"
+#include "select_small.hpp"
 #include "scan_single.hpp"
+#include "scan_short.hpp"
 #include "scan_batched.hpp"
 #include "fold.hpp"
 #ifndef PQ_INSTANCE_TU
@@ -41,11 +43,31 @@ namespace pqk {
     X(4, 1, kThreads, 2, true) X(4, 1, kBigThreads, 2, false) X(4, 1, kThreads, 2, false) \
     X(8, 1, kThreads, 2, true) X(8, 1, kBigThreads, 2, false) X(8, 1, kThreads, 2, false) \
     X(16, 1, kThreads, 2, true) X(16, 1, kBigThreads, 2, false) X(16, 1, kThreads, 2, false)
+// measurement instances (wall-clock stamps per wave) of the two kernels the named single-query workloads run
+#define PQ_SCAN_INSTANCES_STAMPED(X) X(8, 1, kThreads, 1, false, true) X(8, kTableCopies, kBigThreads, 1, false, true)
+// scan_short_kernel<M, U, NT, STAMP> instances: every number of units per thread up to short_max_units(M), in two
+// translation units; measurement instances for m = 8
+#define PQ_SHORT_U(X, M, U) X(M, U, kThreads, false)
+#define PQ_SHORT_INSTANCES_A(X) \
+    PQ_SHORT_U(X, 8, 1) PQ_SHORT_U(X, 8, 2) PQ_SHORT_U(X, 8, 3) PQ_SHORT_U(X, 8, 4) PQ_SHORT_U(X, 8, 5) PQ_SHORT_U(X, 8, 6) \
+    PQ_SHORT_U(X, 8, 7) PQ_SHORT_U(X, 8, 8) \
+    X(8, 1, kThreads, true) X(8, 2, kThreads, true) X(8, 3, kThreads, true) X(8, 4, kThreads, true) X(8, 5, kThreads, true) \
+    X(8, 6, kThreads, true) X(8, 7, kThreads, true) X(8, 8, kThreads, true) \
+    PQ_SHORT_U(X, 1, 1) PQ_SHORT_U(X, 1, 2) PQ_SHORT_U(X, 2, 1) PQ_SHORT_U(X, 2, 2) \
+    PQ_SHORT_U(X, 4, 1) PQ_SHORT_U(X, 4, 2) PQ_SHORT_U(X, 4, 3) PQ_SHORT_U(X, 4, 4)
+#define PQ_SHORT_INSTANCES_B(X) \
+    PQ_SHORT_U(X, 16, 1) PQ_SHORT_U(X, 16, 2) PQ_SHORT_U(X, 16, 3) PQ_SHORT_U(X, 16, 4) PQ_SHORT_U(X, 16, 5) \
+    PQ_SHORT_U(X, 16, 6) PQ_SHORT_U(X, 16, 7) PQ_SHORT_U(X, 16, 8) \
+    PQ_SHORT_U(X, 32, 1) PQ_SHORT_U(X, 32, 2) PQ_SHORT_U(X, 32, 3) PQ_SHORT_U(X, 32, 4) PQ_SHORT_U(X, 64, 1) PQ_SHORT_U(X, 64, 2)
 // the batched kernel
 #define PQ_TILED_INSTANCES(X) X(8) X(16)
 
 #define PQ_SCAN_DEFINE(M, C, NT, CW, GL) template __global__ void scan_topk_kernel<M, C, NT, CW, GL>(ScanArgs);
 #define PQ_SCAN_EXTERN(M, C, NT, CW, GL) extern PQ_SCAN_DEFINE(M, C, NT, CW, GL)
+#define PQ_SCAN_DEFINE6(M, C, NT, CW, GL, ST) template __global__ void scan_topk_kernel<M, C, NT, CW, GL, ST>(ScanArgs);
+#define PQ_SCAN_EXTERN6(M, C, NT, CW, GL, ST) extern PQ_SCAN_DEFINE6(M, C, NT, CW, GL, ST)
+#define PQ_SHORT_DEFINE(M, U, NT, ST) template __global__ void scan_short_kernel<M, U, NT, ST>(ScanArgs);
+#define PQ_SHORT_EXTERN(M, U, NT, ST) extern PQ_SHORT_DEFINE(M, U, NT, ST)
 #define PQ_TILED_DEFINE(M) template __global__ void scan_topk_tiled_kernel<M>(ScanArgs, int);
 #define PQ_TILED_EXTERN(M) extern PQ_TILED_DEFINE(M)
 
@@ -55,6 +77,9 @@ PQ_SCAN_INSTANCES_U8_MAIN(PQ_SCAN_EXTERN)
 PQ_SCAN_INSTANCES_U8_WIDE(PQ_SCAN_EXTERN)
 PQ_SCAN_INSTANCES_GENERIC(PQ_SCAN_EXTERN)
 PQ_SCAN_INSTANCES_U16(PQ_SCAN_EXTERN)
+PQ_SCAN_INSTANCES_STAMPED(PQ_SCAN_EXTERN6)
+PQ_SHORT_INSTANCES_A(PQ_SHORT_EXTERN)
+PQ_SHORT_INSTANCES_B(PQ_SHORT_EXTERN)
 PQ_TILED_INSTANCES(PQ_TILED_EXTERN)
 #endif
 

@@ -31,7 +31,11 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "pqtopk.h"
+#include "pqtopk_measure.h"
 #include "kernels.hpp"
 
 // Built-in scratch of pq_score_topk_static(): device memory, one copy per GPU, held until the process ends.  Host code
@@ -47,6 +51,9 @@ using namespace pqk;
 // host side
 
 thread_local char g_hip_error[256] = "no HIP error recorded";
+
+// pq_measure_force_general(): bit 0 keeps calls off scan_short_kernel, bit 1 off fold_small_kernel (0: the product's choice)
+std::atomic<int> g_force_general{0};
 
 int record_hip(hipError_t e) {
     if (e == hipSuccess) return PQ_OK;
@@ -83,6 +90,8 @@ struct ScanPlan {
     size_t fold_lds;
     bool vec;
     bool glut;       // two-byte sub-ids: the m x b table does not fit LDS and is read from device memory
+    bool short_scan; // scan_short_kernel: every workgroup's share fits its registers, K small
+    int short_units; // ... units (code vectors, or items for m = 32, 64) a thread holds
 };
 
 bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32 || m == 64; }
@@ -235,6 +244,34 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
         }
     }
     p.fold_lds = fold_lds_bytes(p.stage_keys, p.candmax, K);
+    // Single-query scans (one query per workgroup row) with a small K whose share per thread fits a few registers run
+    // the short kernel: scores stay in registers, one selection, a few KB of code.  Its grid is spread as thin as the
+    // CUs allow (one workgroup per CU over all queries): a workgroup's time is the lookups of its share plus a fixed
+    // selection, so the fewer units a thread holds the better, and the small fold takes the 256 lists in its stride.
+    p.short_scan = false;
+    p.short_units = 0;
+    if (cw == 1 && p.vec && !generic && !p.tiled && K <= kSmallKMax) {
+        long long nb = kAssumedCUs / B;
+        if (nb < 1) nb = 1;
+        const long long thin = (units + kThreads - 1) / kThreads;          // workgroups if every thread held one unit
+        if (nb > thin) nb = thin;
+        const long long per_slot = (long long)kThreads * nb;               // units one slot of all threads covers
+        const long long slots = (units + per_slot - 1) / per_slot;
+        if (slots <= short_max_units(m)) {
+            // (the general kernel takes the same grid when the measurement hook keeps a call off the short one)
+            p.nblk = (int)nb;
+            p.copies = 1;
+            p.big = false;
+            p.scan_dyn_lds = scan_lds_bytes(0, p.cap, p.candmax, K, kWaves);
+            p.scan_lds = p.scan_dyn_lds + lut_floats * sizeof(float);
+            if (!(g_force_general.load(std::memory_order_relaxed) & 1)) {
+                p.short_scan = true;
+                p.short_units = (int)slots;
+                p.scan_dyn_lds = 0;
+                p.scan_lds = lut_floats * sizeof(float) + sizeof(SmallSelectLds<kThreads>);
+            }
+        }
+    }
     return p;
 }
 
@@ -271,11 +308,33 @@ int check_topk_args(const void* codes, const void* S, long long N, int B, int m,
     return PQ_OK;
 }
 
+constexpr int kMaxDevices = 64;
+
+// Kernels that take more than 64 KB of dynamic LDS need the limit raised, per kernel and device: done the first time a
+// kernel asks for that much (and again only if it later asks for more), not on every call.
+struct LdsGrant { const void* fn; int dev; size_t bytes; };
+hipError_t allow_lds_once(const void* fn, size_t bytes) {
+    static std::mutex mu;
+    static LdsGrant grants[512];
+    static int n_grants = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    LdsGrant* g = nullptr;
+    for (int i = 0; i < n_grants && g == nullptr; ++i)
+        if (grants[i].fn == fn && grants[i].dev == dev) g = &grants[i];
+    if (g != nullptr && g->bytes >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    if (g == nullptr && n_grants < 512) g = &grants[n_grants++];
+    if (g != nullptr) *g = LdsGrant{fn, dev, bytes};           // (table full: the attribute is simply set again next time)
+    return hipSuccess;
+}
 template <typename KernelT>
 hipError_t allow_lds(KernelT kernel, size_t bytes) {
     if (bytes <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)bytes);
+    return allow_lds_once(reinterpret_cast<const void*>(kernel), bytes);
 }
 
 template <int M, int CW = 1>
@@ -313,14 +372,57 @@ hipError_t launch_scan(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t 
     return hipGetLastError();
 }
 
+template <int M, int U>
+hipError_t launch_short_units(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    if constexpr (U <= short_max_units(M)) {
+        if constexpr (M == 8) {
+            if (a.stamps != nullptr) {
+                hipLaunchKernelGGL((scan_short_kernel<M, U, kThreads, true>), dim3(p.nblk, B), dim3(kThreads), 0, st, a);
+                return hipGetLastError();
+            }
+        }
+        hipLaunchKernelGGL((scan_short_kernel<M, U, kThreads, false>), dim3(p.nblk, B), dim3(kThreads), 0, st, a);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;                         // (the plan never asks for it)
+    }
+}
+template <int M>
+hipError_t launch_short_m(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    switch (p.short_units) {
+        case 1: return launch_short_units<M, 1>(p, a, B, st);
+        case 2: return launch_short_units<M, 2>(p, a, B, st);
+        case 3: return launch_short_units<M, 3>(p, a, B, st);
+        case 4: return launch_short_units<M, 4>(p, a, B, st);
+        case 5: return launch_short_units<M, 5>(p, a, B, st);
+        case 6: return launch_short_units<M, 6>(p, a, B, st);
+        case 7: return launch_short_units<M, 7>(p, a, B, st);
+        case 8: return launch_short_units<M, 8>(p, a, B, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_short(const ScanPlan& p, const ScanArgs& a, int B, int m, hipStream_t st) {
+    switch (m) {
+        case 1: return launch_short_m<1>(p, a, B, st);
+        case 2: return launch_short_m<2>(p, a, B, st);
+        case 4: return launch_short_m<4>(p, a, B, st);
+        case 8: return launch_short_m<8>(p, a, B, st);
+        case 16: return launch_short_m<16>(p, a, B, st);
+        case 32: return launch_short_m<32>(p, a, B, st);
+        default: return launch_short_m<64>(p, a, B, st);
+    }
+}
+
 // Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
 // `subset` / `n_items`: candidate list (then N is its length and the plan is a generic one) or nullptr / N
 // `cw`: bytes per sub-id (2: `codes` holds uint16 values)
 int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
-                 void* workspace, hipStream_t st, const int* subset = nullptr, long long n_items = 0, int cw = 1) {
+                 void* workspace, hipStream_t st, const int* subset = nullptr, long long n_items = 0, int cw = 1,
+                 uint64_t* stamps = nullptr) {
     ScanArgs a;
     a.codes = codes; a.S = S; a.N = N; a.m = m; a.b = b; a.K = K;
     a.subset = subset; a.n_items = (uint32_t)(subset ? n_items : N);
+    a.stamps = stamps;
     a.cap = p.cap; a.candmax = p.candmax;
     // Batched kernel, small K: lists are cut back to their K best once they pass 2K + 8 keys, short enough to rank in
     // one pass; from K = 13 on its shared floors and final filter do better without (K = 16: 53 -> 48 us, K = 28:
@@ -329,6 +431,26 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     a.prune_at = (p.tiled && K <= 12) ? 2 * K + 8 : 0;
     a.ws_keys = static_cast<uint64_t*>(workspace);
     hipError_t e;
+    if (p.short_scan) {
+        if (stamps != nullptr && m != 8) return PQ_ERR_UNSUPPORTED;
+        return record_hip(launch_short(p, a, B, m, st));
+    }
+    if (stamps != nullptr) {
+        // the measurement instances exist for the single-query m = 8 kernels only
+        if (p.tiled || cw != 1 || !p.vec || m != 8 || p.big != (p.copies == kTableCopies)) return PQ_ERR_UNSUPPORTED;
+        if (p.copies == kTableCopies) {
+            e = allow_lds(scan_topk_kernel<8, kTableCopies, kBigThreads, 1, false, true>, p.scan_dyn_lds);
+            if (e == hipSuccess)
+                hipLaunchKernelGGL((scan_topk_kernel<8, kTableCopies, kBigThreads, 1, false, true>), dim3(p.nblk, B),
+                                   dim3(kBigThreads), p.scan_dyn_lds, st, a);
+        } else {
+            e = allow_lds(scan_topk_kernel<8, 1, kThreads, 1, false, true>, p.scan_dyn_lds);
+            if (e == hipSuccess)
+                hipLaunchKernelGGL((scan_topk_kernel<8, 1, kThreads, 1, false, true>), dim3(p.nblk, B), dim3(kThreads),
+                                   p.scan_dyn_lds, st, a);
+        }
+        return record_hip(e == hipSuccess ? hipGetLastError() : e);
+    }
     if (p.tiled) {
         const dim3 grid(p.nblk, (B + kQ - 1) / kQ);
         if (m == 8) {
@@ -386,7 +508,8 @@ size_t fold_area_keys(int nblk, int B, int K) {
 
 // Enqueue the fold of the workspace's lists into the outputs: one launch when a query's lists fit one workgroup's
 // registers, else levels of launches that each fold groups of lists into one list per group.
-int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st) {
+int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids, float* out_scores, hipStream_t st,
+                 uint64_t* stamps = nullptr) {
     hipError_t e = allow_lds(fold_topk_kernel<kThreads, kFoldRegs>, p.fold_lds);
     if (e == hipSuccess) e = allow_lds(fold_topk_kernel<kBigThreads, kFoldWideRegs>, p.fold_lds);
     if (e != hipSuccess) return record_hip(e);
@@ -403,6 +526,27 @@ int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids,
         f.stage_keys = p.stage_keys; f.candmax = p.candmax;
         f.out_keys = groups == 1 ? nullptr : area[1 - src];
         f.out_ids = out_ids; f.out_scores = out_scores;
+        f.stamps = stamps;
+        if (groups == 1 && K <= kSmallKMax && (long long)nlists * K <= (long long)kThreads * kFoldSmallRegsMax &&
+            !(g_force_general.load(std::memory_order_relaxed) & 2)) {
+            // small K, few keys: the lean fold
+            const bool few = (long long)nlists * K <= (long long)kThreads * kFoldSmallRegs;
+            if (stamps != nullptr) {
+                if (few) hipLaunchKernelGGL((fold_small_kernel<kThreads, kFoldSmallRegs, true>), dim3(1, B), dim3(kThreads), 0, st, f);
+                else hipLaunchKernelGGL((fold_small_kernel<kThreads, kFoldSmallRegsMax, true>), dim3(1, B), dim3(kThreads), 0, st, f);
+            } else {
+                if (few) hipLaunchKernelGGL((fold_small_kernel<kThreads, kFoldSmallRegs, false>), dim3(1, B), dim3(kThreads), 0, st, f);
+                else hipLaunchKernelGGL((fold_small_kernel<kThreads, kFoldSmallRegsMax, false>), dim3(1, B), dim3(kThreads), 0, st, f);
+            }
+            return record_hip(hipGetLastError());
+        }
+        if (stamps != nullptr) {                             // measurement instance: the usual one-launch fold only
+            if (wide || groups != 1) return PQ_ERR_UNSUPPORTED;
+            e = allow_lds(fold_topk_kernel<kThreads, kFoldRegs, true>, p.fold_lds);
+            if (e != hipSuccess) return record_hip(e);
+            hipLaunchKernelGGL((fold_topk_kernel<kThreads, kFoldRegs, true>), dim3(1, B), dim3(kThreads), p.fold_lds, st, f);
+            return record_hip(hipGetLastError());
+        }
         if (wide)
             hipLaunchKernelGGL((fold_topk_kernel<kBigThreads, kFoldWideRegs>), dim3(groups, B), dim3(kBigThreads), p.fold_lds,
                                st, f);
@@ -434,8 +578,6 @@ void launch_subitem(const float* queries, const float* centroids, float* S, int 
 }
 
 // ---- the built-in scratch of pq_score_topk_static(): one array per GPU, held until the process ends
-constexpr int kMaxDevices = 64;
-
 // Device address of `scratch` on the current device.  In host code the array's name is only a handle for
 // hipGetSymbolAddress(): every GPU holds its own copy at its own address, looked up once per device and kept.
 int static_scratch(void** out) {
@@ -555,6 +697,38 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
                           void* stream, int iters, float* scan_ms) {
     return profile_scan(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given, stream, iters,
                         scan_ms, 1);
+}
+
+int pq_measure_force_general(int mask) {
+    return g_force_general.exchange(mask & 3, std::memory_order_relaxed);
+}
+
+int pq_measure_step_stamps(const float* queries, const float* centroids, const uint8_t* codes, long long N, int B,
+                           int d, int m, int b, int K, float* S, int* out_ids, float* out_scores, void* workspace,
+                           size_t workspace_bytes_given, uint64_t* stamps, size_t stamps_bytes, int* scan_grid,
+                           void* stream) {
+    if (!queries || !centroids || !S || !stamps) return PQ_ERR_NULL;
+    int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
+    if (rc != PQ_OK) return rc;
+    if (d < 1 || d % m != 0) return PQ_ERR_SHAPE;
+    if (B != 1 || m != 8 || d / m != 64) return PQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)stamps & 7)) return PQ_ERR_ALIGN;
+    if (stamps_bytes < PQ_STAMP_BYTES) return PQ_ERR_WORKSPACE;
+    static_assert(PQ_STAMP_SLOTS == kStampSlots, "header and kernels agree on the record size");
+    const ScanPlan p = make_plan(N, B, m, K);
+    const int waves = p.big ? kMaxWaves : kWaves;
+    if ((long long)p.nblk * waves > PQ_STAMP_RECORDS || (m * b + kSubThreads - 1) / kSubThreads > PQ_STAMP_RECORDS)
+        return PQ_ERR_UNSUPPORTED;
+    if (scan_grid != nullptr) { scan_grid[0] = p.nblk; scan_grid[1] = waves; }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t section = (size_t)PQ_STAMP_RECORDS * PQ_STAMP_SLOTS;
+    hipLaunchKernelGGL((subitem_scores_kernel<64, true>), dim3((m * b + kSubThreads - 1) / kSubThreads, 1), dim3(kSubThreads), 0,
+                       st, queries, centroids, S, B, d, m, b, stamps);
+    rc = record_hip(hipGetLastError());
+    if (rc != PQ_OK) return rc;
+    rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st, nullptr, 0, 1, stamps + section);
+    if (rc != PQ_OK) return rc;
+    return enqueue_fold(p, B, K, workspace, out_ids, out_scores, st, stamps + 2 * section);
 }
 
 size_t pq_score_topk_u16_workspace_bytes(long long N, int B, int m, int b, int K) {

@@ -1,6 +1,7 @@
 // Eq. 5 + TopK for one query per workgroup (scan_topk_kernel): the catalogue scan of pq_score_topk and pq_score_topk_subset.
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// fold.hpp, comparison.hpp.
 #pragma once
 
 struct ScanArgs {
@@ -14,6 +15,7 @@ struct ScanArgs {
     uint64_t* ws_keys;   // [B][nblk][K]
     const int* subset;   // candidate list V (generic kernel only): unit p stands for item subset[p]; nullptr: V = I
     uint32_t n_items;    // items in the catalogue (bounds the ids read from `subset`)
+    uint64_t* stamps;    // STAMP instances only: wall-clock stamps, kStampSlots per wave (slot names: StampSlot)
 };
 
 // Items a thread holds per round.  M > 0: an item's row of sub-ids takes M bytes (m sub-ids of one byte, or m / 2 of
@@ -296,7 +298,9 @@ __device__ __forceinline__ uint32_t item_of_slot(uint32_t rr, int nblk, int blk,
 // table in dynamic LDS as it lies in memory (b entries per split); the vector instances are those whose rows take
 // 8, 16 or 32 bytes (m = 4, 8, 16).
 // GL (two-byte sub-ids only): the m x b table does not fit LDS and is read where it lies, in device memory (L2).
-template <int M, int C = 1, int NT = kThreads, int CW = 1, bool GL = false>
+// STAMP: measurement instance that also records wall-clock stamps per wave (and waits for the first rounds' codes
+// before scoring, so that waiting and scoring can be told apart).
+template <int M, int C = 1, int NT = kThreads, int CW = 1, bool GL = false, bool STAMP = false>
 __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     constexpr int NW = NT / kWave;
     constexpr int P = M * CW;                                  // bytes of an item's row (0: known at run time only)
@@ -315,6 +319,8 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     constexpr int kItems = Round<P>::kItems;
     constexpr int kUnits = Round<P>::kUnitsPerThread;
     constexpr int kWords = Round<P>::kWords;
+    uint64_t* const rec = STAMP ? a.stamps + (((size_t)q * nblk + blockIdx.x) * NW + wave) * kStampSlots : nullptr;
+    stamp<STAMP>(rec, kStampEntry, lane);
 
     // Vector kernels scan the code vectors that lie wholly inside the catalogue; the fewer than 16 / M items after
     // them (when N * M is not a multiple of 16) are scored one by one at the end.  The generic kernel scans items.
@@ -419,7 +425,13 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     }
     for (int i = tid; i < kBins; i += NT) L.hist[i] = 0;
     if (tid == 0) { ctl->next_unit = kRing * NW; ctl->shared_floor = -__builtin_inff(); ctl->ncand = 0; }
+    stamp<STAMP>(rec, kStampRequested, lane);
     __syncthreads();
+    stamp<STAMP>(rec, kStampTables, lane);
+    if constexpr (STAMP) {
+        __builtin_amdgcn_s_waitcnt(0);                        // every outstanding load: the first rounds' codes are here
+        stamp<STAMP>(rec, kStampCodes, lane);
+    }
     const float* const lut = [&]() -> const float* {
         if constexpr (GL) return Sq;
         else return lut_base + (C > 1 ? lane % C : 0);        // this lane's copy
@@ -537,6 +549,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
                 }
             }
         }
+        stamp<STAMP>(rec, kStampScored, lane);
         int ncand = 0;
         if (K < kRegisterSelectMinK) {
             // (mx: the lane's best score, -inf if it holds no item; at least K of the wave's items reach the floor, and
@@ -573,6 +586,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
                 const int pos = base + __popcll(mk & below);
                 if (((mk >> lane) & 1ull) && pos < a.candmax) L.cand[pos] = make_key(tail_sc + 0.0f, id_of(tail_item));
             }
+            stamp<STAMP>(rec, kStampOffered, lane);
             __syncthreads();
             ncand = ctl->ncand;
         } else {
@@ -619,6 +633,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         // ---- 2. first round: scores in registers, histogram over their range, cut
         float sc[kItems];
         score_round<M, C, NT, CW, GL>(a, lut, stride, r, nblk, blk, tid, r < inside_rounds, total_units, w[0], sc);
+        stamp<STAMP>(rec, kStampScored, lane);
         float mn = __builtin_inff(), mx = -__builtin_inff();
 #pragma unroll
         for (int e = 0; e < kItems; ++e)
@@ -639,6 +654,7 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
             if (lane == 0) ctl->shared_floor = next_up(ctl->cut);
         }
         __syncthreads();
+        stamp<STAMP>(rec, kStampOffered, lane);
         const int bstar = ctl->bstar;
         top.floor_ge = next_up(ctl->cut);                     // bucket >= b* implies score > cut
 #pragma unroll
@@ -710,11 +726,14 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
         }
     }
 
+    stamp<STAMP>(rec, kStampStreamed, lane);
     // ---- 4. workgroup selection: the waves' lists -> exact K best, sorted
     // (the running histogram's floor joins the final selection from K = 32 on: below, the waves' own floors leave few
     // enough keys, and deriving it would cost more than it saves)
     workgroup_select<NT>(L, ctl, top, K, a.cap, a.candmax, tid, wide_floor && K >= 32, hlo, hscale);
     }
+    stamp<STAMP>(rec, kStampSelected, lane);
     uint64_t* mine_out = a.ws_keys + ((size_t)q * nblk + blockIdx.x) * K;
     for (int t = tid; t < K; t += NT) mine_out[t] = L.sorted[t];
+    stamp<STAMP>(rec, kStampEnd, lane);
 }

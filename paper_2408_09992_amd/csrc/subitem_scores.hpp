@@ -1,6 +1,7 @@
 // Eq. 4: the sub-id score matrix S (pq_subitem_scores).
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, scan_single.hpp, scan_batched.hpp, fold.hpp, comparison.hpp.
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// fold.hpp, comparison.hpp.
 #pragma once
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -9,11 +10,15 @@
 constexpr int kSubThreads = 64;
 constexpr int kSubQueryTile = 16;
 
-template <int S_ELEMS>   // d/m when it is one of the unrolled sizes, else 0 (runtime loop)
+// STAMP: measurement instance that also records wall-clock stamps (entry and end) per workgroup in `stamps`.
+template <int S_ELEMS, bool STAMP = false>   // S_ELEMS: d/m when it is one of the unrolled sizes, else 0 (runtime loop)
 __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float* __restrict__ queries,
                                                                      const float* __restrict__ centroids,
-                                                                     float* __restrict__ S, int B, int d, int m, int b) {
+                                                                     float* __restrict__ S, int B, int d, int m, int b,
+                                                                     uint64_t* stamps = nullptr) {
     const int s = S_ELEMS ? S_ELEMS : d / m;
+    uint64_t* const rec = STAMP ? stamps + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * kStampSlots : nullptr;
+    stamp<STAMP>(rec, kStampEntry, threadIdx.x);
     const int kj = blockIdx.x * kSubThreads + threadIdx.x;       // k * b + j
     const int q0 = blockIdx.y * kSubQueryTile;
     if (kj >= m * b) return;
@@ -41,6 +46,7 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float
             for (int t = 0; t < S_ELEMS; ++t) acc = __builtin_fmaf(w[t], phi[t], acc);
             S[(size_t)q * m * b + kj] = acc;
         }
+        stamp<STAMP>(rec, kStampEnd, threadIdx.x);
     } else {
         for (int q = q0; q < q1; ++q) {
             const float* phi = queries + (size_t)q * d + (size_t)k * s;

@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "pqtopk.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
 
 OK, NULL, SHAPE, UNSUPPORTED, WORKSPACE, ALIGN, HIP = 0, -1, -2, -3, -4, -5, -6
 
@@ -41,9 +42,12 @@ def lib(pqlib_path):
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pq_[a-z_0-9]+)\s*\(", text)))
+    """Every function any header under include/ declares (comments stripped)."""
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(pq_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(lib):

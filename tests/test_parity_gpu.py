@@ -321,6 +321,57 @@ def test_short_scans_with_larger_k_select_from_registers(pq, oracle):
         assert ids[1][0] == N - 1
 
 
+@pytest.mark.parametrize("m", [1, 2, 4, 8, 16, 32, 64])
+def test_short_scan_every_number_of_units_per_thread(pq, oracle, m):
+    # single-query scans whose workgroups hold their whole share in registers (the short kernel) take a kernel instance
+    # per number of units a thread holds; catalogue sizes that land on each of them, odd so that the last slot is ragged
+    # and items follow the last whole code vector; K = 1, 10 and 31 (the largest the short kernel and small fold take)
+    unit_items = 16 // m if m <= 16 else 1
+    max_units = {1: 2, 2: 2, 4: 4, 8: 8, 16: 8, 32: 4, 64: 2}[m]
+    S = tables(m, 1, m, 256)
+    for units in range(1, max_units + 1):
+        N = (units - 1) * 256 * 512 * unit_items + 77_001 * unit_items + 3
+        G = W.codes_uniform(N, m, 256, seed=units + m)
+        G[N - 1] = S[0].argmax(axis=1)                         # the last item (after the last whole vector) is the best
+        for K in (1, 10, 31):
+            ids, _ = assert_same_topk(pq, oracle, G, S, K, f"short units={units}")
+            if m >= 4:                                             # (fewer splits: other items share its row, lower ids first)
+                assert ids[0][0] == N - 1
+
+
+def test_short_scan_and_small_fold_against_the_general_kernels(pq, oracle):
+    # the same calls through the general scan and fold kernels (measurement hook) give the same bits; heavy ties take
+    # the short kernel's slow path (more candidates than its array holds): all items equal, coarse tables, -0 tables
+    cases = []
+    N = 1_280_000
+    cases.append((W.codes_uniform(N, 8, 256, seed=5), tables(5, 1, 8, 256), 10, "headline shape"))
+    cases.append((np.full((300_001, 8), 3, dtype=np.uint8), tables(6, 1, 8, 256), 31, "all equal"))
+    coarse = (np.round(tables(7, 1, 4, 16) * 2) / 2).astype(np.float32)
+    cases.append((W.codes_uniform(900_001, 4, 16, seed=7), coarse, 20, "coarse tables"))
+    zeros = np.zeros((2, 8, 256), dtype=np.float32)
+    zeros[:, ::2] = -0.0
+    cases.append((W.codes_uniform(200_003, 8, 256, seed=8), zeros, 7, "zero tables"))
+    cases.append((W.codes_uniform(31, 8, 256, seed=9), tables(9, 3, 8, 256), 31, "K = N"))
+    cases.append((W.codes_uniform(5, 16, 256, seed=10), tables(10, 1, 16, 256), 2, "one code vector"))
+    for G, S, K, tag in cases:
+        ids, sc = assert_same_topk(pq, oracle, G, S, K, tag)
+        for mask in (1, 2, 3):
+            prev = pq.pq_measure_force_general(mask)
+            try:
+                ids2, sc2 = run_topk(pq, G, S, K)
+            finally:
+                pq.pq_measure_force_general(prev)
+            assert np.array_equal(ids, ids2) and np.array_equal(sc.view(np.uint32), sc2.view(np.uint32)), (tag, mask)
+
+
+def test_small_fold_many_lists(pq, oracle):
+    # the small-K fold with both of its instances: up to 3072 and up to 6144 keys per query (256 lists of K = 10, 24),
+    # a batch of queries folded side by side, and lists with empty slots (fewer than K items in a workgroup's share)
+    for N, B, K in ((1_280_000, 1, 24), (2_000_003, 2, 12), (1_280_001, 2, 31), (300, 1, 10), (70_000, 5, 31)):
+        G = W.codes_uniform(N, 8, 256, seed=N % 97)
+        assert_same_topk(pq, oracle, G, tables(N % 89, B, 8, 256), K, "small fold")
+
+
 def test_coarse_tables_many_ties(pq, oracle):
     G = W.codes_uniform(300_000, 4, 16, seed=3)
     S = (np.round(W.normal_f32(W.stream_key(3, W.STREAM_QUERIES), 2 * 4 * 16) * 2) / 2).astype(np.float32)
