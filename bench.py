@@ -384,6 +384,14 @@ def yardsticks_mode(args):
         reads[str(nbytes)] = {"us": ms * 1e3, "GBps": nbytes / (ms * 1e-3) / 1e9}
         del buf
     out["stream_read"] = reads
+    # synchronising inside a launch against a launch boundary (why a step stays three launches)
+    scratch = torch.zeros(pq.PQ_SYNC_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+    sync = {}
+    for v, name in enumerate(pq.PQ_SYNC_VARIANT_NAMES):
+        pq.pq_measure_sync_variant(v, scratch, 200)
+        sync[name] = sorted(pq.pq_measure_sync_variant(v, scratch, 1000) for _ in range(5))[2] * 1e3
+        print(f"sync variant {name:28s} {sync[name]:7.2f} us per iteration", file=sys.stderr, flush=True)
+    out["in_launch_sync_us"] = sync
     sink = torch.zeros(16, dtype=torch.int32, device="cuda")
     gathers = []
     rounds = 16 * 256

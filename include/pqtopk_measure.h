@@ -66,6 +66,36 @@ int pq_measure_lds_gather(int width, int table_bytes, int rounds, int conflict_f
                           uint32_t* sink, void* stream, int iters, float* gather_ms);
 
 /*
+ * What synchronising inside one launch costs on this machine, against a launch boundary: the reason a step stays three
+ * launches.  Each variant is launched once untimed and then `iters` times back to back on `stream` between two HIP
+ * events; *variant_ms (host) receives elapsed / iters.  The kernels are stand-ins that do the synchronisation and the
+ * memory traffic of a scheme and none of its arithmetic (grid of 256 workgroups of 512 threads, as the single-query scan):
+ *   PQ_SYNC_EMPTY                      an empty kernel on that grid: the floor
+ *   PQ_SYNC_FOLD_LAUNCH                every workgroup writes 10 keys; a second launch of one workgroup reads all 2560
+ *   PQ_SYNC_LAST_FOLDS_FENCED          one launch: ... acquire-release ticket, the last workgroup to arrive reads them
+ *   PQ_SYNC_LAST_FOLDS_RELAXED         ... keys written through and read with agent-scope accesses, relaxed ticket
+ *   PQ_SYNC_LAST_FOLDS_RELAXED_2LEVEL  ... sixteen group tickets, then one (a self-resetting two-level ticket)
+ *   PQ_SYNC_EQ4_LAUNCH                 Eq. 4 (2048 chains of 64 multiply-adds) as its own launch, then a launch in which
+ *                                      every workgroup loads the 8 KB table into LDS
+ *   PQ_SYNC_EQ4_BARRIER_FENCED         one launch: Eq. 4 spread over the grid, a grid-wide barrier on generation tags
+ *                                      (release store, acquire fence), then every workgroup loads the table
+ *   PQ_SYNC_EQ4_BARRIER_RELAXED        ... with agent-scope relaxed accesses and no fence
+ * Every wait in these kernels is bounded.  `scratch`: device memory, 256-byte aligned, at least PQ_SYNC_SCRATCH_BYTES;
+ * it is zeroed here.  Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_ALIGN, PQ_ERR_WORKSPACE, PQ_ERR_HIP.
+ */
+#define PQ_SYNC_EMPTY                      0
+#define PQ_SYNC_FOLD_LAUNCH                1
+#define PQ_SYNC_LAST_FOLDS_FENCED          2
+#define PQ_SYNC_LAST_FOLDS_RELAXED         3
+#define PQ_SYNC_LAST_FOLDS_RELAXED_2LEVEL  4
+#define PQ_SYNC_EQ4_LAUNCH                 5
+#define PQ_SYNC_EQ4_BARRIER_FENCED         6
+#define PQ_SYNC_EQ4_BARRIER_RELAXED        7
+#define PQ_SYNC_VARIANTS                   8
+#define PQ_SYNC_SCRATCH_BYTES ((size_t)2 << 20)
+int pq_measure_sync_variant(int variant, void* scratch, size_t scratch_bytes, void* stream, int iters, float* variant_ms);
+
+/*
  * Which kernels single-query calls with small K take, for A/B measurement and for tests that must reach the general
  * kernels on shapes the lean ones would serve.  mask bit 0: catalogue scans never take the short kernel (scores in
  * registers, one selection) but the general scan kernel; bit 1: folds never take the small-K fold but the general

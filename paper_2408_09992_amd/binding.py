@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.pq_measure_empty_launch.restype = I
         L.pq_measure_lds_gather.argtypes = [I, I, I, I, I, I, I, P, P, I, ctypes.POINTER(ctypes.c_float)]
         L.pq_measure_lds_gather.restype = I
+        L.pq_measure_sync_variant.argtypes = [I, P, SZ, P, I, ctypes.POINTER(ctypes.c_float)]
+        L.pq_measure_sync_variant.restype = I
         L.pq_measure_force_general.argtypes = [I]
         L.pq_measure_force_general.restype = I
         L.pq_measure_step_stamps.argtypes = [P, P, P, LL, I, I, I, I, I, P, P, P, P, SZ, P, SZ, ctypes.POINTER(I * 2), P]
@@ -351,6 +353,21 @@ def pq_measure_lds_gather(width: int, table_bytes: int, rounds: int, conflict_fr
                                      _stream(), iters, ctypes.byref(ms))
     if rc != PQ_OK:
         raise PQError(rc, "pq_measure_lds_gather")
+    return float(ms.value)
+
+
+PQ_SYNC_VARIANT_NAMES = ("empty", "fold_launch", "last_folds_fenced", "last_folds_relaxed", "last_folds_relaxed_2level",
+                         "eq4_launch", "eq4_barrier_fenced", "eq4_barrier_relaxed")
+PQ_SYNC_SCRATCH_BYTES = 2 << 20
+
+
+def pq_measure_sync_variant(variant: int, scratch: torch.Tensor, iters: int) -> float:
+    """Mean time (ms) per iteration of one of the in-launch synchronisation stand-ins (see pqtopk_measure.h)."""
+    ms = ctypes.c_float(0.0)
+    rc = lib().pq_measure_sync_variant(variant, scratch.data_ptr(), scratch.numel() * scratch.element_size(), _stream(),
+                                       iters, ctypes.byref(ms))
+    if rc != PQ_OK:
+        raise PQError(rc, "pq_measure_sync_variant")
     return float(ms.value)
 
 
