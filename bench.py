@@ -305,13 +305,14 @@ def breakdown_mode(args):
     from paper_2408_09992_amd import binding as pq, workloads as W
 
     cfg = W.CONFIGS[args.config]
-    G, cent, Q = W.make(cfg, B=1)
+    B = args.batch if args.batch is not None else 1
+    G, cent, Q = W.make(cfg, B=B)
     N, m, b, K, d = cfg.N, cfg.m, cfg.b, cfg.K, cfg.d
     Gd, Cd, Qd = torch.from_numpy(G).cuda(), torch.from_numpy(cent).cuda(), torch.from_numpy(Q).cuda()
-    S = torch.empty((1, m, b), dtype=torch.float32, device="cuda")
-    ws = torch.empty(pq.pq_score_topk_workspace_bytes(N, 1, m, b, K), dtype=torch.uint8, device="cuda")
-    ids = torch.empty((1, K), dtype=torch.int32, device="cuda")
-    sc = torch.empty((1, K), dtype=torch.float32, device="cuda")
+    S = torch.empty((B, m, b), dtype=torch.float32, device="cuda")
+    ws = torch.empty(pq.pq_score_topk_workspace_bytes(N, B, m, b, K), dtype=torch.uint8, device="cuda")
+    ids = torch.empty((B, K), dtype=torch.int32, device="cuda")
+    sc = torch.empty((B, K), dtype=torch.float32, device="cuda")
     stamps = torch.zeros((3, pq.PQ_STAMP_RECORDS, pq.PQ_STAMP_SLOTS), dtype=torch.int64, device="cuda")
     tick_us = 0.01                                           # wall_clock64(): 100 MHz on MI355X
     names = {0: "entry", 1: "requested", 2: "tables", 3: "codes", 4: "scored", 5: "offered", 6: "streamed", 7: "selected",
@@ -325,8 +326,12 @@ def breakdown_mode(args):
         eq4 = t[0][t[0][:, 0] > 0]
         scan = t[1][: nblk * waves]
         fold = t[2][t[2][:, 0] > 0]
-        t0 = eq4[:, 0].min()
-        row = {"eq4_first_entry": 0.0, "eq4_last_end": (eq4[:, 8].max() - t0) * tick_us}
+        if len(eq4):
+            t0 = eq4[:, 0].min()
+            row = {"eq4_first_entry": 0.0, "eq4_last_end": (eq4[:, 8].max() - t0) * tick_us}
+        else:                                                # (no stamping instance of Eq. 4 for this shape: times count from the scan's first wave)
+            t0 = scan[:, 0][scan[:, 0] > 0].min()
+            row = {}
         for slot in (0, 1, 2, 3, 4, 5, 6, 7, 8):
             col = scan[:, slot]
             col = col[col > 0]
@@ -334,7 +339,7 @@ def breakdown_mode(args):
                 row[f"scan_{names[slot]}_first"] = (col.min() - t0) * tick_us
                 row[f"scan_{names[slot]}_median"] = (np.median(col) - t0) * tick_us
                 row[f"scan_{names[slot]}_last"] = (col.max() - t0) * tick_us
-        for (s0, s1) in ((0, 2), (2, 3), (3, 4), (4, 5), (5, 7), (7, 8)):   # per-wave durations
+        for (s0, s1) in ((0, 2), (2, 3), (3, 4), (2, 4), (4, 5), (5, 6), (5, 7), (6, 7), (7, 8)):   # per-wave durations
             ok = (scan[:, s0] > 0) & (scan[:, s1] > 0)
             if ok.any():
                 dd = (scan[ok, s1] - scan[ok, s0]) * tick_us
@@ -356,7 +361,7 @@ def breakdown_mode(args):
         "metric": "in-kernel wall-clock stamps of one step (Eq. 4, scan, fold), microseconds after the step's first wave",
         "value": med["fold_end_last"], "unit": "us", "n_gpus": 1, "higher_is_better": False, "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch=1, codes {cfg.codes}, seed {cfg.seed}",
+        "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch={B}, codes {cfg.codes}, seed {cfg.seed}",
                    "scan_workgroups": nblk, "waves_per_workgroup": waves, "samples": args.breakdown_samples,
                    "steps_per_sample": args.breakdown_steps, "tick_us": tick_us},
         "stamps_us": med}))

@@ -108,11 +108,12 @@ int pq_measure_force_general(int mask);
  * One whole step (pq_subitem_scores, then pq_score_topk's scan and fold launches) with the measurement instances of
  * the three kernels, which record wall-clock stamps (hipDeviceAttributeWallClockRate ticks, 100 MHz on MI355X) at
  * fixed points: lane 0 of every wave writes PQ_STAMP_SLOTS 64-bit values.  Results (S, ids, scores) are those of the
- * product entry points.  Only single-query calls with m = 8 and d / m = 64 have measurement instances
- * (PQ_ERR_UNSUPPORTED otherwise).
+ * product entry points.  Measurement instances exist for the scans of single-query calls with m = 8 (short and long)
+ * and for the batched scan (m = 8 and 16), for both folds, and for Eq. 4 at batch 1 with d / m = 64 (otherwise the
+ * product's Eq. 4 kernel runs and section 0 stays as it was); PQ_ERR_UNSUPPORTED for other shapes.
  *   stamps       out  uint64 [3][PQ_STAMP_RECORDS][PQ_STAMP_SLOTS]: section 0 = the Eq. 4 kernel (one record per
- *                     workgroup), section 1 = the scan kernel (record = workgroup * waves + wave), section 2 = the fold
- *                     kernel (one record per wave).  Slots a kernel does not pass are left as they were: zero the
+ *                     workgroup), section 1 = the scan kernel (record = workgroup * waves + wave, workgroups numbered
+ *                     blockIdx.y * gridDim.x + blockIdx.x), section 2 = the fold kernel (record = query * waves + wave).  Slots a kernel does not pass are left as they were: zero the
  *                     buffer first.  Slot meanings: PQ_STAMP_* below.
  *   stamps_bytes      at least PQ_STAMP_BYTES
  *   scan_grid    out  (host, may be NULL) [0] = scan workgroups, [1] = waves per scan workgroup

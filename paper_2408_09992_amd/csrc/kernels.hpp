@@ -60,7 +60,7 @@ namespace pqk {
     PQ_SHORT_U(X, 16, 6) PQ_SHORT_U(X, 16, 7) PQ_SHORT_U(X, 16, 8) \
     PQ_SHORT_U(X, 32, 1) PQ_SHORT_U(X, 32, 2) PQ_SHORT_U(X, 32, 3) PQ_SHORT_U(X, 32, 4) PQ_SHORT_U(X, 64, 1) PQ_SHORT_U(X, 64, 2)
 // the batched kernel
-#define PQ_TILED_INSTANCES(X) X(8) X(16)
+#define PQ_TILED_INSTANCES(X) X(8, false) X(16, false) X(8, true) X(16, true)
 
 #define PQ_SCAN_DEFINE(M, C, NT, CW, GL) template __global__ void scan_topk_kernel<M, C, NT, CW, GL>(ScanArgs);
 #define PQ_SCAN_EXTERN(M, C, NT, CW, GL) extern PQ_SCAN_DEFINE(M, C, NT, CW, GL)
@@ -68,8 +68,8 @@ namespace pqk {
 #define PQ_SCAN_EXTERN6(M, C, NT, CW, GL, ST) extern PQ_SCAN_DEFINE6(M, C, NT, CW, GL, ST)
 #define PQ_SHORT_DEFINE(M, U, NT, ST) template __global__ void scan_short_kernel<M, U, NT, ST>(ScanArgs);
 #define PQ_SHORT_EXTERN(M, U, NT, ST) extern PQ_SHORT_DEFINE(M, U, NT, ST)
-#define PQ_TILED_DEFINE(M) template __global__ void scan_topk_tiled_kernel<M>(ScanArgs, int);
-#define PQ_TILED_EXTERN(M) extern PQ_TILED_DEFINE(M)
+#define PQ_TILED_DEFINE(M, ST) template __global__ void scan_topk_tiled_kernel<M, ST>(ScanArgs, int);
+#define PQ_TILED_EXTERN(M, ST) extern PQ_TILED_DEFINE(M, ST)
 
 #ifndef PQ_INSTANCE_TU
 PQ_SCAN_INSTANCES_U8_NARROW(PQ_SCAN_EXTERN)

@@ -435,9 +435,23 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
         if (stamps != nullptr && m != 8) return PQ_ERR_UNSUPPORTED;
         return record_hip(launch_short(p, a, B, m, st));
     }
+    if (p.tiled) {
+        const dim3 grid(p.nblk, (B + kQ - 1) / kQ);
+        auto launch_tiled = [&](auto kernel) {
+            hipError_t err = allow_lds(kernel, p.scan_dyn_lds);
+            if (err == hipSuccess) {
+                hipLaunchKernelGGL(kernel, grid, dim3(kThreads), p.scan_dyn_lds, st, a, B);
+                err = hipGetLastError();
+            }
+            return err;
+        };
+        if (stamps != nullptr) e = m == 8 ? launch_tiled(scan_topk_tiled_kernel<8, true>) : launch_tiled(scan_topk_tiled_kernel<16, true>);
+        else e = m == 8 ? launch_tiled(scan_topk_tiled_kernel<8, false>) : launch_tiled(scan_topk_tiled_kernel<16, false>);
+        return record_hip(e);
+    }
     if (stamps != nullptr) {
-        // the measurement instances exist for the single-query m = 8 kernels only
-        if (p.tiled || cw != 1 || !p.vec || m != 8 || p.big != (p.copies == kTableCopies)) return PQ_ERR_UNSUPPORTED;
+        // single-query scans: measurement instances exist for m = 8 only
+        if (cw != 1 || !p.vec || m != 8 || p.big != (p.copies == kTableCopies)) return PQ_ERR_UNSUPPORTED;
         if (p.copies == kTableCopies) {
             e = allow_lds(scan_topk_kernel<8, kTableCopies, kBigThreads, 1, false, true>, p.scan_dyn_lds);
             if (e == hipSuccess)
@@ -448,17 +462,6 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
             if (e == hipSuccess)
                 hipLaunchKernelGGL((scan_topk_kernel<8, 1, kThreads, 1, false, true>), dim3(p.nblk, B), dim3(kThreads),
                                    p.scan_dyn_lds, st, a);
-        }
-        return record_hip(e == hipSuccess ? hipGetLastError() : e);
-    }
-    if (p.tiled) {
-        const dim3 grid(p.nblk, (B + kQ - 1) / kQ);
-        if (m == 8) {
-            e = allow_lds(scan_topk_tiled_kernel<8>, p.scan_dyn_lds);
-            if (e == hipSuccess) hipLaunchKernelGGL(scan_topk_tiled_kernel<8>, grid, dim3(kThreads), p.scan_dyn_lds, st, a, B);
-        } else {
-            e = allow_lds(scan_topk_tiled_kernel<16>, p.scan_dyn_lds);
-            if (e == hipSuccess) hipLaunchKernelGGL(scan_topk_tiled_kernel<16>, grid, dim3(kThreads), p.scan_dyn_lds, st, a, B);
         }
         return record_hip(e == hipSuccess ? hipGetLastError() : e);
     }
@@ -711,20 +714,24 @@ int pq_measure_step_stamps(const float* queries, const float* centroids, const u
     int rc = check_topk_args(codes, S, N, B, m, b, K, out_ids, out_scores, workspace, workspace_bytes_given);
     if (rc != PQ_OK) return rc;
     if (d < 1 || d % m != 0) return PQ_ERR_SHAPE;
-    if (B != 1 || m != 8 || d / m != 64) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)stamps & 7)) return PQ_ERR_ALIGN;
     if (stamps_bytes < PQ_STAMP_BYTES) return PQ_ERR_WORKSPACE;
     static_assert(PQ_STAMP_SLOTS == kStampSlots, "header and kernels agree on the record size");
     const ScanPlan p = make_plan(N, B, m, K);
+    if (!(p.tiled || m == 8)) return PQ_ERR_UNSUPPORTED;       // (scan kernels with a measurement instance)
     const int waves = p.big ? kMaxWaves : kWaves;
-    if ((long long)p.nblk * waves > PQ_STAMP_RECORDS || (m * b + kSubThreads - 1) / kSubThreads > PQ_STAMP_RECORDS)
-        return PQ_ERR_UNSUPPORTED;
-    if (scan_grid != nullptr) { scan_grid[0] = p.nblk; scan_grid[1] = waves; }
+    const long long scan_groups = p.tiled ? (long long)p.nblk * ((B + kQ - 1) / kQ) : (long long)p.nblk * B;
+    if (scan_groups * waves > PQ_STAMP_RECORDS || (long long)B * kWaves > PQ_STAMP_RECORDS) return PQ_ERR_UNSUPPORTED;
+    if (scan_grid != nullptr) { scan_grid[0] = (int)scan_groups; scan_grid[1] = waves; }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t section = (size_t)PQ_STAMP_RECORDS * PQ_STAMP_SLOTS;
-    hipLaunchKernelGGL((subitem_scores_kernel<64, true>), dim3((m * b + kSubThreads - 1) / kSubThreads, 1), dim3(kSubThreads), 0,
-                       st, queries, centroids, S, B, d, m, b, stamps);
-    rc = record_hip(hipGetLastError());
+    if (B == 1 && d / m == 64 && (m * b + kSubThreads - 1) / kSubThreads <= PQ_STAMP_RECORDS) {
+        hipLaunchKernelGGL((subitem_scores_kernel<64, true>), dim3((m * b + kSubThreads - 1) / kSubThreads, 1), dim3(kSubThreads), 0,
+                           st, queries, centroids, S, B, d, m, b, stamps);
+        rc = record_hip(hipGetLastError());
+    } else {
+        rc = pq_subitem_scores(queries, centroids, S, B, d, m, b, stream);   // (no measurement instance: section 0 stays empty)
+    }
     if (rc != PQ_OK) return rc;
     rc = enqueue_scan(p, codes, S, N, B, m, b, K, workspace, st, nullptr, 0, 1, stamps + section);
     if (rc != PQ_OK) return rc;

@@ -140,8 +140,9 @@ struct TileLds {
 // ctl(q)->keep keys) into best[q]: the exact K best of everything the workgroup scanned, sorted.  Two paths:
 //   - few keys everywhere: wave q ranks query q by counting, no workgroup barrier inside;
 //   - otherwise: ranking / sorting by the whole workgroup, one query at a time.
-// Every thread of the workgroup calls it.  Out of line: the streaming loop stays small.
-__device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, bool filter, int tid) {
+// Every thread of the workgroup calls it, once, after the streaming loop (inlined: a call would save the caller's registers to
+// the stack for a function that returns to nothing but the final store).
+__device__ __forceinline__ void tile_checkpoint(const TileLds& L, int nq, int K, int cap, int candmax, bool filter, int tid) {
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(L.pctl + (size_t)q * align16(sizeof(Ctl))); };
     auto reset_lists = [&](int q, int wv, float floor_ge) {   // one thread per (query, wave)
@@ -246,9 +247,12 @@ __device__ __noinline__ void tile_checkpoint(const TileLds& L, int nq, int K, in
     }
 }
 
-template <int M>
+// STAMP: measurement instance that also records wall-clock stamps per wave.
+template <int M, bool STAMP = false>
 __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, int B) {
     constexpr int IPV = 16 / M, kItems = kTileVecs * IPV, kWords = kTileVecs * 4;
+    uint64_t* const rec = STAMP ? a.stamps + (((size_t)blockIdx.y * gridDim.x + blockIdx.x) * kWaves + threadIdx.x / kWave) * kStampSlots : nullptr;
+    stamp<STAMP>(rec, kStampEntry, threadIdx.x & (kWave - 1));
     __shared__ __align__(16) float4 lut4[M * kLutStride];
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem);
@@ -313,22 +317,22 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     load(r, tid, wa);
     load(r + nblk, tid, wb);
     {
-        float* lutf = reinterpret_cast<float*>(lut4);
-        if (b == kLutStride) {                                // whole rows: 16-byte loads, four sub-ids at a time
-            for (int e4 = tid; e4 < kQ * M * kLutStride / 4; e4 += kThreads) {
-                const int q = e4 / (M * kLutStride / 4), kj4 = e4 % (M * kLutStride / 4);
-                float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if (q < nq) v = reinterpret_cast<const float4*>(a.S + (size_t)(q0 + q) * M * kLutStride)[kj4];
-                float* dst = lutf + (size_t)kj4 * 4 * kQ + q;
-                dst[0] = v.x; dst[kQ] = v.y; dst[2 * kQ] = v.z; dst[3 * kQ] = v.w;
-            }
-        } else {
-            for (int e = tid; e < kQ * M * kLutStride; e += kThreads) {
-                const int q = e / (M * kLutStride), kj = e % (M * kLutStride), k = kj / kLutStride, j = kj % kLutStride;
-                const float v = (q < nq && j < b) ? a.S[((size_t)(q0 + q) * M + k) * b + j] : 0.0f;
-                lutf[((size_t)k * kLutStride + j) * kQ + q] = v;
-            }
+        // A thread owns table entries (split, sub-id) = tid, tid + kThreads, ...: it reads that entry of each of the
+        // tile's four tables (consecutive lanes read consecutive floats) and writes them as one float4, consecutive
+        // lanes to consecutive 16-byte slots: no bank conflicts, and every load is on its way before the first store.
+        // Sub-ids from b on (tables with fewer than 256 entries per split) and queries past B get zeros.
+        constexpr int kPer = M * kLutStride / kThreads;        // entries per thread
+        static_assert(M * kLutStride % kThreads == 0, "whole entries per thread");
+        float tv[kPer][kQ];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = tid + i * kThreads, k = e / kLutStride, j = e % kLutStride;
+#pragma unroll
+            for (int q = 0; q < kQ; ++q)
+                tv[i][q] = (q < nq && j < b) ? a.S[((size_t)(q0 + q) * M + k) * b + j] : 0.0f;
         }
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) lut4[tid + i * kThreads] = make_float4(tv[i][0], tv[i][1], tv[i][2], tv[i][3]);
         for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
         for (int i = tid; i < kQ * kFloorBins; i += kThreads) fhist[i] = 0;
         for (int i = tid; i < kQ * kpad; i += kThreads) best[i] = 0;
@@ -336,7 +340,9 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         if (tid == 0) ctl_of(0)->next_unit = 3 * kWaves;       // units 0 .. 3 kWaves - 1 are the waves' own (see 3.)
         if (lane < kQ) my_state[lane] = WaveQ{0ull, 0, -__builtin_inff()};
     }
+    stamp<STAMP>(rec, kStampRequested, lane);
     __syncthreads();
+    stamp<STAMP>(rec, kStampTables, lane);
 
     // One round's scores against the kQ lists of this wave.  The lists' lengths are cached in scalar registers
     // (cnt[q]) while rounds stream: a survivor then costs one ballot-compacted LDS write and no LDS round trip.
@@ -423,6 +429,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         // ---- 2. first round: per query a histogram over its own score range gives that query's cut
         float sc[kQ][kItems];
         score(wa, sc);
+        stamp<STAMP>(rec, kStampScored, lane);
         load(r + 2 * nblk, tid, wa);
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
@@ -469,6 +476,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
         }
         wave_sync();
         offer_round(sc, r, tid, bk, bstar);
+        stamp<STAMP>(rec, kStampOffered, lane);
     }
 
     // ---- 3. stream.  Work is handed out in units of one wave's share of one of this workgroup's rounds: unit u is
@@ -548,10 +556,13 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     }
 
     // ---- 4. last checkpoint, then the workgroup's exact K best per query go to the workspace, sorted
+    stamp<STAMP>(rec, kStampStreamed, lane);
     publish_counts();
     tile_checkpoint(tl, nq, K, a.cap, a.candmax, a.prune_at == 0, tid);
+    stamp<STAMP>(rec, kStampSelected, lane);
     for (int i = tid; i < nq * K; i += kThreads) {
         const int q = i / K, t = i % K;
         a.ws_keys[((size_t)(q0 + q) * nblk + blockIdx.x) * K + t] = best[(size_t)q * kpad + t];
     }
+    stamp<STAMP>(rec, kStampEnd, lane);
 }
