@@ -99,7 +99,7 @@ int pq_measure_sync_variant(int variant, void* scratch, size_t scratch_bytes, vo
  * Which kernels single-query calls with small K take, for A/B measurement and for tests that must reach the general
  * kernels on shapes the lean ones would serve.  mask bit 0: catalogue scans never take the short kernel (scores in
  * registers, one selection) but the general scan kernel; bit 1: folds never take the small-K fold but the general
- * one.  0 restores the library's own choice.  Process-wide, takes effect for calls made after it returns (workspace
+ * one; bit 2: Eq. 4 never runs on the matrix cores but in the scalar kernels.  0 restores the library's own choice.  Process-wide, takes effect for calls made after it returns (workspace
  * sizes do not depend on it).  Returns the previous mask.
  */
 int pq_measure_force_general(int mask);

@@ -372,8 +372,8 @@ def pq_measure_sync_variant(variant: int, scratch: torch.Tensor, iters: int) -> 
 
 
 def pq_measure_force_general(mask: int) -> int:
-    """Bit 0: scans avoid the short kernel; bit 1: folds avoid the small-K fold; 0: the library's choice.  Returns the
-    previous mask."""
+    """Bit 0: scans avoid the short kernel; bit 1: folds avoid the small-K fold; bit 2: Eq. 4 avoids the matrix cores;
+    0: the library's choice.  Returns the previous mask."""
     return int(lib().pq_measure_force_general(int(mask)))
 
 

@@ -52,7 +52,8 @@ using namespace pqk;
 
 thread_local char g_hip_error[256] = "no HIP error recorded";
 
-// pq_measure_force_general(): bit 0 keeps calls off scan_short_kernel, bit 1 off fold_small_kernel (0: the product's choice)
+// pq_measure_force_general(): bit 0 keeps calls off scan_short_kernel, bit 1 off fold_small_kernel, bit 2 Eq. 4 off the
+// matrix cores (0: the product's choice)
 std::atomic<int> g_force_general{0};
 
 int record_hip(hipError_t e) {
@@ -563,6 +564,22 @@ int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids,
     }
 }
 
+// Batch from which Eq. 4 runs on the matrix cores.  The scalar kernels are faster below: a wave's chain of d/m matrix
+// instructions takes as long for one tile of 32 queries as for a GPU full of them (measured at d = 512, m = 8, b = 256:
+// 5.8 us against 5.0 us at B = 256, 6.1 against 6.7 at B = 512, 6.7 against 10.8 at B = 1024, 21 against 35 at B = 4096).
+constexpr int kSubMfmaMinBatch = 448;
+
+// Eq. 4 on the matrix cores when the shape allows: rows 16-byte aligned, d/m a multiple of 16.
+bool launch_subitem_mfma(const float* queries, const float* centroids, float* S, int B, int d, int m, int b, hipStream_t st) {
+    const int s = d / m;
+    if (B < kSubMfmaMinBatch || s % 16 != 0 || d % 4 != 0 || ((((uintptr_t)queries | (uintptr_t)centroids)) & 15) != 0) return false;
+    const dim3 grid(m * ((b + 63) / 64), (B + kSubMfmaQueries - 1) / kSubMfmaQueries);
+    if (s % 64 == 0) hipLaunchKernelGGL(subitem_scores_mfma_kernel<64>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, b);
+    else if (s % 32 == 0) hipLaunchKernelGGL(subitem_scores_mfma_kernel<32>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, b);
+    else hipLaunchKernelGGL(subitem_scores_mfma_kernel<16>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, b);
+    return true;
+}
+
 template <int S_ELEMS>
 void launch_subitem(const float* queries, const float* centroids, float* S, int B, int d, int m, int b, hipStream_t st) {
     if constexpr (S_ELEMS % 4 == 0) {
@@ -611,6 +628,8 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
     if (B > PQ_MAX_B || m > PQ_MAX_M) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)S & 3)) return PQ_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!(g_force_general.load(std::memory_order_relaxed) & 4) && launch_subitem_mfma(queries, centroids, S, B, d, m, b, st))
+        return record_hip(hipGetLastError());
     switch (d / m) {
         case 4: launch_subitem<4>(queries, centroids, S, B, d, m, b, st); break;
         case 8: launch_subitem<8>(queries, centroids, S, B, d, m, b, st); break;
@@ -703,7 +722,7 @@ int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int
 }
 
 int pq_measure_force_general(int mask) {
-    return g_force_general.exchange(mask & 3, std::memory_order_relaxed);
+    return g_force_general.exchange(mask & 7, std::memory_order_relaxed);
 }
 
 int pq_measure_step_stamps(const float* queries, const float* centroids, const uint8_t* codes, long long N, int B,

@@ -104,3 +104,74 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_batched_kernel(con
             if (live && q + i < q1) S[(size_t)(q + i) * m * b + kj] = acc[i];
     }
 }
+
+// Eq. 4 on the matrix cores, for batches.  Per split, S_k = Phi_k Psi_k^T is a [B x d/m] x [d/m x b] product, and
+// the fp32 matrix instruction with an inner dimension of ONE (v_mfma_f32_32x32x1_2b_f32: two independent 32 x 32
+// outer products per issue) adds exactly one product to every accumulator, as a fused multiply-add with one
+// rounding: a chain of d/m such instructions over t = 0, 1, ... is the same left-to-right chain from +0 as the
+// scalar kernels run, bit for bit, denormals included (checked against the CPU's fmaf chain).  The instructions with a
+// deeper inner dimension sum several products per issue in an order of their own and are not used.
+// A workgroup of four waves owns 64 sub-ids of one split and 128 queries, a wave 32 of the queries: lanes l and
+// l + 32 supply query (l % 32)'s chunk, lane l supplies sub-item embedding j0 + l, and block 0 / block 1 of the
+// instruction are sub-ids j0 .. j0 + 31 / j0 + 32 .. j0 + 63.  Accumulator register v of lane l is query
+// 8 * ((v % 16) / 4) + 4 * (l / 32) + v % 4 and sub-id j0 + 32 * (v / 16) + l % 32.
+// Both operands are rows of 64 floats that a lane needs whole, one row per lane: read straight from memory that is one
+// cache line per lane and load.  So the workgroup copies its tiles (the 64 sub-item embeddings: 16 KB of consecutive
+// memory; each wave's 32 query chunks) to LDS with consecutive lanes on consecutive 16 bytes, rows padded to 68 floats
+// (a lane's row then starts four banks after its neighbour's), and lanes read their rows from there.
+// grid = (m * ceil(b / 64), ceil(B / 128)).  Rows of queries and centroids must be 16-byte aligned and d/m a multiple
+// of 16; chunks of CH elements are staged at a time.
+typedef float floatx32 __attribute__((ext_vector_type(32)));
+constexpr int kSubMfmaThreads = 256;
+constexpr int kSubMfmaQueries = 32 * (kSubMfmaThreads / kWave);   // queries per workgroup
+constexpr int kSubMfmaPad = 4;                                    // floats added to a staged row
+
+template <int CH>   // elements staged at a time: 16, 32 or 64
+__global__ __launch_bounds__(kSubMfmaThreads) void subitem_scores_mfma_kernel(const float* __restrict__ queries,
+                                                                            const float* __restrict__ centroids,
+                                                                            float* __restrict__ S, int B, int d, int m, int b) {
+    constexpr int ROW = CH + kSubMfmaPad, NW = kSubMfmaThreads / kWave, C4 = CH / 4;   // C4: 16-byte pieces of a staged row
+    __shared__ __align__(16) float psi[64 * ROW];
+    __shared__ __align__(16) float phi[NW][32 * ROW];
+    const int s = d / m;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int jtiles = (b + 63) / 64;
+    const int k = blockIdx.x / jtiles, j0 = (blockIdx.x % jtiles) * 64;
+    const int q0 = blockIdx.y * kSubMfmaQueries + wave * 32;   // (a wave past the batch stages repeats and stores nothing)
+    floatx32 acc;
+#pragma unroll
+    for (int v = 0; v < 32; ++v) acc[v] = 0.0f;
+    for (int c = 0; c < s; c += CH) {
+        if (c != 0) __syncthreads();                           // the previous chunk has been read
+        // sub-item embeddings j0 .. j0 + 63, elements c .. c + CH - 1 (rows past b repeat the last one)
+#pragma unroll
+        for (int p = tid; p < 64 * C4; p += kSubMfmaThreads) {
+            const int row = p / C4, piece = p % C4, j = min(j0 + row, b - 1);
+            const float4 x = reinterpret_cast<const float4*>(centroids + ((size_t)k * b + j) * s + c)[piece];
+            *reinterpret_cast<float4*>(&psi[row * ROW + 4 * piece]) = x;
+        }
+        // this wave's 32 query chunks
+#pragma unroll
+        for (int p = lane; p < 32 * C4; p += kWave) {
+            const int row = p / C4, piece = p % C4, q = min(q0 + row, B - 1);
+            const float4 x = reinterpret_cast<const float4*>(queries + (size_t)q * d + (size_t)k * s + c)[piece];
+            *reinterpret_cast<float4*>(&phi[wave][row * ROW + 4 * piece]) = x;
+        }
+        __syncthreads();
+        float av[CH], bv[CH];
+#pragma unroll
+        for (int i = 0; i < C4; ++i) {
+            const float4 x = *reinterpret_cast<const float4*>(&phi[wave][(lane & 31) * ROW + 4 * i]);
+            const float4 y = *reinterpret_cast<const float4*>(&psi[lane * ROW + 4 * i]);
+            av[4 * i] = x.x; av[4 * i + 1] = x.y; av[4 * i + 2] = x.z; av[4 * i + 3] = x.w;
+            bv[4 * i] = y.x; bv[4 * i + 1] = y.y; bv[4 * i + 2] = y.z; bv[4 * i + 3] = y.w;
+        }
+#pragma unroll
+        for (int t = 0; t < CH; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x1f32(av[t], bv[t], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 32; ++v) {
+        const int qq = q0 + 8 * ((v % 16) / 4) + 4 * (lane / 32) + v % 4, jj = j0 + 32 * (v / 16) + (lane & 31);
+        if (qq < B && jj < b) S[((size_t)qq * m + k) * b + jj] = acc[v];
+    }
+}

@@ -60,6 +60,32 @@ def test_subitem_scores_bit_exact(pq, oracle, B, d, m, b):
 
 # ---------------------------------------------------------------- Algorithm 1, small shapes, several tiles + ragged tails
 
+@pytest.mark.parametrize("B,d,m,b", [(1024, 512, 8, 256), (449, 512, 16, 256), (470, 768, 16, 256), (500, 1024, 8, 256),
+                                     (600, 768, 8, 256), (529, 128, 8, 100), (460, 512, 8, 1000), (512, 64, 4, 256),
+                                     (457, 2048, 8, 7), (3000, 96, 6, 70)])
+def test_subitem_scores_on_the_matrix_cores(pq, oracle, B, d, m, b):
+    # batches large enough for the matrix-core kernel (chains of K = 1 fp32 matrix instructions): the same bits as the
+    # oracle's fused chain, the same bits as the scalar kernels (measurement hook), also with denormal products and
+    # with magnitudes that differ by many orders inside one chain; ragged batches, alphabets that are no multiple of
+    # 64, chunks of 16, 32 and 64 elements, several chunks per chain
+    print(f"case subitem mfma B={B} d={d} m={m} b={b}", flush=True)
+    for scale_c, scale_q in ((1.0, 1.0), (1e-21, 1e-19), (1e8, 1e-3)):
+        cent = (W.centroids(m, b, d, seed=B + d) * scale_c).astype(np.float32)
+        Q = (W.queries(B, d, seed=B + d) * scale_q).astype(np.float32)
+        if scale_c == 1e8:
+            cent[:, :, ::3] *= 1e-12                               # alternating magnitudes along the chain
+        got = pq.pq_subitem_scores(dev(Q), dev(cent))
+        prev = pq.pq_measure_force_general(4)
+        try:
+            scalar = pq.pq_subitem_scores(dev(Q), dev(cent))
+        finally:
+            pq.pq_measure_force_general(prev)
+        torch.cuda.synchronize()
+        ref = oracle.subitem_scores(Q, cent)
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (scale_c, scale_q)
+        assert torch.equal(got.view(torch.int32), scalar.view(torch.int32)), (scale_c, scale_q)
+
+
 @pytest.mark.parametrize("m", [1, 2, 3, 4, 8, 16, 32, 64])
 def test_score_topk_small_shapes(pq, oracle, m):
     for N in (1, 2, 5, 63, 64, 65, 127, 1000, 4099, 70_001):
