@@ -189,10 +189,12 @@ int pq_reconstruct_items(const uint8_t* codes, const float* centroids, long long
                          void* stream);
 
 /*
- * Eq. 3, the default scoring: scores[q][i] = W[i] . phi_q in float32.  The paper fixes no order for this product;
- * here sixteen lanes share a row of W, each accumulates every sixteenth 16-byte piece with fused multiply-adds, and
- * the sixteen partial sums are added across lanes, so results agree with a float64 product to float32 rounding
- * (not bit for bit with any particular serial order).  One pass over W per query.
+ * Eq. 3, the default scoring: scores[q][i] = W[i] . phi_q in float32.  The paper fixes no order for this product, so
+ * results agree with a float64 product to float32 rounding (not bit for bit with any particular order):
+ *   - one or two queries: a mat-vec pass over W per query (sixteen lanes share a row of W, each accumulates every
+ *     sixteenth 16-byte piece with fused multiply-adds, the partial sums are added across lanes);
+ *   - three queries or more (and d a multiple of 16): ONE pass over W for the whole batch on the matrix cores, 32 queries
+ *     x 64 items per wave, each score one left-to-right chain of fused multiply-adds over the d elements.
  *   W float [N][d] (16-byte aligned);  queries float [B][d] (16-byte aligned);  scores out float [B][ld], ld >= N
  * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_UNSUPPORTED (d % 4 != 0, d > 16384, B > PQ_MAX_B), PQ_ERR_ALIGN, PQ_ERR_HIP.
  */

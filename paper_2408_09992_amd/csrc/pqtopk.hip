@@ -568,15 +568,20 @@ int enqueue_fold(const ScanPlan& p, int B, int K, void* workspace, int* out_ids,
 // instructions takes as long for one tile of 32 queries as for a GPU full of them (measured at d = 512, m = 8, b = 256:
 // 5.8 us against 5.0 us at B = 256, 6.1 against 6.7 at B = 512, 6.7 against 10.8 at B = 1024, 21 against 35 at B = 4096).
 constexpr int kSubMfmaMinBatch = 448;
+constexpr int kDefaultMfmaMinBatch = 3;    // default scoring: batch from which one matrix-core pass over W beats B mat-vec passes
 
-// Eq. 4 on the matrix cores when the shape allows: rows 16-byte aligned, d/m a multiple of 16.
-bool launch_subitem_mfma(const float* queries, const float* centroids, float* S, int B, int d, int m, int b, hipStream_t st) {
+// Eq. 4 on the matrix cores when the shape allows: rows 16-byte aligned, d/m a multiple of 16.  `ldS`: floats from one
+// query's row of S to the next.
+bool launch_subitem_mfma(const float* queries, const float* centroids, float* S, int B, int d, int m, long long b, long long ldS,
+                         hipStream_t st) {
     const int s = d / m;
-    if (B < kSubMfmaMinBatch || s % 16 != 0 || d % 4 != 0 || ((((uintptr_t)queries | (uintptr_t)centroids)) & 15) != 0) return false;
-    const dim3 grid(m * ((b + 63) / 64), (B + kSubMfmaQueries - 1) / kSubMfmaQueries);
-    if (s % 64 == 0) hipLaunchKernelGGL(subitem_scores_mfma_kernel<64>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, b);
-    else if (s % 32 == 0) hipLaunchKernelGGL(subitem_scores_mfma_kernel<32>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, b);
-    else hipLaunchKernelGGL(subitem_scores_mfma_kernel<16>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, b);
+    if (s % 16 != 0 || d % 4 != 0 || ((((uintptr_t)queries | (uintptr_t)centroids)) & 15) != 0) return false;
+    const long long jtiles = (b + 63) / 64;
+    if (m * jtiles > 2147483647LL) return false;
+    const dim3 grid((unsigned)(m * jtiles), (B + kSubMfmaQueries - 1) / kSubMfmaQueries);
+    if (s % 64 == 0) hipLaunchKernelGGL(subitem_scores_mfma_kernel<64>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, (int)b, ldS);
+    else if (s % 32 == 0) hipLaunchKernelGGL(subitem_scores_mfma_kernel<32>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, (int)b, ldS);
+    else hipLaunchKernelGGL(subitem_scores_mfma_kernel<16>, grid, dim3(kSubMfmaThreads), 0, st, queries, centroids, S, B, d, m, (int)b, ldS);
     return true;
 }
 
@@ -628,7 +633,8 @@ int pq_subitem_scores(const float* queries, const float* centroids, float* S, in
     if (B > PQ_MAX_B || m > PQ_MAX_M) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)queries & 3) || ((uintptr_t)centroids & 3) || ((uintptr_t)S & 3)) return PQ_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (!(g_force_general.load(std::memory_order_relaxed) & 4) && launch_subitem_mfma(queries, centroids, S, B, d, m, b, st))
+    if (B >= kSubMfmaMinBatch && !(g_force_general.load(std::memory_order_relaxed) & 4) &&
+        launch_subitem_mfma(queries, centroids, S, B, d, m, b, (long long)m * b, st))
         return record_hip(hipGetLastError());
     switch (d / m) {
         case 4: launch_subitem<4>(queries, centroids, S, B, d, m, b, st); break;
@@ -939,6 +945,11 @@ int pq_default_scores(const float* W, const float* queries, long long N, int B, 
     if (N < 1 || B < 1 || d < 1 || ld < N || N >= 2147483648LL) return PQ_ERR_SHAPE;
     if (B > PQ_MAX_B || d % 4 != 0 || (size_t)d * sizeof(float) > 64 * 1024) return PQ_ERR_UNSUPPORTED;
     if (((uintptr_t)W & 15) || ((uintptr_t)queries & 15) || ((uintptr_t)scores & 3)) return PQ_ERR_ALIGN;
+    // batches: one pass over W for all queries, on the matrix cores (the same kernel as Eq. 4: one split, the items in
+    // the place of the sub-ids); a single query, or a shape that kernel does not take: one mat-vec pass per query
+    if (B >= kDefaultMfmaMinBatch && !(g_force_general.load(std::memory_order_relaxed) & 4) &&
+        launch_subitem_mfma(queries, W, scores, B, d, 1, N, ld, static_cast<hipStream_t>(stream)))
+        return record_hip(hipGetLastError());
     long long blocks = (N + kDefaultThreads / 16 - 1) / (kDefaultThreads / 16);
     if (blocks > 16 * kAssumedCUs) blocks = 16 * kAssumedCUs;
     hipLaunchKernelGGL(default_scores_kernel, dim3((unsigned)blocks, B), dim3(kDefaultThreads), (size_t)d * sizeof(float),

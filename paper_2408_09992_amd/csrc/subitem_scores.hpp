@@ -120,7 +120,9 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_batched_kernel(con
 // memory; each wave's 32 query chunks) to LDS with consecutive lanes on consecutive 16 bytes, rows padded to 68 floats
 // (a lane's row then starts four banks after its neighbour's), and lanes read their rows from there.
 // grid = (m * ceil(b / 64), ceil(B / 128)).  Rows of queries and centroids must be 16-byte aligned and d/m a multiple
-// of 16; chunks of CH elements are staged at a time.
+// of 16; chunks of CH elements are staged at a time.  Query q's row of S starts at S + q * ldS (ldS = m * b for Eq. 4).
+// The default scoring r = W phi of Section 2 (Eq. 3) is the same product with one split and the items in the place of
+// the sub-ids (m = 1, b = |I|, centroids = W): pq_default_scores() runs this kernel for batches.
 typedef float floatx32 __attribute__((ext_vector_type(32)));
 constexpr int kSubMfmaThreads = 256;
 constexpr int kSubMfmaQueries = 32 * (kSubMfmaThreads / kWave);   // queries per workgroup
@@ -129,7 +131,8 @@ constexpr int kSubMfmaPad = 4;                                    // floats adde
 template <int CH>   // elements staged at a time: 16, 32 or 64
 __global__ __launch_bounds__(kSubMfmaThreads) void subitem_scores_mfma_kernel(const float* __restrict__ queries,
                                                                             const float* __restrict__ centroids,
-                                                                            float* __restrict__ S, int B, int d, int m, int b) {
+                                                                            float* __restrict__ S, int B, int d, int m, int b,
+                                                                            long long ldS) {
     constexpr int ROW = CH + kSubMfmaPad, NW = kSubMfmaThreads / kWave, C4 = CH / 4;   // C4: 16-byte pieces of a staged row
     __shared__ __align__(16) float psi[64 * ROW];
     __shared__ __align__(16) float phi[NW][32 * ROW];
@@ -137,10 +140,13 @@ __global__ __launch_bounds__(kSubMfmaThreads) void subitem_scores_mfma_kernel(co
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int jtiles = (b + 63) / 64;
     const int k = blockIdx.x / jtiles, j0 = (blockIdx.x % jtiles) * 64;
-    const int q0 = blockIdx.y * kSubMfmaQueries + wave * 32;   // (a wave past the batch stages repeats and stores nothing)
+    const int q0 = blockIdx.y * kSubMfmaQueries + wave * 32;
+    const bool active = q0 < B;                                // (a wave past the batch only helps staging the embeddings)
     floatx32 acc;
 #pragma unroll
     for (int v = 0; v < 32; ++v) acc[v] = 0.0f;
+    // (Issuing the next chunk's loads before this chunk's matrix instructions, through registers, was measured and is
+    // slower: the extra registers cost more than the overlap gains; two or three workgroups per CU overlap instead.)
     for (int c = 0; c < s; c += CH) {
         if (c != 0) __syncthreads();                           // the previous chunk has been read
         // sub-item embeddings j0 .. j0 + 63, elements c .. c + CH - 1 (rows past b repeat the last one)
@@ -152,12 +158,13 @@ __global__ __launch_bounds__(kSubMfmaThreads) void subitem_scores_mfma_kernel(co
         }
         // this wave's 32 query chunks
 #pragma unroll
-        for (int p = lane; p < 32 * C4; p += kWave) {
+        for (int p = lane; active && p < 32 * C4; p += kWave) {
             const int row = p / C4, piece = p % C4, q = min(q0 + row, B - 1);
             const float4 x = reinterpret_cast<const float4*>(queries + (size_t)q * d + (size_t)k * s + c)[piece];
             *reinterpret_cast<float4*>(&phi[wave][row * ROW + 4 * piece]) = x;
         }
         __syncthreads();
+        if (!active) continue;
         float av[CH], bv[CH];
 #pragma unroll
         for (int i = 0; i < C4; ++i) {
@@ -172,6 +179,6 @@ __global__ __launch_bounds__(kSubMfmaThreads) void subitem_scores_mfma_kernel(co
 #pragma unroll
     for (int v = 0; v < 32; ++v) {
         const int qq = q0 + 8 * ((v % 16) / 4) + 4 * (lane / 32) + v % 4, jj = j0 + 32 * (v / 16) + (lane & 31);
-        if (qq < B && jj < b) S[((size_t)qq * m + k) * b + jj] = acc[v];
+        if (qq < B && jj < b) S[(size_t)qq * ldS + (size_t)k * b + jj] = acc[v];
     }
 }

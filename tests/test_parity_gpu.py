@@ -756,8 +756,12 @@ def test_recjpq_scores_equal_algorithm_1(pq, oracle, N, m, b, B):
     assert np.array_equal(ids.cpu().numpy(), rid)
 
 
-@pytest.mark.parametrize("N,d,m,b,B", [(1, 8, 2, 4, 1), (1000, 64, 4, 256, 2), (4099, 96, 3, 7, 1), (200_000, 512, 8, 256, 2)])
+@pytest.mark.parametrize("N,d,m,b,B", [(1, 8, 2, 4, 1), (1000, 64, 4, 256, 2), (4099, 96, 3, 7, 1), (200_000, 512, 8, 256, 2),
+                                       (70_001, 512, 8, 256, 17), (30_000, 96, 3, 7, 64), (5_003, 512, 8, 256, 130),
+                                       (999, 8, 2, 4, 5)])
 def test_default_scoring_against_float64(pq, oracle, N, d, m, b, B):
+    # (batches of two and more take one pass over W on the matrix cores when d is a multiple of 16; a single query, and
+    # d = 8, take the mat-vec kernel once per query)
     cent = W.centroids(m, b, d, seed=N)
     Q = W.queries(B, d, seed=N)
     G = W.codes_uniform(N, m, b, seed=N)
