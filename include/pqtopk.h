@@ -116,7 +116,8 @@ int pq_score_topk_static(const uint8_t* codes, const float* S, long long N, int 
  * nextpow2(K + 64) bytes) fit 160 KB, e.g. m * b <= 36864 at K = 10 (m = 8: b <= 4608); a larger table is read where
  * it lies, in device memory (it stays in L2; several times slower per lookup, sub-ids clamped to b - 1).  Rows of 8,
  * 16 or 32 bytes (m = 4, 8, 16) are scanned as 16-byte vectors; any other m row by row.  Every query of a batch scans
- * the codebook by itself (no shared pass).  A sub-id >= b reads an unspecified table or LDS word (never outside them).
+ * the codebook by itself (no shared pass).  A sub-id >= b makes the result unspecified, but no device memory outside the
+ * arguments is touched: lookups in device memory are clamped to the table, lookups in LDS stay in LDS.
  * Errors: as pq_score_topk(), with PQ_ERR_SHAPE for b > 65536.
  */
 size_t pq_score_topk_u16_workspace_bytes(long long N, int B, int m, int b, int K);

@@ -45,6 +45,22 @@ __device__ __forceinline__ uint64_t make_key(float score, uint32_t id) {
     return ((uint64_t)orderable_bits(score) << 32) | (uint32_t)(~id);
 }
 
+// Words in LDS that one wave writes while other waves of the workgroup read them with no barrier in between (shared
+// floors, "something changed" flags, histogram counters that other waves update with atomic adds): relaxed atomic
+// accesses at workgroup scope.  They compile to the plain LDS loads and stores, but the compiler may neither tear,
+// repeat nor hoist them.  Any value such a read returns is one that was stored at some time, which is all the users
+// need (every floor ever stored is a valid floor).
+template <typename T>
+__device__ __forceinline__ T lds_peek(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+template <typename T>
+__device__ __forceinline__ void lds_poke(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+// four consecutive histogram counters (16-byte aligned) that other waves may be incrementing: two 8-byte atomic loads
+__device__ __forceinline__ uint4 lds_peek_counters4(const uint32_t* p) {
+    const unsigned long long a = lds_peek(reinterpret_cast<const unsigned long long*>(p));
+    const unsigned long long b = lds_peek(reinterpret_cast<const unsigned long long*>(p) + 1);
+    return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
+}
+
 // Ordering point between LDS accesses of the lanes of ONE wave (LDS serves a wave's requests in issue order).
 __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

@@ -53,37 +53,23 @@ __global__ __launch_bounds__(NT) void fold_topk_kernel(FoldArgs a) {
         }
     };
 
-    // score range of all the keys (empty slots of short lists are 0); a modest number of keys stays in registers
+    // score range of all the keys (empty slots of short lists are 0).  The host never gives a workgroup more keys than
+    // its registers hold (nkeys <= NT * REGS: fold_lists_per_group()).
     const int lane = tid & (kWave - 1);
-    const bool in_regs = nkeys <= (long long)NT * REGS;
     uint64_t keys[REGS];
     float mn = __builtin_inff(), mx = -__builtin_inff();
-    if (in_regs) {
 #pragma unroll
-        for (int r = 0; r < REGS; ++r) {
-            const long long i = (long long)r * NT + tid;
-            keys[r] = (i < nkeys) ? key_at(i) : 0ull;
-            if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
-        }
-    } else {
-        for (long long i0 = tid; i0 < nkeys; i0 += 8LL * NT) {          // eight loads in flight per thread
-            uint64_t kk[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const long long i = i0 + (long long)j * NT;
-                kk[j] = i < nkeys ? key_at(i) : 0ull;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (kk[j]) { float s = score_of_key(kk[j]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
-        }
+    for (int r = 0; r < REGS; ++r) {
+        const long long i = (long long)r * NT + tid;
+        keys[r] = (i < nkeys) ? key_at(i) : 0ull;
+        if (keys[r]) { float s = score_of_key(keys[r]); mn = fminf(mn, s); mx = fmaxf(mx, s); }
     }
     for (int i = tid; i < kBins; i += NT) hist[i] = 0;
     stamp<STAMP>(rec, kStampLoaded, lane);
     float lo, scale;
     set_range<NT / kWave>(mn, mx, ctl, tid, lo, scale);
 
-    if (in_regs) {
+    {
         // one pass: histogram, cut, collect the few keys at or above the cut, rank them
         int bk[REGS];
 #pragma unroll
@@ -114,55 +100,6 @@ __global__ __launch_bounds__(NT) void fold_topk_kernel(FoldArgs a) {
             return;
         }
         // too many keys share the cut bucket (heavy ties): take the staged, sorting path below
-    } else {
-        // many keys (many workgroups times a large K): the same three steps, with the keys re-read from the workspace
-        // (they sit in L2) instead of held in registers: histogram, cut, collect, rank
-        constexpr int kBatch = 8;                            // loads in flight per thread (the passes are latency-bound)
-        auto for_each_key = [&](auto&& f) {
-            for (long long i0 = tid; i0 < nkeys; i0 += (long long)kBatch * NT) {
-                uint64_t kk[kBatch];
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) {
-                    const long long i = i0 + (long long)j * NT;
-                    kk[j] = i < nkeys ? key_at(i) : 0ull;
-                }
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j)
-                    if (kk[j]) f(kk[j]);
-            }
-        };
-        for_each_key([&](uint64_t key) { atomicAdd(&hist[bucket_of(score_of_key(key), lo, scale)], 1u); });
-        __syncthreads();
-        if (tid < kWave) find_cut(hist, K, ctl, lane);
-        __syncthreads();
-        const int bstar = ctl->bstar;
-        for (long long i0 = tid; i0 - tid < nkeys; i0 += (long long)kBatch * NT) {   // (whole waves stay in the loop)
-            uint64_t kk[kBatch];
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                const long long i = i0 + (long long)j * NT;
-                kk[j] = i < nkeys ? key_at(i) : 0ull;
-            }
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {               // kept keys are compacted per wave: one counter update each
-                const bool take = kk[j] != 0ull && bucket_of(score_of_key(kk[j]), lo, scale) >= bstar;
-                const uint64_t mask = __ballot(take);
-                if (mask == 0) continue;
-                int base = 0;
-                if (lane == 0) base = atomicAdd(&ctl->ncand, __popcll(mask));
-                base = __builtin_amdgcn_readfirstlane(base);
-                const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
-                if (take && pos < a.candmax) cand[pos] = kk[j];
-            }
-        }
-        __syncthreads();
-        const int C = ctl->ncand;
-        if (C <= a.candmax) {
-            rank_select<NT>(cand, C, K, sorted, tid);
-            emit(sorted);
-            return;
-        }
-        __syncthreads();                                     // (cand and hist are reused below)
     }
 
     int keep = 0;                                            // best-so-far keys carried at the front of stage

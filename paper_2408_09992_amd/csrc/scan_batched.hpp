@@ -33,15 +33,15 @@ struct FloorState {
     int dirty;           // a score was counted since the floor was last derived
     int pad;
 };
-// (the floors themselves are kQ floats of their own, read once per round by kQ lanes of each wave; a racing store may
-// lower one briefly, which is still a valid floor)
+// (the floors themselves are kQ floats of their own, read once per round by kQ lanes of each wave with relaxed atomic
+// accesses; a racing store may lower one briefly, which is still a valid floor)
 
 // One wave: the floor the histogram allows (see above), -inf if it counts fewer than K scores.  Same value in all lanes.
 __device__ __forceinline__ float floor_from_hist(const uint32_t* hist, int K, float lo, float scale, int lane) {
     constexpr int per = kFloorBins / kWave;                  // buckets per lane; lane 0 owns the top ones
     const int first = kFloorBins - per * (lane + 1);
-    const uint4 v = *reinterpret_cast<const uint4*>(hist + first);
-    static_assert(per == 4, "one 16-byte read per lane");
+    const uint4 v = lds_peek_counters4(hist + first);          // (other waves may be counting into the histogram)
+    static_assert(per == 4, "four counters per lane");
     const uint32_t mine = v.x + v.y + v.z + v.w;
     const uint32_t upto = wave_prefix_sum(mine);
     const uint64_t has = __ballot(upto >= (uint32_t)K);
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     auto offer_round = [&](const float (&sc)[kQ][kItems], long long rr, int vt, const int* bk, const int* bstar) {
         const bool inside = rr < inside_rounds;
         // the kQ floors: read by kQ lanes only (an LDS read costs by the lane), then handed to the whole wave
-        const int my_floor = lane < kQ ? __float_as_int(sfloor[lane]) : 0;
+        const int my_floor = lane < kQ ? __float_as_int(lds_peek(&sfloor[lane])) : 0;
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
             if (q >= nq) continue;
@@ -390,7 +390,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
                         atomicAdd(&fhist[q * kFloorBins + bucket_of<kFloorBins>(sc[q][e], flo, fscale)], 1u);
                 }
                 cnt[q] += n;
-                if (bk == nullptr && lane == 0) fstate[q].dirty = 1;
+                if (bk == nullptr && lane == 0) lds_poke(&fstate[q].dirty, 1);
             }
             if (stop < kItems || (a.prune_at != 0 && cnt[q] >= a.prune_at)) {
                 Slots<kItems> s;
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
                 wave_sync();
                 offer_slow<kItems>(&my_state[q], buf, a.cap, K, a.prune_at, s, lane);
                 cnt[q] = __builtin_amdgcn_readfirstlane(my_state[q].cnt);
-                if (lane == 0 && my_state[q].floor_ge > sfloor[q]) sfloor[q] = my_state[q].floor_ge;   // the wave's K-th best
+                if (lane == 0 && my_state[q].floor_ge > lds_peek(&sfloor[q])) lds_poke(&sfloor[q], my_state[q].floor_ge);   // the wave's K-th best
             }
         }
     };
@@ -415,11 +415,11 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     auto refresh_floors = [&]() {
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
-            if (q >= nq || fstate[q].dirty == 0) continue;
-            if (lane == 0) fstate[q].dirty = 0;               // before the histogram is read: a count that lands
+            if (q >= nq || lds_peek(&fstate[q].dirty) == 0) continue;
+            if (lane == 0) lds_poke(&fstate[q].dirty, 0);     // before the histogram is read: a count that lands
             wave_sync();                                      // later sets it again
             const float f = floor_from_hist(fhist + q * kFloorBins, K, fstate[q].lo, fstate[q].scale, lane);
-            if (lane == 0 && f > sfloor[q]) sfloor[q] = f;
+            if (lane == 0 && f > lds_peek(&sfloor[q])) lds_poke(&sfloor[q], f);
         }
     };
     int turn = wave;                                          // rounds until this wave's next refresh

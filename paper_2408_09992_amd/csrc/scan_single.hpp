@@ -462,12 +462,12 @@ __global__ __launch_bounds__(NT, 4) void scan_topk_kernel(ScanArgs a) {
     // what a round's scores offer to the wave's list: everything at or above its floor
     auto offer = [&](const float (&sc)[kItems], uint32_t rr, int vt) {
         if (wide_floor) {
-            top.floor_ge = fmaxf(top.floor_ge, ctl->shared_floor);
+            top.floor_ge = fmaxf(top.floor_ge, lds_peek(&ctl->shared_floor));
             if (--turn < 0) {
                 gap += gap >> 2;
                 turn = gap;
                 const float f = floor_of_hist<kBins>(L.hist, K, hlo, hscale, lane);
-                if (lane == 0 && f > ctl->shared_floor) ctl->shared_floor = f;   // (a racing lower store is still a floor)
+                if (lane == 0 && f > lds_peek(&ctl->shared_floor)) lds_poke(&ctl->shared_floor, f);   // (a racing lower store is still a floor)
                 top.floor_ge = fmaxf(top.floor_ge, f);
             }
         }

@@ -129,7 +129,7 @@ __device__ __forceinline__ float floor_of_hist(const uint32_t* hist, int K, floa
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < per; i += 4) {
-        const uint4 v = *reinterpret_cast<const uint4*>(hist + first + i);
+        const uint4 v = lds_peek_counters4(hist + first + i);  // (other waves may be counting into the histogram)
         c[i] = v.x; c[i + 1] = v.y; c[i + 2] = v.z; c[i + 3] = v.w;
         mine += v.x + v.y + v.z + v.w;
     }
