@@ -53,14 +53,34 @@ def cpu_baseline(G, cent, Q, K, budget_s=12.0):
 
 
 def measured_traffic(workload: str):
-    """HBM bytes per scan launch from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, each scaled by a
-    plain copy of known size), if this workload has been profiled; else None.  Counters cannot be read in-process."""
+    """HBM bytes per scan launch of this workload as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, each scaled by a
+    plain copy of known size), with where the figure comes from.  Counters cannot be read in-process: the figure is the
+    one recorded in profiles/pmc_traffic.json from the --pmc runs whose summaries lie beside it (it describes the
+    kernel as it was when those runs were made), or None for a workload that has not been profiled."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get("traffic_bytes_per_launch")
+            rec = json.load(f).get(workload)
     except (OSError, ValueError):
-        return None
+        rec = None
+    if not rec:
+        return None, "not profiled: no rocprofv3 --pmc run of this workload is recorded in profiles/pmc_traffic.json"
+    return rec.get("traffic_bytes_per_launch"), \
+        f"recorded, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in {rec.get('source')}"
+
+
+def measured_lds_peak(pq, torch):
+    """Random 16-byte gathers from a 32 KB table in LDS, 16 waves per CU (the batched scan's lookup pattern with nothing
+    else going on), measured now: GB/s over the whole chip."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    rounds = 16 * 256
+    best = 0.0
+    for threads, per_cu in ((512, 2), (1024, 1)):
+        pq.pq_measure_lds_gather(16, 32768, rounds, False, cus * per_cu, threads, 3, sink)
+        ms = sorted(pq.pq_measure_lds_gather(16, 32768, rounds, False, cus * per_cu, threads, 10, sink) for _ in range(5))[2]
+        best = max(best, cus * per_cu * threads * rounds * 16.0 / (ms * 1e-3) / 1e9)
+    return best
 
 
 def sweep(args):
@@ -295,6 +315,64 @@ def wide_mode(args):
         "wide": points}))
 
 
+def variants_mode(args):
+    """The step of --config at batch 1 under each choice of kernels the library has for a small K: the short scan and
+    the small fold (what it runs), and each of them replaced by the general kernel (pq_measure_force_general).  Every
+    variant: steady-state time per step over --steps steps, parity with the oracle, one step at a time.  Run under
+    rocprofv3 --kernel-trace --stats, the kernels of all variants show up under their own names."""
+    import numpy as np
+    import torch
+    from oracle import pq_oracle
+    from paper_2408_09992_amd import binding as pq, workloads as W
+
+    cfg = W.CONFIGS[args.config]
+    G, cent, Q = W.make(cfg, B=1)
+    N, m, b, d = cfg.N, cfg.m, cfg.b, cfg.d
+    Gd, Cd, Qd = torch.from_numpy(G).cuda(), torch.from_numpy(cent).cuda(), torch.from_numpy(Q).cuda()
+    Sd = torch.empty((1, m, b), dtype=torch.float32, device="cuda")
+    rows = []
+    names = {0: "short scan + small fold (the library's choice)", 1: "general scan + small fold", 2: "short scan + general fold",
+             3: "general scan + general fold"}
+    try:
+        for K in (1, 10, 31):
+            rid, rsc = pq_oracle.pqtopk(G, cent, Q, K)
+            for mask in (0, 1, 2, 3):
+                pq.pq_measure_force_general(mask)
+                ws = torch.empty(pq.pq_score_topk_workspace_bytes(N, 1, m, b, K), dtype=torch.uint8, device="cuda")
+                ids = torch.empty((1, K), dtype=torch.int32, device="cuda")
+                sc = torch.empty((1, K), dtype=torch.float32, device="cuda")
+                sub = pq.PreparedSubitemScores(Qd, Cd, out=Sd)
+                top = pq.PreparedScoreTopK(Gd, Sd, K, workspace=ws, out_ids=ids, out_scores=sc)
+                t_warm = time.perf_counter()
+                while time.perf_counter() - t_warm < 0.05:
+                    for _ in range(200):
+                        sub(); top()
+                    torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    sub(); top()
+                torch.cuda.synchronize()
+                us = (time.perf_counter() - t0) / args.steps * 1e6
+                lat = []
+                for _ in range(200):
+                    t1 = time.perf_counter()
+                    sub(); top()
+                    torch.cuda.synchronize()
+                    lat.append((time.perf_counter() - t1) * 1e6)
+                parity = bool(np.array_equal(ids.cpu().numpy(), rid) and
+                              np.all(np.abs(sc.cpu().numpy() - rsc) <= 1e-5 * np.maximum(np.abs(rsc), 1.0)))
+                rows.append({"K": K, "variant": names[mask], "mask": mask, "us_per_step": us,
+                             "one_at_a_time_median_us": float(np.median(lat)), "parity_vs_oracle": parity})
+                print(f"K={K:3d} {names[mask]:48s} {us:7.2f} us/step  one at a time {np.median(lat):7.2f} us  parity {parity}",
+                      file=sys.stderr, flush=True)
+    finally:
+        pq.pq_measure_force_general(0)
+    best = min(r["us_per_step"] for r in rows if r["K"] == 10)
+    print(json.dumps({"metric": "step time under each choice of kernels (PQTopK, batch 1)", "value": best, "unit": "us/step (K = 10, best variant)",
+                      "n_gpus": 1, "steps": args.steps, "higher_is_better": False, "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} batch=1, K in (1, 10, 31)"}, "variants": rows}))
+
+
 def breakdown_mode(args):
     """Where the time of a step goes: the three launches of a single-query step (Eq. 4, scan, fold) are run with the
     kernels' stamping instances (wall-clock stamps at fixed points, lane 0 of every wave), back to back as in the timed
@@ -464,6 +542,8 @@ def main():
                     "single-query step on --config (m = 8 only)")
     ap.add_argument("--breakdown-samples", type=int, default=20)
     ap.add_argument("--breakdown-steps", type=int, default=50)
+    ap.add_argument("--variants", action="store_true", help="step time of --config at batch 1 with the short scan / small fold "
+                    "and with the general kernels in their place")
     ap.add_argument("--yardsticks", action="store_true", help="machine yardsticks: empty launch, plain streaming read, "
                     "random gathers from LDS")
     ap.add_argument("--sweep-max-bytes", type=float, default=16e9, help="largest code matrix the sweep allocates")
@@ -490,6 +570,9 @@ def main():
         return
     if args.yardsticks:
         yardsticks_mode(args)
+        return
+    if args.variants:
+        variants_mode(args)
         return
 
     import numpy as np
@@ -525,9 +608,11 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    warmup_run = args.warmup
     while time.perf_counter() - t_warm < 0.03:             # (untimed) a GPU that was idle needs ~20 ms of work before
         for _ in range(50):                                 # its clocks settle, however few warm-up steps were asked for
             step()
+        warmup_run += 50                                    # (reported: `warmup_steps_run`)
         torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -537,10 +622,11 @@ def main():
 
     # parity of the timed run's own output, against the oracle
     from oracle import pq_oracle
-    rid, rsc = pq_oracle.pqtopk(G, cent, Q[:min(B, 8)], K)
-    got_ids, got_sc = ids.cpu().numpy(), sc.cpu().numpy()
-    parity = bool(np.array_equal(got_ids[:len(rid)], rid) and
-                  np.all(np.abs(got_sc[:len(rid)] - rsc) <= 1e-5 * np.maximum(np.abs(rsc), 1.0)))
+    # (every query of the batch up to 128; of a larger batch 128 spread evenly, the first and the last among them)
+    checked = np.arange(B) if B <= 128 else np.unique(np.linspace(0, B - 1, 128).round().astype(np.int64))
+    rid, rsc = pq_oracle.pqtopk(G, cent, np.ascontiguousarray(Q[checked]), K)
+    got_ids, got_sc = ids.cpu().numpy()[checked], sc.cpu().numpy()[checked]
+    parity = bool(np.array_equal(got_ids, rid) and np.all(np.abs(got_sc - rsc) <= 1e-5 * np.maximum(np.abs(rsc), 1.0)))
 
     # the scan kernel's own duration: median of five back-to-back sequences.  The oracle run above left the GPU idle
     # for tens of milliseconds, so its clocks are brought back up first (untimed).
@@ -597,18 +683,19 @@ def main():
 
     ms_per_step = el / args.steps * 1e3
     workload = f"{cfg.name}: N={N} d={d} m={m} b={b} K={K} batch={B}, codes {cfg.codes}, seed {cfg.seed}"
+    traffic, traffic_source = measured_traffic(workload)
     out = {
         "metric": "items scored/sec (PQTopK, whole path incl. top-K)",
         "value": N * B * args.steps / el,
         "unit": "items/s",
         "queries_per_s": B * args.steps / el,
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "warmup_steps_run": warmup_run, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": workload},
-        "parity_vs_oracle": parity,
+        "parity_vs_oracle": parity, "parity_queries_checked": int(len(checked)),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "catalogue scan (Eq. 5 + per-workgroup top-K)", "kernel_ms": scan_ms,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "read_kernel_GBps": read_gbs, "frac_of_read_kernel": achieved / read_gbs,
@@ -623,10 +710,16 @@ def main():
     }
     if B > 1:
         # a batch re-uses every code byte B times: the table lookups (4 bytes gathered from LDS per split, item and
-        # query), not HBM, bound the scan; reported beside the HBM figure, against what the LDS can return at best
+        # query), not HBM, bound the scan; reported beside the HBM figure, against what the LDS returns at best on paper
+        # (`peak`: 128 bytes per clock and CU) and against what random 16-byte gathers get out of it on this machine,
+        # measured by this run (`measured_peak`; the batched kernel reads four queries' values with one such gather)
         lds_bytes = 4.0 * m * N * B
-        out["lds_gather"] = {"bound": "lds", "achieved": lds_bytes / (scan_ms * 1e-3) / 1e9, "peak": LDS_PEAK_GBS,
-                             "unit": "GB/s", "frac": lds_bytes / (scan_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
+        lds_achieved = lds_bytes / (scan_ms * 1e-3) / 1e9
+        lds_measured = measured_lds_peak(pq, torch)
+        out["lds_gather"] = {"bound": "lds", "achieved": lds_achieved, "peak": LDS_PEAK_GBS,
+                             "unit": "GB/s", "frac": lds_achieved / LDS_PEAK_GBS,
+                             "measured_peak": lds_measured, "frac_of_measured": lds_achieved / lds_measured,
+                             "measured_peak_what": "random 16-byte gathers from a 32 KB LDS table, 16 waves per CU, nothing else (pq_measure_lds_gather)",
                              "algorithmic_bytes_per_launch": lds_bytes}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(G, cent, Q, K)

@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     auto ctl_of = [&](int q) { return reinterpret_cast<Ctl*>(pctl + (size_t)q * align16(sizeof(Ctl))); };
     const TileLds tl{hist, pctl, states, lists, cand, sorted, best, kpad, sfloor, fhist, fstate};
 
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;   // (set again after the streaming loop)
     const int q0 = blockIdx.y * kQ, nblk = gridDim.x, K = a.K, b = a.b;
     const int nq = (B - q0 < kQ) ? B - q0 : kQ;               // queries of this tile that exist
     // The rounds cover the code vectors that lie wholly inside the catalogue (at least one: the host sends smaller
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
     const long long round_units = (long long)kThreads * kTileVecs;
     const long long rounds = (total_units + round_units - 1) / round_units;
     const long long inside_rounds = total_units / round_units;
-    WaveQ* const my_state = states + wave * kQ;
+    WaveQ* my_state = states + wave * kQ;
     auto list_of = [&](int q) { return lists + ((size_t)q * kWaves + wave) * a.cap; };
 
     // a round's code vectors: always kTileVecs plain 16-byte loads, the index clamped to the last whole vector (no
@@ -520,6 +520,14 @@ __global__ __launch_bounds__(kThreads) void scan_topk_tiled_kernel(ScanArgs a, i
             if (turn < 0) { gap += gap >> 2; turn += gap; refresh_floors(); }
         }
     }
+    // What the code after the loop needs of the thread's own addresses is derived afresh from the thread index: kept
+    // alive over the loop, which has no register to spare, two of them went to scratch memory and back (8 bytes per
+    // lane: a megabyte of write-back per launch).
+    tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    lane = tid & (kWave - 1);
+    wave = tid / kWave;
+    my_state = states + wave * kQ;
     // the fewer than 16 / M items after the last whole code vector: one per lane of one wave, per query
     if (blockIdx.x == 0 && wave == 0 && n_scan < a.N) {
         const long long item = n_scan + lane;
