@@ -119,7 +119,11 @@ def sweep(args):
                 sub(); top()
             torch.cuda.synchronize()
             el = (time.perf_counter() - t0) / steps
-            scan_ms = pq.pq_score_topk_profile(Gd, sub.S, K, max(3, min(50, steps)), workspace=top.workspace)
+            n_prof = max(3, min(50, steps))
+            t_warm = time.perf_counter()                     # (untimed: the scan kernel alone until the clocks have settled)
+            while time.perf_counter() - t_warm < 0.02:
+                pq.pq_score_topk_profile(Gd, sub.S, K, n_prof, workspace=top.workspace)
+            scan_ms = sorted(pq.pq_score_topk_profile(Gd, sub.S, K, n_prof, workspace=top.workspace) for _ in range(5))[2]
             parity = None
             if N * m <= args.sweep_check_bytes:
                 rid, rsc = pq_oracle.score_topk(Gd.cpu().numpy(), sub.S.cpu().numpy(), K)

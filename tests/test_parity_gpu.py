@@ -391,9 +391,11 @@ def test_short_scan_and_small_fold_against_the_general_kernels(pq, oracle):
 
 
 def test_small_fold_many_lists(pq, oracle):
-    # the small-K fold with both of its instances: up to 3072 and up to 6144 keys per query (256 lists of K = 10, 24),
+    # the small-K fold with both of its instances: up to 3072 and up to 6144 keys per query (256 lists of K = 10, 24; with
+    # K = 28, 31 the 256 lists go to the general fold: a third instance of 16 keys per thread was slower than it),
     # a batch of queries folded side by side, and lists with empty slots (fewer than K items in a workgroup's share)
-    for N, B, K in ((1_280_000, 1, 24), (2_000_003, 2, 12), (1_280_001, 2, 31), (300, 1, 10), (70_000, 5, 31)):
+    for N, B, K in ((1_280_000, 1, 24), (2_000_003, 2, 12), (1_280_001, 2, 31), (300, 1, 10), (70_000, 5, 31),
+                    (1_280_000, 1, 31), (1_280_003, 1, 28)):
         G = W.codes_uniform(N, 8, 256, seed=N % 97)
         assert_same_topk(pq, oracle, G, tables(N % 89, B, 8, 256), K, "small fold")
 
