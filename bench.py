@@ -377,6 +377,128 @@ def variants_mode(args):
                       "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} batch=1, K in (1, 10, 31)"}, "variants": rows}))
 
 
+def kcost_mode(args):
+    """What K costs on --config at --batch: for K in 1, 10, 100, 512 the scan kernel alone (HIP events around back-to-back
+    launches) and the whole pq_score_topk call (scan + fold, enqueued back to back), each result compared with the oracle
+    (all queries of the batch up to 8)."""
+    import numpy as np
+    import torch
+    from oracle import pq_oracle
+    from paper_2408_09992_amd import binding as pq, workloads as W
+
+    cfg = W.CONFIGS[args.config]
+    B = args.batch if args.batch is not None else cfg.batches[0]
+    G, cent, Q = W.make(cfg, B=B)
+    N, m, b, d = cfg.N, cfg.m, cfg.b, cfg.d
+    Gd, Cd, Qd = torch.from_numpy(G).cuda(), torch.from_numpy(cent).cuda(), torch.from_numpy(Q).cuda()
+    sub = pq.PreparedSubitemScores(Qd, Cd)
+    sub()
+    torch.cuda.synchronize()
+    S_host = sub.S.cpu().numpy()
+    rows = []
+    for K in (1, 10, 100, 512):
+        top = pq.PreparedScoreTopK(Gd, sub.S, K)
+        iters = int(max(5, min(1000, 2e8 / (float(N) * B))))
+        t_warm = time.perf_counter()
+        while time.perf_counter() - t_warm < 0.03:
+            for _ in range(iters):
+                top()
+            torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        calls = []
+        for _ in range(5):
+            e0.record()
+            for _ in range(iters):
+                top()
+            e1.record()
+            torch.cuda.synchronize()
+            calls.append(e0.elapsed_time(e1) / iters * 1e3)
+        n_prof = max(3, min(50, iters))
+        scan_us = sorted(pq.pq_score_topk_profile(Gd, sub.S, K, n_prof, workspace=top.workspace) for _ in range(5))[2] * 1e3
+        nq = min(B, 8)
+        rid, rsc = pq_oracle.score_topk(G, S_host[:nq], K)
+        parity = bool(np.array_equal(top.ids.cpu().numpy()[:nq], rid) and
+                      np.array_equal(top.scores.cpu().numpy()[:nq].view(np.uint32), rsc.view(np.uint32)))
+        rows.append({"K": K, "scan_kernel_us": scan_us, "pq_score_topk_us": sorted(calls)[2], "parity_vs_oracle": parity})
+        print(f"{cfg.name} B={B} K={K:3d}  scan {scan_us:9.2f} us  scan + fold {sorted(calls)[2]:9.2f} us  parity {parity}",
+              file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "cost of K: scan kernel and pq_score_topk call", "value": rows[1]["pq_score_topk_us"], "unit": "us (K = 10)",
+                      "n_gpus": 1, "higher_is_better": False, "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b} batch={B}, K in (1, 10, 100, 512)"}, "kcost": rows}))
+
+
+def matrix_cores_mode(args):
+    """The two dense contractions beside the scan, on the matrix cores and on the scalar kernels
+    (pq_measure_force_general bit 2): Eq. 4 over batch sizes (chains of K = 1 fp32 matrix instructions, bit-equal to the
+    fused chain: checked against the oracle), and the default scorer W phi (Eq. 3) for batches on the headline catalogue
+    (2.62 GB embedding matrix read once per batch instead of once per query)."""
+    import numpy as np
+    import torch
+    from oracle import pq_oracle
+    from paper_2408_09992_amd import binding as pq, workloads as W
+
+    cfg = W.CONFIGS[args.config]
+    N, m, b, d = cfg.N, cfg.m, cfg.b, cfg.d
+    G, cent, Q = W.make(cfg, B=4096)
+    Gd, Cd = torch.from_numpy(G).cuda(), torch.from_numpy(cent).cuda()
+
+    def timed(fn, n):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t = []
+        for _ in range(3):
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            t.append(e0.elapsed_time(e1) / n * 1e3)
+        return sorted(t)[1]
+
+    eq4, default = [], []
+    try:
+        for B in (1, 64, 256, 448, 1024, 4096):
+            Qd = torch.from_numpy(np.ascontiguousarray(Q[:B])).cuda()
+            sub = pq.PreparedSubitemScores(Qd, Cd)
+            res = {}
+            for mask in (4, 0):
+                pq.pq_measure_force_general(mask)
+                for _ in range(300):
+                    sub()
+                res[mask] = timed(sub, 500)
+            pq.pq_measure_force_general(0)
+            sub()
+            torch.cuda.synchronize()
+            ref = pq_oracle.subitem_scores(np.ascontiguousarray(Q[:B]), cent)
+            ok = bool(np.array_equal(sub.S.cpu().numpy().view(np.uint32), ref.view(np.uint32)))
+            eq4.append({"B": B, "scalar_kernels_us": res[4], "library_choice_us": res[0], "bit_equal_to_oracle": ok})
+            print(f"Eq. 4  B={B:5d}: scalar kernels {res[4]:7.2f} us   library's choice {res[0]:7.2f} us   bit-equal to the oracle {ok}",
+                  file=sys.stderr, flush=True)
+        Wd = pq.pq_reconstruct_items(Gd, Cd)
+        for B in (1, 2, 4, 16, 64, 128):
+            Qd = torch.from_numpy(np.ascontiguousarray(Q[:B])).cuda()
+            out = torch.empty((B, N), dtype=torch.float32, device="cuda")
+            res = {}
+            for mask in (4, 0):
+                pq.pq_measure_force_general(mask)
+                res[mask] = timed(lambda: pq.pq_default_scores(Wd, Qd, out=out), 3 if (mask == 4 and B > 4) else 10)
+                if mask == 4:
+                    ref = out.clone()
+            pq.pq_measure_force_general(0)
+            err = float((out - ref).abs().max())
+            default.append({"B": B, "matvec_per_query_us": res[4], "library_choice_us": res[0], "TFLOPs": 2.0 * N * d * B / res[0] / 1e6,
+                            "W_read_TBps": N * d * 4 / res[0] / 1e6, "max_abs_diff_between_paths": err})
+            print(f"Eq. 3  B={B:4d}: mat-vec per query {res[4]:9.1f} us   library's choice {res[0]:9.1f} us "
+                  f"({2.0 * N * d * B / res[0] / 1e6:6.1f} TFLOP/s, W at {N * d * 4 / res[0] / 1e6:5.2f} TB/s)   max |diff| {err:.2e}",
+                  file=sys.stderr, flush=True)
+    finally:
+        pq.pq_measure_force_general(0)
+    print(json.dumps({"metric": "Eq. 4 and the default scorer on the matrix cores against the scalar kernels", "value": eq4[-2]["library_choice_us"],
+                      "unit": "us (Eq. 4, B = 1024)", "n_gpus": 1, "higher_is_better": False, "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: N={N} d={d} m={m} b={b}; Eq. 4 at B = 1 .. 4096, Eq. 3 at B = 1 .. 128"},
+                      "eq4": eq4, "default_scorer": default}))
+
+
 def breakdown_mode(args):
     """Where the time of a step goes: the three launches of a single-query step (Eq. 4, scan, fold) are run with the
     kernels' stamping instances (wall-clock stamps at fixed points, lane 0 of every wave), back to back as in the timed
@@ -548,6 +670,10 @@ def main():
     ap.add_argument("--breakdown-steps", type=int, default=50)
     ap.add_argument("--variants", action="store_true", help="step time of --config at batch 1 with the short scan / small fold "
                     "and with the general kernels in their place")
+    ap.add_argument("--kcost", action="store_true", help="scan kernel and pq_score_topk call for K = 1, 10, 100, 512 on --config "
+                    "at --batch")
+    ap.add_argument("--matrix-cores", action="store_true", help="Eq. 4 and the default scorer (Eq. 3) on the matrix cores "
+                    "against the scalar kernels, over batch sizes")
     ap.add_argument("--yardsticks", action="store_true", help="machine yardsticks: empty launch, plain streaming read, "
                     "random gathers from LDS")
     ap.add_argument("--sweep-max-bytes", type=float, default=16e9, help="largest code matrix the sweep allocates")
@@ -577,6 +703,12 @@ def main():
         return
     if args.variants:
         variants_mode(args)
+        return
+    if args.kcost:
+        kcost_mode(args)
+        return
+    if args.matrix_cores:
+        matrix_cores_mode(args)
         return
 
     import numpy as np
