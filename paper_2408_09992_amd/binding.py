@@ -204,10 +204,7 @@ def pq_score_topk_subset_workspace_bytes(n_subset: int, B: int, m: int, b: int, 
     return int(lib().pq_score_topk_subset_workspace_bytes(n_subset, B, m, b, K))
 
 
-def pq_score_topk_subset(codes: torch.Tensor, S: torch.Tensor, subset: torch.Tensor, K: int,
-                         workspace: Optional[torch.Tensor] = None, out_ids: Optional[torch.Tensor] = None,
-                         out_scores: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Algorithm 1 with a candidate list V: subset int32 [n] of distinct item ids -> the K best items of the list."""
+def _subset_args(codes, S, subset, K, workspace, out_ids, out_scores):
     _dev(codes, torch.uint8, "codes")
     _dev(S, torch.float32, "S")
     _dev(subset, torch.int32, "subset")
@@ -225,6 +222,14 @@ def pq_score_topk_subset(codes: torch.Tensor, S: torch.Tensor, subset: torch.Ten
         out_scores = torch.empty((B, K), dtype=torch.float32, device=codes.device)
     _dev(out_ids, torch.int32, "out_ids")
     _dev(out_scores, torch.float32, "out_scores")
+    return n, N, B, m, b, workspace, out_ids, out_scores
+
+
+def pq_score_topk_subset(codes: torch.Tensor, S: torch.Tensor, subset: torch.Tensor, K: int,
+                         workspace: Optional[torch.Tensor] = None, out_ids: Optional[torch.Tensor] = None,
+                         out_scores: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Algorithm 1 with a candidate list V: subset int32 [n] of distinct item ids -> the K best items of the list."""
+    n, N, B, m, b, workspace, out_ids, out_scores = _subset_args(codes, S, subset, K, workspace, out_ids, out_scores)
     rc = lib().pq_score_topk_subset(codes.data_ptr(), S.data_ptr(), subset.data_ptr(), n, N, B, m, b, K,
                                     out_ids.data_ptr(), out_scores.data_ptr(), workspace.data_ptr(),
                                     workspace.numel(), _stream())
@@ -398,10 +403,25 @@ def pq_measure_step_stamps(queries: torch.Tensor, centroids: torch.Tensor, codes
     return int(grid[0]), int(grid[1])
 
 
-class PreparedSubitemScores:
-    """pq_subitem_scores with its arguments marshalled once; calling it only enqueues (for tight serving loops).
-    The tensors are kept alive by this object; `stream` is a raw hipStream_t handle (default: torch's current
-    stream at construction)."""
+class _Prepared:
+    """An entry point with its arguments marshalled once; calling the object only enqueues (for tight serving loops).
+    The tensors are kept alive by the object; `stream` is a raw hipStream_t handle (default: torch's current stream at
+    construction)."""
+
+    def _prepare(self, entry: str, keep, result, stream: Optional[int], make_args):
+        self._entry, self._keep, self._result = entry, keep, result
+        self._fn = getattr(lib(), entry)
+        self._args = make_args(ctypes.c_void_p(_stream() if stream is None else stream))
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != PQ_OK:
+            raise PQError(rc, self._entry)
+        return self._result
+
+
+class PreparedSubitemScores(_Prepared):
+    """pq_subitem_scores, marshalled once; returns S."""
 
     def __init__(self, queries: torch.Tensor, centroids: torch.Tensor, out: Optional[torch.Tensor] = None,
                  stream: Optional[int] = None):
@@ -413,91 +433,43 @@ class PreparedSubitemScores:
             raise PQError(PQ_ERR_SHAPE, "pq_subitem_scores")
         self.S = out if out is not None else torch.empty((B, m, b), dtype=torch.float32, device=queries.device)
         _dev(self.S, torch.float32, "S")
-        self._keep = (queries, centroids)
-        st = _stream() if stream is None else stream
         c = ctypes
-        self._fn = lib().pq_subitem_scores
-        self._args = (c.c_void_p(queries.data_ptr()), c.c_void_p(centroids.data_ptr()), c.c_void_p(self.S.data_ptr()),
-                      c.c_int(B), c.c_int(d), c.c_int(m), c.c_int(b), c.c_void_p(st))
-
-    def __call__(self) -> torch.Tensor:
-        rc = self._fn(*self._args)
-        if rc != PQ_OK:
-            raise PQError(rc, "pq_subitem_scores")
-        return self.S
+        self._prepare("pq_subitem_scores", (queries, centroids), self.S, stream, lambda st: (
+            c.c_void_p(queries.data_ptr()), c.c_void_p(centroids.data_ptr()), c.c_void_p(self.S.data_ptr()),
+            c.c_int(B), c.c_int(d), c.c_int(m), c.c_int(b), st))
 
 
-class PreparedScoreTopK:
-    """pq_score_topk with its arguments marshalled once (workspace and outputs allocated here if not given)."""
+class PreparedScoreTopK(_Prepared):
+    """pq_score_topk, marshalled once (workspace and outputs allocated here if not given); returns (ids, scores)."""
+    _ENTRY, _WIDE = "pq_score_topk", False
 
     def __init__(self, codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optional[torch.Tensor] = None,
                  out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
                  stream: Optional[int] = None):
-        N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores)
+        N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores, wide=self._WIDE)
         self.ids, self.scores, self.workspace = out_ids, out_scores, workspace
-        self._keep = (codes, S)
-        st = _stream() if stream is None else stream
         c = ctypes
-        self._fn = lib().pq_score_topk
-        self._args = (c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_longlong(N), c.c_int(B), c.c_int(m),
-                      c.c_int(b), c.c_int(K), c.c_void_p(out_ids.data_ptr()), c.c_void_p(out_scores.data_ptr()),
-                      c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), c.c_void_p(st))
-
-    def __call__(self) -> Tuple[torch.Tensor, torch.Tensor]:
-        rc = self._fn(*self._args)
-        if rc != PQ_OK:
-            raise PQError(rc, "pq_score_topk")
-        return self.ids, self.scores
+        self._prepare(self._ENTRY, (codes, S), (out_ids, out_scores), stream, lambda st: (
+            c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_longlong(N), c.c_int(B), c.c_int(m),
+            c.c_int(b), c.c_int(K), c.c_void_p(out_ids.data_ptr()), c.c_void_p(out_scores.data_ptr()),
+            c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), st))
 
 
 class PreparedScoreTopKU16(PreparedScoreTopK):
-    """pq_score_topk_u16 with its arguments marshalled once."""
-
-    def __init__(self, codes: torch.Tensor, S: torch.Tensor, K: int, workspace: Optional[torch.Tensor] = None,
-                 out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
-                 stream: Optional[int] = None):
-        N, B, m, b, workspace, out_ids, out_scores = _topk_args(codes, S, K, workspace, out_ids, out_scores, wide=True)
-        self.ids, self.scores, self.workspace = out_ids, out_scores, workspace
-        self._keep = (codes, S)
-        st = _stream() if stream is None else stream
-        c = ctypes
-        self._fn = lib().pq_score_topk_u16
-        self._args = (c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_longlong(N), c.c_int(B), c.c_int(m),
-                      c.c_int(b), c.c_int(K), c.c_void_p(out_ids.data_ptr()), c.c_void_p(out_scores.data_ptr()),
-                      c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), c.c_void_p(st))
+    """pq_score_topk_u16, marshalled once (same signature, uint16 codes)."""
+    _ENTRY, _WIDE = "pq_score_topk_u16", True
 
 
-class PreparedScoreTopKSubset:
-    """pq_score_topk_subset with its arguments marshalled once (workspace and outputs allocated here if not given)."""
+class PreparedScoreTopKSubset(_Prepared):
+    """pq_score_topk_subset, marshalled once (workspace and outputs allocated here if not given); returns (ids, scores)."""
 
     def __init__(self, codes: torch.Tensor, S: torch.Tensor, subset: torch.Tensor, K: int,
                  workspace: Optional[torch.Tensor] = None, stream: Optional[int] = None):
-        _dev(codes, torch.uint8, "codes")
-        _dev(S, torch.float32, "S")
-        _dev(subset, torch.int32, "subset")
-        N, m = codes.shape
-        B, m2, b = S.shape
-        if m2 != m or subset.dim() != 1:
-            raise PQError(PQ_ERR_SHAPE, "pq_score_topk_subset")
-        n = subset.numel()
-        if workspace is None:
-            workspace = torch.empty(max(pq_score_topk_subset_workspace_bytes(n, B, m, b, K), 16), dtype=torch.uint8,
-                                    device=codes.device)
-        self.ids = torch.empty((B, K), dtype=torch.int32, device=codes.device)
-        self.scores = torch.empty((B, K), dtype=torch.float32, device=codes.device)
+        n, N, B, m, b, workspace, self.ids, self.scores = _subset_args(codes, S, subset, K, workspace, None, None)
         self.workspace = workspace
-        self._keep = (codes, S, subset)
-        st = _stream() if stream is None else stream
         c = ctypes
-        self._fn = lib().pq_score_topk_subset
-        self._args = (c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_void_p(subset.data_ptr()),
-                      c.c_longlong(n), c.c_longlong(N), c.c_int(B), c.c_int(m), c.c_int(b), c.c_int(K),
-                      c.c_void_p(self.ids.data_ptr()), c.c_void_p(self.scores.data_ptr()),
-                      c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), c.c_void_p(st))
-
-    def __call__(self) -> Tuple[torch.Tensor, torch.Tensor]:
-        rc = self._fn(*self._args)
-        if rc != PQ_OK:
-            raise PQError(rc, "pq_score_topk_subset")
-        return self.ids, self.scores
-
+        self._prepare("pq_score_topk_subset", (codes, S, subset), (self.ids, self.scores), stream, lambda st: (
+            c.c_void_p(codes.data_ptr()), c.c_void_p(S.data_ptr()), c.c_void_p(subset.data_ptr()),
+            c.c_longlong(n), c.c_longlong(N), c.c_int(B), c.c_int(m), c.c_int(b), c.c_int(K),
+            c.c_void_p(self.ids.data_ptr()), c.c_void_p(self.scores.data_ptr()),
+            c.c_void_p(workspace.data_ptr()), c.c_size_t(workspace.numel()), st))
