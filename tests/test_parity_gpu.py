@@ -390,6 +390,15 @@ def test_short_scan_and_small_fold_against_the_general_kernels(pq, oracle):
             assert np.array_equal(ids, ids2) and np.array_equal(sc.view(np.uint32), sc2.view(np.uint32)), (tag, mask)
 
 
+@pytest.mark.parametrize("B", [2, 5, 64, 257, 1024])
+def test_short_scans_side_by_side(pq, oracle, B):
+    # batches of short scans in one launch (grid.y = B): the grid is spread over the CUs by B, so the number of
+    # workgroups per query (256 / B, at least one) and of code vectors per thread change with it; m = 8, 4 and 64
+    for N, m, K in ((3_001, 8, 10), (40_001, 8, 31), (9_001, 4, 1), (2_003, 64, 5)):
+        G = W.codes_uniform(N, m, 256, seed=B + m)
+        assert_same_topk(pq, oracle, G, tables(N + B, B, m, 256), K, "short side by side")
+
+
 def test_small_fold_many_lists(pq, oracle):
     # the small-K fold with both of its instances: up to 3072 and up to 6144 keys per query (256 lists of K = 10, 24; with
     # K = 28, 31 the 256 lists go to the general fold: a third instance of 16 keys per thread was slower than it),
