@@ -599,6 +599,14 @@ void launch_subitem(const float* queries, const float* centroids, float* S, int 
         }
     }
     dim3 grid((m * b + kSubThreads - 1) / kSubThreads, (B + kSubQueryTile - 1) / kSubQueryTile);
+    if constexpr (S_ELEMS != 0 && S_ELEMS % 4 == 0 && S_ELEMS <= 128) {
+        // whole waves of 16-byte aligned rows: the wave reads its block of sub-item embeddings piece after piece
+        if (((long long)m * b) % kSubThreads == 0 && ((uintptr_t)centroids & 15) == 0) {
+            hipLaunchKernelGGL((subitem_scores_kernel<S_ELEMS, false, true>), grid, dim3(kSubThreads), 0, st, queries, centroids, S,
+                               B, d, m, b, nullptr);
+            return;
+        }
+    }
     hipLaunchKernelGGL(subitem_scores_kernel<S_ELEMS>, grid, dim3(kSubThreads), 0, st, queries, centroids, S, B, d, m, b);
 }
 
@@ -751,8 +759,12 @@ int pq_measure_step_stamps(const float* queries, const float* centroids, const u
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t section = (size_t)PQ_STAMP_RECORDS * PQ_STAMP_SLOTS;
     if (B == 1 && d / m == 64 && (m * b + kSubThreads - 1) / kSubThreads <= PQ_STAMP_RECORDS) {
-        hipLaunchKernelGGL((subitem_scores_kernel<64, true>), dim3((m * b + kSubThreads - 1) / kSubThreads, 1), dim3(kSubThreads), 0,
-                           st, queries, centroids, S, B, d, m, b, stamps);
+        if (((long long)m * b) % kSubThreads == 0 && ((uintptr_t)centroids & 15) == 0)
+            hipLaunchKernelGGL((subitem_scores_kernel<64, true, true>), dim3(m * b / kSubThreads, 1), dim3(kSubThreads), 0,
+                               st, queries, centroids, S, B, d, m, b, stamps);
+        else
+            hipLaunchKernelGGL((subitem_scores_kernel<64, true>), dim3((m * b + kSubThreads - 1) / kSubThreads, 1), dim3(kSubThreads), 0,
+                               st, queries, centroids, S, B, d, m, b, stamps);
         rc = record_hip(hipGetLastError());
     } else {
         rc = pq_subitem_scores(queries, centroids, S, B, d, m, b, stream);   // (no measurement instance: section 0 stays empty)

@@ -11,7 +11,12 @@ constexpr int kSubThreads = 64;
 constexpr int kSubQueryTile = 16;
 
 // STAMP: measurement instance that also records wall-clock stamps (entry and end) per workgroup in `stamps`.
-template <int S_ELEMS, bool STAMP = false>   // S_ELEMS: d/m when it is one of the unrolled sizes, else 0 (runtime loop)
+// COAL (the host: S_ELEMS a multiple of 4, 64 | m * b, centroids 16-byte aligned): the wave's 64 sub-item embeddings are
+// one contiguous block of memory, which the lanes read piece after piece (a load instruction covers 1 KB of whole
+// cache lines) and hand to their owners through LDS (rows padded by 16 bytes: conflict-free both ways).  Read row by
+// row instead, every load instruction touches 64 lines for 16 bytes each, and the sixteen of them keep the L1's tag
+// lookup busy for a good part of this kernel's microsecond.
+template <int S_ELEMS, bool STAMP = false, bool COAL = false>   // S_ELEMS: d/m when it is one of the unrolled sizes, else 0 (runtime loop)
 __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float* __restrict__ queries,
                                                                      const float* __restrict__ centroids,
                                                                      float* __restrict__ S, int B, int d, int m, int b,
@@ -28,7 +33,26 @@ __global__ __launch_bounds__(kSubThreads) void subitem_scores_kernel(const float
     if (q1 > B) q1 = B;
     if (S_ELEMS) {
         float w[S_ELEMS ? S_ELEMS : 1];
-        if ((S_ELEMS % 4) == 0 && (((uintptr_t)psi) & 15) == 0) {
+        if constexpr (COAL) {
+            constexpr int PPR = S_ELEMS / 4;                       // 16-byte pieces per row
+            constexpr int kRow = S_ELEMS + 4;                      // floats from one row to the next in LDS
+            __shared__ __align__(16) float rows[kSubThreads * kRow];
+            const float4* blk4 = reinterpret_cast<const float4*>(centroids + (size_t)blockIdx.x * kSubThreads * S_ELEMS);
+            float4 v[PPR];
+#pragma unroll
+            for (int i = 0; i < PPR; ++i) v[i] = blk4[threadIdx.x + i * kSubThreads];
+#pragma unroll
+            for (int i = 0; i < PPR; ++i) {
+                const int piece = threadIdx.x + i * kSubThreads;
+                *reinterpret_cast<float4*>(&rows[(piece / PPR) * kRow + 4 * (piece % PPR)]) = v[i];
+            }
+            __syncthreads();                                       // (a workgroup is one wave)
+#pragma unroll
+            for (int t = 0; t < PPR; ++t) {
+                const float4 x = *reinterpret_cast<const float4*>(&rows[threadIdx.x * kRow + 4 * t]);
+                w[4 * t] = x.x; w[4 * t + 1] = x.y; w[4 * t + 2] = x.z; w[4 * t + 3] = x.w;
+            }
+        } else if ((S_ELEMS % 4) == 0 && (((uintptr_t)psi) & 15) == 0) {
             const float4* p4 = reinterpret_cast<const float4*>(psi);
 #pragma unroll
             for (int t = 0; t < S_ELEMS / 4; ++t) {
