@@ -21,8 +21,8 @@ extern "C" {
  * Enqueues the catalogue scan kernel of pq_score_topk() (the kernel that streams `codes`) once
  * untimed and then `iters` times back to back between two HIP events on `stream`, enqueues the fold so the outputs
  * are those of pq_score_topk(), waits for the stream, and stores elapsed / iters in milliseconds in *scan_ms (host
- * pointer): the scan kernel's mean duration including its launch gap.  The one entry point that synchronises and
- * that creates / destroys HIP events.  Same errors as pq_score_topk(); PQ_ERR_SHAPE if iters < 1.
+ * pointer): the scan kernel's mean duration including its launch gap.  Like every entry point of this header it synchronises and
+ * creates / destroys HIP events.  Same errors as pq_score_topk(); PQ_ERR_SHAPE if iters < 1.
  */
 int pq_score_topk_profile(const uint8_t* codes, const float* S, long long N, int B, int m, int b, int K,
                           int* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
