@@ -490,15 +490,20 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
 
 // Lists one fold workgroup takes at a level with `nlists` lists per query.  All of them when their keys fit the usual
 // fold's registers (kThreads * kFoldRegs keys), or the wide fold's (kBigThreads * kFoldWideRegs keys, `wide` set: one
-// launch of one larger workgroup instead of two levels).  More keys than that are split into groups of the usual size:
-// several small folds side by side and one more level beat one workgroup that reads everything (256 lists of
-// K = 100: 14 us in two levels, 16-24 us in one workgroup of 1024 threads holding 26 keys each).
+// launch of one larger workgroup instead of two levels).  More keys than that are split into groups: several small
+// folds side by side and one more level beat one workgroup that reads everything (256 lists of K = 100: 12 us in two
+// levels, 16-24 us in one workgroup of 1024 threads holding 26 keys each).  A group has about sqrt(nlists) lists, so
+// that both levels are small (256 lists of K = 100: 16 folds of 16 lists, then one of 16, instead of 5 folds of 61
+// lists and one of 5: 14.4 -> 12.2 us), and never more keys than the usual fold's registers hold.
 int fold_lists_per_group(int nlists, int K, bool* wide) {
     const long long nkeys = (long long)nlists * K;
     *wide = nkeys > (long long)kThreads * kFoldRegs && nkeys <= (long long)kBigThreads * kFoldWideRegs;
     if (nkeys <= (long long)kBigThreads * kFoldWideRegs) return nlists;
     const int fit = kThreads * kFoldRegs / K;
-    return fit < 2 ? 2 : fit;
+    int per = 2;
+    while (per * per < nlists) ++per;
+    if (per > fit) per = fit;
+    return per < 2 ? 2 : per;
 }
 
 // Keys of the second key area of the workspace: what the first fold level writes when the lists of a query do not fit
