@@ -757,7 +757,7 @@ int pq_measure_step_stamps(const float* queries, const float* centroids, const u
     static_assert(PQ_STAMP_SLOTS == kStampSlots, "header and kernels agree on the record size");
     const ScanPlan p = make_plan(N, B, m, K);
     if (!(p.tiled || m == 8)) return PQ_ERR_UNSUPPORTED;       // (scan kernels with a measurement instance)
-    const int waves = p.big ? kMaxWaves : kWaves;
+    const int waves = (!p.tiled && p.big) ? kMaxWaves : kWaves;   // (the batched kernel: always kWaves)
     const long long scan_groups = p.tiled ? (long long)p.nblk * ((B + kQ - 1) / kQ) : (long long)p.nblk * B;
     if (scan_groups * waves > PQ_STAMP_RECORDS || (long long)B * kWaves > PQ_STAMP_RECORDS) return PQ_ERR_UNSUPPORTED;
     if (scan_grid != nullptr) { scan_grid[0] = (int)scan_groups; scan_grid[1] = waves; }
