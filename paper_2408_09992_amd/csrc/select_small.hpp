@@ -22,7 +22,7 @@ struct SmallSelectLds {
     uint64_t cand[kSmallCand];
     uint64_t wave_best[NT / kWave];
     int ncand;
-    int pad;
+    uint32_t floor_bits;   // order-preserving image of the highest floor a wave has found so far (0: none yet)
 };
 
 // Before the workgroup barrier that precedes select_small_k(): an empty candidate array and counter.
@@ -30,7 +30,7 @@ template <int NT>
 __device__ __forceinline__ void small_select_clear(SmallSelectLds<NT>& L, int tid) {
     static_assert(kSmallCand % 2 == 0, "cleared two keys at a time");
     for (int i = tid; i < kSmallCand / 2; i += NT) reinterpret_cast<ulonglong2*>(L.cand)[i] = make_ulonglong2(0ull, 0ull);
-    if (tid == 0) L.ncand = 0;
+    if (tid == 0) { L.ncand = 0; L.floor_bits = 0u; }
 }
 
 // max over the wave of a 64-bit key, in every lane (DPP steps inside quads and rows, readlane across the four rows)
@@ -113,7 +113,17 @@ __device__ __forceinline__ void select_small_k(const float (&sc)[R], IdOf&& id_o
     float best = -__builtin_inff();
 #pragma unroll
     for (int i = 0; i < R; ++i) best = fmaxf(best, sc[i]);    // (an empty slot's NaN never wins)
-    const float f = wave_floor_for_k<kSmallFloorSteps>(best, K);
+    // A floor that some wave has found holds for the whole workgroup (that wave alone has K items at or above it), so a
+    // wave that gets here later takes it and saves the search.  (In the short scan the second wave of every SIMD
+    // finishes its lookups most of a microsecond after the first: its selection is what the workgroup waits for.)
+    const uint32_t seen = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_peek(&L.floor_bits));
+    float f;
+    if (seen != 0u) {
+        f = float_of_orderable(seen);
+    } else {
+        f = wave_floor_for_k<kSmallFloorSteps>(best, K);
+        if (lane == 0 && f > -__builtin_inff()) atomicMax(&L.floor_bits, orderable_bits(f));
+    }
     bool mine[R];                                             // this lane's slot i is a candidate
     bool any_mine = false;
     uint64_t any = 0ull;
