@@ -320,6 +320,33 @@ def test_score_topk_largest_catalogue(pq, oracle):
     assert ids[0][0] == N - 1
 
 
+def test_billion_items_of_64_splits(pq, oracle):
+    # the far end of the catalogue-size sweep (Section 5: up to 10^9 items, m = 64): 64 GB of codes drawn on the device,
+    # byte offsets far beyond 2^32.  No oracle run over that; instead four planted rows (the best sub-id of every
+    # split, and with the first one, two, three splits on their second-best) at the last item, just past a 2^32-byte
+    # boundary, in the middle and near the start must come back first, in that order, with the oracle's scores
+    N, m, K = 1_000_000_000, 64, 10
+    Gd = W.codes_uniform_device(N, m, 256, seed=9)
+    S = tables(64, 1, m, 256)
+    best = S[0].argmax(axis=1).astype(np.uint8)
+    second = np.argsort(S[0], axis=1)[:, -2].astype(np.uint8)
+    places = [N - 1, (1 << 26) + 5, N // 2 + 1, 3]
+    rows = np.stack([best] * 4)
+    for j in range(1, 4):
+        rows[j, :j] = second[:j]
+    for i, row in zip(places, rows):
+        Gd[i] = torch.from_numpy(row).cuda()
+    ids, sc = pq.pq_score_topk(Gd, dev(S), K)
+    torch.cuda.synchronize()
+    want = oracle.item_scores(rows, S[0])
+    assert want[0] > want[1] > want[2] > want[3]
+    assert ids.cpu().numpy()[0, :4].tolist() == places
+    assert np.array_equal(sc.cpu().numpy()[0, :4].view(np.uint32), want.view(np.uint32))
+    assert float(sc[0, 4]) < 0.5 * float(want[3])           # (random rows score far below)
+    del Gd
+    torch.cuda.empty_cache()
+
+
 def test_all_items_equal(pq, oracle):
     for N in (500, 100_000):
         G = np.full((N, 8), 17, dtype=np.uint8)
