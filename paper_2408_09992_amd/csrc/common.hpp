@@ -1,6 +1,6 @@
 // Constants, cross-lane helpers (DPP), wave-level reductions and the bitonic sort shared by every kernel.
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_subset.hpp, scan_batched.hpp,
 // fold.hpp, comparison.hpp.
 #pragma once
 

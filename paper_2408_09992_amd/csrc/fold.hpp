@@ -1,6 +1,6 @@
 // The second launch of every TopK call: the workgroups' lists -> the final sorted K per query (fold_topk_kernel).
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_subset.hpp, scan_batched.hpp,
 // fold.hpp, comparison.hpp.
 #pragma once
 

@@ -16,6 +16,7 @@ namespace pqk {
 #include "select_small.hpp"
 #include "scan_single.hpp"
 #include "scan_short.hpp"
+#include "scan_subset.hpp"
 #include "scan_batched.hpp"
 #include "fold.hpp"
 #ifndef PQ_INSTANCE_TU
@@ -59,6 +60,10 @@ namespace pqk {
     PQ_SHORT_U(X, 16, 1) PQ_SHORT_U(X, 16, 2) PQ_SHORT_U(X, 16, 3) PQ_SHORT_U(X, 16, 4) PQ_SHORT_U(X, 16, 5) \
     PQ_SHORT_U(X, 16, 6) PQ_SHORT_U(X, 16, 7) PQ_SHORT_U(X, 16, 8) \
     PQ_SHORT_U(X, 32, 1) PQ_SHORT_U(X, 32, 2) PQ_SHORT_U(X, 32, 3) PQ_SHORT_U(X, 32, 4) PQ_SHORT_U(X, 64, 1) PQ_SHORT_U(X, 64, 2)
+// scan_subset_kernel<M, U, NT>: rows of 4, 8, 16 bytes, every number of vectors per thread
+#define PQ_SUBSET_M(X, M) X(M, 1, kThreads) X(M, 2, kThreads) X(M, 3, kThreads) X(M, 4, kThreads) X(M, 5, kThreads) \
+    X(M, 6, kThreads) X(M, 7, kThreads) X(M, 8, kThreads)
+#define PQ_SUBSET_INSTANCES(X) PQ_SUBSET_M(X, 4) PQ_SUBSET_M(X, 8) PQ_SUBSET_M(X, 16)
 // the batched kernel
 #define PQ_TILED_INSTANCES(X) X(8, false) X(16, false) X(8, true) X(16, true)
 
@@ -68,6 +73,8 @@ namespace pqk {
 #define PQ_SCAN_EXTERN6(M, C, NT, CW, GL, ST) extern PQ_SCAN_DEFINE6(M, C, NT, CW, GL, ST)
 #define PQ_SHORT_DEFINE(M, U, NT, ST) template __global__ void scan_short_kernel<M, U, NT, ST>(ScanArgs);
 #define PQ_SHORT_EXTERN(M, U, NT, ST) extern PQ_SHORT_DEFINE(M, U, NT, ST)
+#define PQ_SUBSET_DEFINE(M, U, NT) template __global__ void scan_subset_kernel<M, U, NT>(ScanArgs);
+#define PQ_SUBSET_EXTERN(M, U, NT) extern PQ_SUBSET_DEFINE(M, U, NT)
 #define PQ_TILED_DEFINE(M, ST) template __global__ void scan_topk_tiled_kernel<M, ST>(ScanArgs, int);
 #define PQ_TILED_EXTERN(M, ST) extern PQ_TILED_DEFINE(M, ST)
 
@@ -80,6 +87,7 @@ PQ_SCAN_INSTANCES_U16(PQ_SCAN_EXTERN)
 PQ_SCAN_INSTANCES_STAMPED(PQ_SCAN_EXTERN6)
 PQ_SHORT_INSTANCES_A(PQ_SHORT_EXTERN)
 PQ_SHORT_INSTANCES_B(PQ_SHORT_EXTERN)
+PQ_SUBSET_INSTANCES(PQ_SUBSET_EXTERN)
 PQ_TILED_INSTANCES(PQ_TILED_EXTERN)
 #endif
 

@@ -93,6 +93,8 @@ struct ScanPlan {
     bool glut;       // two-byte sub-ids: the m x b table does not fit LDS and is read from device memory
     bool short_scan; // scan_short_kernel: every workgroup's share fits its registers, K small
     int short_units; // ... units (code vectors, or items for m = 32, 64) a thread holds
+    bool short_subset; // scan_subset_kernel: a candidate list whose share per thread fits its registers, K small
+    int subset_vecs;   // ... code vectors' worth of gathered rows a thread holds
 };
 
 bool is_vec_m(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32 || m == 64; }
@@ -273,6 +275,29 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
             }
         }
     }
+    // Candidate lists (the `generic` plans) of rows of 4, 8 or 16 bytes with a small K, short enough for a thread to
+    // hold its share: every row of a thread is requested at once and the selection comes straight from registers.
+    // Same thin grid as the short scan.
+    p.short_subset = false;
+    p.subset_vecs = 0;
+    if (generic && cw == 1 && (m == 4 || m == 8 || m == 16) && K <= kSmallKMax &&
+        !(g_force_general.load(std::memory_order_relaxed) & 1)) {
+        long long nb = kAssumedCUs / B;
+        if (nb < 1) nb = 1;
+        const long long thin = (N + kThreads - 1) / kThreads;              // workgroups if every thread held one candidate
+        if (nb > thin) nb = thin;
+        const long long per_thread = (N + kThreads * nb - 1) / (kThreads * nb);
+        const long long vecs = (per_thread * m + 15) / 16;
+        if (vecs <= kSubsetMaxVecs) {
+            p.short_subset = true;
+            p.subset_vecs = (int)vecs;
+            p.nblk = (int)nb;
+            p.copies = 1;
+            p.big = false;
+            p.scan_dyn_lds = 0;
+            p.scan_lds = (size_t)m * kLutStride * sizeof(float) + sizeof(SmallSelectLds<kThreads>);
+        }
+    }
     return p;
 }
 
@@ -414,6 +439,25 @@ hipError_t launch_short(const ScanPlan& p, const ScanArgs& a, int B, int m, hipS
     }
 }
 
+template <int M>
+hipError_t launch_subset_m(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(p.nblk, B), dim3(kThreads), 0, st, a);
+        return hipGetLastError();
+    };
+    switch (p.subset_vecs) {
+        case 1: return go(scan_subset_kernel<M, 1, kThreads>);
+        case 2: return go(scan_subset_kernel<M, 2, kThreads>);
+        case 3: return go(scan_subset_kernel<M, 3, kThreads>);
+        case 4: return go(scan_subset_kernel<M, 4, kThreads>);
+        case 5: return go(scan_subset_kernel<M, 5, kThreads>);
+        case 6: return go(scan_subset_kernel<M, 6, kThreads>);
+        case 7: return go(scan_subset_kernel<M, 7, kThreads>);
+        case 8: return go(scan_subset_kernel<M, 8, kThreads>);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 // Enqueue the catalogue scan: every workgroup's K best keys land in the workspace.
 // `subset` / `n_items`: candidate list (then N is its length and the plan is a generic one) or nullptr / N
 // `cw`: bytes per sub-id (2: `codes` holds uint16 values)
@@ -435,6 +479,10 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     if (p.short_scan) {
         if (stamps != nullptr && m != 8) return PQ_ERR_UNSUPPORTED;
         return record_hip(launch_short(p, a, B, m, st));
+    }
+    if (p.short_subset) {
+        if (subset == nullptr || stamps != nullptr) return PQ_ERR_UNSUPPORTED;   // (the plan is only made for candidate lists)
+        return record_hip(m == 4 ? launch_subset_m<4>(p, a, B, st) : m == 8 ? launch_subset_m<8>(p, a, B, st) : launch_subset_m<16>(p, a, B, st));
     }
     if (p.tiled) {
         const dim3 grid(p.nblk, (B + kQ - 1) / kQ);

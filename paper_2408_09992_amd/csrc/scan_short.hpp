@@ -1,7 +1,7 @@
 // Eq. 5 + TopK for catalogues short enough that a workgroup's share fits its registers (scan_short_kernel): the scan of
 // every single-query call over up to a few million items with K < 32, the headline workload among them.
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_subset.hpp, scan_batched.hpp,
 // fold.hpp, comparison.hpp.
 #pragma once
 

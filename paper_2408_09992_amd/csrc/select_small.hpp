@@ -1,6 +1,6 @@
 // TopK for small K straight from registers: the selection shared by the short catalogue scan and the small fold.
 // Part of kernels.hpp, which includes these parts inside namespace pqk in this order:
-// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_batched.hpp,
+// common.hpp, subitem_scores.hpp, topk_parts.hpp, select_small.hpp, scan_single.hpp, scan_short.hpp, scan_subset.hpp, scan_batched.hpp,
 // fold.hpp, comparison.hpp.
 //
 // These kernels run for a few microseconds with two to four waves per SIMD, so a wave's time is its instruction count

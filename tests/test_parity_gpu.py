@@ -729,6 +729,38 @@ def test_subset_of_the_large_catalogue(pq, oracle, large_codes):
             assert np.array_equal(ids, full_ids)
 
 
+@pytest.mark.parametrize("m", [4, 8, 16])
+def test_subset_lists_held_in_registers(pq, oracle, m):
+    # candidate lists with K < 32 whose share per thread fits its registers take a kernel of their own (every row of a
+    # thread requested at once), with an instance per number of code vectors' worth of rows a thread holds: list
+    # lengths that land on each of them (ragged last slots), batches (fewer workgroups per query), ascending lists,
+    # every item equal (ties by item id; more candidates than the selection's array holds), ids clamped never
+    N = 2_400_001
+    G = W.codes_uniform(N, m, 256, seed=m)
+    ipv = 16 // m
+    for vecs in range(1, 9):
+        n = (vecs - 1) * ipv * 256 * 512 + 3 * 256 * 512 // 4 + 77
+        if n > N:
+            break
+        V = W.candidate_list(N, n, seed=vecs, ascending=(vecs % 3 == 0))
+        for B, K in ((1, 10), (1, 31), (3, 1)):
+            ids, sc = assert_same_subset_topk(pq, oracle, G, tables(vecs + B, B, m, 256), V, K, f"subset registers vecs={vecs}")
+            prev = pq.pq_measure_force_general(1)                  # the general kernel gives the same bits
+            try:
+                ids2, sc2 = pq.pq_score_topk_subset(dev(G), dev(tables(vecs + B, B, m, 256)), dev(V), K)
+                torch.cuda.synchronize()
+            finally:
+                pq.pq_measure_force_general(prev)
+            assert np.array_equal(ids, ids2.cpu().numpy()) and np.array_equal(sc.view(np.uint32), sc2.cpu().numpy().view(np.uint32))
+    Ge = np.full((300_000, m), 9, dtype=np.uint8)
+    V = W.candidate_list(300_000, 200_001, seed=5)
+    ids, _ = assert_same_subset_topk(pq, oracle, Ge, tables(5, 2, m, 256), V, 31, "subset registers all equal")
+    assert ids[0].tolist() == np.sort(V)[:31].tolist()
+    Gs = W.codes_uniform(5000, m, 16, seed=3)                  # a short alphabet and a list of a few candidates
+    for n in (1, 2, 31, 513):
+        assert_same_subset_topk(pq, oracle, Gs, tables(n, 2, m, 16), W.candidate_list(5000, n, seed=n), min(n, 10), "subset registers tiny")
+
+
 def test_subset_ties_go_to_the_lower_item_id(pq, oracle):
     # every item scores the same: the K lowest ITEM ids of the list win, wherever they sit in it
     N, m, K = 50_000, 8, 20
