@@ -60,6 +60,14 @@ namespace pqk {
     PQ_SHORT_U(X, 16, 1) PQ_SHORT_U(X, 16, 2) PQ_SHORT_U(X, 16, 3) PQ_SHORT_U(X, 16, 4) PQ_SHORT_U(X, 16, 5) \
     PQ_SHORT_U(X, 16, 6) PQ_SHORT_U(X, 16, 7) PQ_SHORT_U(X, 16, 8) \
     PQ_SHORT_U(X, 32, 1) PQ_SHORT_U(X, 32, 2) PQ_SHORT_U(X, 32, 3) PQ_SHORT_U(X, 32, 4) PQ_SHORT_U(X, 64, 1) PQ_SHORT_U(X, 64, 2)
+// scan_short_kernel<M, U, NT, false, 2>: two-byte sub-ids, m = 4, 8 (up to 12 code vectors per thread), 16 (up to 6 items)
+#define PQ_SHORT16_U(X, M, U) X(M, U, kThreads, false, 2)
+#define PQ_SHORT16_INSTANCES(X) \
+    PQ_SHORT16_U(X, 4, 1) PQ_SHORT16_U(X, 4, 2) PQ_SHORT16_U(X, 4, 3) PQ_SHORT16_U(X, 4, 4) PQ_SHORT16_U(X, 4, 5) PQ_SHORT16_U(X, 4, 6) \
+    PQ_SHORT16_U(X, 4, 7) PQ_SHORT16_U(X, 4, 8) PQ_SHORT16_U(X, 4, 9) PQ_SHORT16_U(X, 4, 10) PQ_SHORT16_U(X, 4, 11) PQ_SHORT16_U(X, 4, 12) \
+    PQ_SHORT16_U(X, 8, 1) PQ_SHORT16_U(X, 8, 2) PQ_SHORT16_U(X, 8, 3) PQ_SHORT16_U(X, 8, 4) PQ_SHORT16_U(X, 8, 5) PQ_SHORT16_U(X, 8, 6) \
+    PQ_SHORT16_U(X, 8, 7) PQ_SHORT16_U(X, 8, 8) PQ_SHORT16_U(X, 8, 9) PQ_SHORT16_U(X, 8, 10) PQ_SHORT16_U(X, 8, 11) PQ_SHORT16_U(X, 8, 12) \
+    PQ_SHORT16_U(X, 16, 1) PQ_SHORT16_U(X, 16, 2) PQ_SHORT16_U(X, 16, 3) PQ_SHORT16_U(X, 16, 4) PQ_SHORT16_U(X, 16, 5) PQ_SHORT16_U(X, 16, 6)
 // scan_subset_kernel<M, U, NT>: rows of 4, 8, 16 bytes, every number of vectors per thread
 #define PQ_SUBSET_M(X, M) X(M, 1, kThreads) X(M, 2, kThreads) X(M, 3, kThreads) X(M, 4, kThreads) X(M, 5, kThreads) \
     X(M, 6, kThreads) X(M, 7, kThreads) X(M, 8, kThreads)
@@ -73,6 +81,8 @@ namespace pqk {
 #define PQ_SCAN_EXTERN6(M, C, NT, CW, GL, ST) extern PQ_SCAN_DEFINE6(M, C, NT, CW, GL, ST)
 #define PQ_SHORT_DEFINE(M, U, NT, ST) template __global__ void scan_short_kernel<M, U, NT, ST>(ScanArgs);
 #define PQ_SHORT_EXTERN(M, U, NT, ST) extern PQ_SHORT_DEFINE(M, U, NT, ST)
+#define PQ_SHORT16_DEFINE(M, U, NT, ST, CW) template __global__ void scan_short_kernel<M, U, NT, ST, CW>(ScanArgs);
+#define PQ_SHORT16_EXTERN(M, U, NT, ST, CW) extern PQ_SHORT16_DEFINE(M, U, NT, ST, CW)
 #define PQ_SUBSET_DEFINE(M, U, NT) template __global__ void scan_subset_kernel<M, U, NT>(ScanArgs);
 #define PQ_SUBSET_EXTERN(M, U, NT) extern PQ_SUBSET_DEFINE(M, U, NT)
 #define PQ_TILED_DEFINE(M, ST) template __global__ void scan_topk_tiled_kernel<M, ST>(ScanArgs, int);
@@ -88,6 +98,7 @@ PQ_SCAN_INSTANCES_STAMPED(PQ_SCAN_EXTERN6)
 PQ_SHORT_INSTANCES_A(PQ_SHORT_EXTERN)
 PQ_SHORT_INSTANCES_B(PQ_SHORT_EXTERN)
 PQ_SUBSET_INSTANCES(PQ_SUBSET_EXTERN)
+PQ_SHORT16_INSTANCES(PQ_SHORT16_EXTERN)
 PQ_TILED_INSTANCES(PQ_TILED_EXTERN)
 #endif
 

@@ -253,24 +253,32 @@ ScanPlan make_plan(long long N, int B, int m, int K, bool generic = false, int c
     // selection, so the fewer units a thread holds the better, and the small fold takes the 256 lists in its stride.
     p.short_scan = false;
     p.short_units = 0;
-    if (cw == 1 && p.vec && !generic && !p.tiled && K <= kSmallKMax) {
+    // (two-byte sub-ids: when the table fits LDS beside the selection's few KB)
+    const bool short16 = cw == 2 && !p.glut && lut_floats * sizeof(float) + sizeof(SmallSelectLds<kThreads>) <= kMaxLdsBytes;
+    if ((cw == 1 || short16) && p.vec && !generic && !p.tiled && K <= kSmallKMax) {
         long long nb = kAssumedCUs / B;
         if (nb < 1) nb = 1;
         const long long thin = (units + kThreads - 1) / kThreads;          // workgroups if every thread held one unit
         if (nb > thin) nb = thin;
         const long long per_slot = (long long)kThreads * nb;               // units one slot of all threads covers
         const long long slots = (units + per_slot - 1) / per_slot;
-        if (slots <= short_max_units(m)) {
-            // (the general kernel takes the same grid when the measurement hook keeps a call off the short one)
-            p.nblk = (int)nb;
-            p.copies = 1;
-            p.big = false;
-            p.scan_dyn_lds = scan_lds_bytes(0, p.cap, p.candmax, K, kWaves);
-            p.scan_lds = p.scan_dyn_lds + lut_floats * sizeof(float);
-            if (!(g_force_general.load(std::memory_order_relaxed) & 1)) {
+        if (slots <= (cw == 1 ? short_max_units(m) : short16_max_units(m))) {
+            // (one-byte sub-ids: the general kernel takes the same grid when the measurement hook keeps a call off the
+            // short one; two-byte sub-ids: its plan stays as it is)
+            const bool forced = (g_force_general.load(std::memory_order_relaxed) & 1) != 0;
+            if (cw == 1 || !forced) {
+                p.nblk = (int)nb;
+                p.copies = 1;
+                p.big = false;
+            }
+            if (cw == 1) {
+                p.scan_dyn_lds = scan_lds_bytes(0, p.cap, p.candmax, K, kWaves);
+                p.scan_lds = p.scan_dyn_lds + lut_floats * sizeof(float);
+            }
+            if (!forced) {
                 p.short_scan = true;
                 p.short_units = (int)slots;
-                p.scan_dyn_lds = 0;
+                p.scan_dyn_lds = cw == 1 ? 0 : lut_floats * sizeof(float);
                 p.scan_lds = lut_floats * sizeof(float) + sizeof(SmallSelectLds<kThreads>);
             }
         }
@@ -439,6 +447,36 @@ hipError_t launch_short(const ScanPlan& p, const ScanArgs& a, int B, int m, hipS
     }
 }
 
+template <int M, int U>
+hipError_t launch_short16_units(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    if constexpr (U <= short16_max_units(M)) {
+        hipError_t e = allow_lds(scan_short_kernel<M, U, kThreads, false, 2>, p.scan_dyn_lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((scan_short_kernel<M, U, kThreads, false, 2>), dim3(p.nblk, B), dim3(kThreads), p.scan_dyn_lds, st, a);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;                         // (the plan never asks for it)
+    }
+}
+template <int M>
+hipError_t launch_short16_m(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
+    switch (p.short_units) {
+        case 1: return launch_short16_units<M, 1>(p, a, B, st);
+        case 2: return launch_short16_units<M, 2>(p, a, B, st);
+        case 3: return launch_short16_units<M, 3>(p, a, B, st);
+        case 4: return launch_short16_units<M, 4>(p, a, B, st);
+        case 5: return launch_short16_units<M, 5>(p, a, B, st);
+        case 6: return launch_short16_units<M, 6>(p, a, B, st);
+        case 7: return launch_short16_units<M, 7>(p, a, B, st);
+        case 8: return launch_short16_units<M, 8>(p, a, B, st);
+        case 9: return launch_short16_units<M, 9>(p, a, B, st);
+        case 10: return launch_short16_units<M, 10>(p, a, B, st);
+        case 11: return launch_short16_units<M, 11>(p, a, B, st);
+        case 12: return launch_short16_units<M, 12>(p, a, B, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 template <int M>
 hipError_t launch_subset_m(const ScanPlan& p, const ScanArgs& a, int B, hipStream_t st) {
     auto go = [&](auto kernel) {
@@ -476,6 +514,10 @@ int enqueue_scan(const ScanPlan& p, const uint8_t* codes, const float* S, long l
     a.prune_at = (p.tiled && K <= 12) ? 2 * K + 8 : 0;
     a.ws_keys = static_cast<uint64_t*>(workspace);
     hipError_t e;
+    if (p.short_scan && cw == 2) {
+        if (stamps != nullptr) return PQ_ERR_UNSUPPORTED;
+        return record_hip(m == 4 ? launch_short16_m<4>(p, a, B, st) : m == 8 ? launch_short16_m<8>(p, a, B, st) : launch_short16_m<16>(p, a, B, st));
+    }
     if (p.short_scan) {
         if (stamps != nullptr && m != 8) return PQ_ERR_UNSUPPORTED;
         return record_hip(launch_short(p, a, B, m, st));

@@ -7,6 +7,8 @@
 
 // Most units (16-byte code vectors for m <= 16, items for m = 32 and 64) a thread of the short kernel holds.
 __host__ __device__ constexpr int short_max_units(int m) { return kRing * vec_per_thread(m); }
+// ... with two-byte sub-ids (rows of 8, 16, 32 bytes: m = 4, 8, 16): code vectors, or items of two vectors for m = 16
+__host__ __device__ constexpr int short16_max_units(int m) { return m == 16 ? 6 : 12; }
 
 // grid = (item blocks, B); one query per workgroup; a thread holds U units of its workgroup's share: unit u of thread t
 // of workgroup g is number (u * blocks + g) * NT + t of the catalogue's units (slot u of all workgroups together is one
@@ -15,22 +17,27 @@ __host__ __device__ constexpr int short_max_units(int m) { return kRing * vec_pe
 // differs is everything around them: all codes are requested before anything else happens, no lists, no histogram, one
 // barrier after the tables' and one in the selection.  This step is all latency (the code matrix is a few
 // microseconds of traffic), and a wave's latency is its instruction count: a kernel of its own, a few KB of code.
-//   M: bytes of an item's row (1, 2, 4, 8, 16: 16 / M items per code vector; 32, 64: M / 16 vectors per item)
-template <int M, int U, int NT, bool STAMP = false>
+//   M: splits; CW: bytes per sub-id.  An item's row takes P = M * CW bytes (1, 2, 4, 8, 16: 16 / P items per code vector;
+//   32, 64: P / 16 vectors per item).  CW = 2 (M = 4, 8, 16): the query's m x b table lies in dynamic LDS as in memory.
+template <int M, int U, int NT, bool STAMP = false, int CW = 1>
 __global__ __launch_bounds__(NT) void scan_short_kernel(ScanArgs a) {
     constexpr int NW = NT / kWave;
-    constexpr int VPU = Round<M>::kVPU, IPV = Round<M>::kIPV;  // vectors per unit, items per unit
-    constexpr bool kTail = M <= 16;                            // items after the last whole code vector exist
+    constexpr int P = M * CW;
+    constexpr int VPU = Round<P>::kVPU, IPV = Round<P>::kIPV;  // vectors per unit, items per unit
+    constexpr bool kTail = P < 16 || (CW == 1 && P == 16);     // items after the last whole code vector may exist (a slot is kept for them)
     constexpr int R = U * IPV + (kTail ? 1 : 0);
-    static_assert(U >= 1 && U <= short_max_units(M), "units per thread");
-    __shared__ __align__(16) float lut[M * kLutStride];
+    static_assert(CW == 1 || CW == 2, "one- or two-byte sub-ids");
+    static_assert(U >= 1 && U <= (CW == 1 ? short_max_units(M) : short16_max_units(M)), "units per thread");
+    __shared__ __align__(16) float lut_static[CW == 1 ? M * kLutStride : 4];
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* const lut = CW == 1 ? lut_static : reinterpret_cast<float*>(smem);
     __shared__ SmallSelectLds<NT> sel;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int q = blockIdx.y, nblk = gridDim.x, blk = blockIdx.x, K = a.K, b = a.b;
     uint64_t* const rec = STAMP ? a.stamps + (((size_t)q * nblk + blk) * NW + wave) * kStampSlots : nullptr;
     stamp<STAMP>(rec, kStampEntry, lane);
 
-    const uint32_t total_units = (uint32_t)(M <= 16 ? (a.N * M) / 16 : a.N);   // whole code vectors (M <= 16) or items; >= 1
+    const uint32_t total_units = (uint32_t)(P <= 16 ? (a.N * P) / 16 : a.N);   // whole code vectors (P <= 16) or items; >= 1
     const uint32_t last_unit = total_units - 1;
     const uint32_t first = (uint32_t)blk * NT + (uint32_t)tid, stride = (uint32_t)nblk * NT;   // unit u: first + u * stride
 
@@ -49,7 +56,20 @@ __global__ __launch_bounds__(NT) void scan_short_kernel(ScanArgs a) {
         }
     };
     const float* Sq = a.S + (size_t)q * M * b;
-    if (b == kLutStride && ((uintptr_t)Sq & 15) == 0) {
+    if constexpr (CW == 2) {
+        // the m x b table as it lies in memory, in 16-byte pieces when its size and address allow
+        const int total = M * b;
+        fetch_codes();
+        if ((total & 3) == 0 && ((uintptr_t)Sq & 15) == 0) {
+            const float4* src = reinterpret_cast<const float4*>(Sq);
+            float4* dst = reinterpret_cast<float4*>(lut);
+#pragma unroll 4
+            for (int e = tid; e < (total >> 2); e += NT) dst[e] = src[e];
+        } else {
+#pragma unroll 4
+            for (int e = tid; e < total; e += NT) lut[e] = Sq[e];
+        }
+    } else if (b == kLutStride && ((uintptr_t)Sq & 15) == 0) {
         constexpr int kPieces = M * kLutStride / 4;
         constexpr int kPer = (kPieces + NT - 1) / NT;
         const float4* src = reinterpret_cast<const float4*>(Sq);
@@ -92,7 +112,10 @@ __global__ __launch_bounds__(NT) void scan_short_kernel(ScanArgs a) {
         const bool have = u < U - 1 || first + (uint32_t)u * stride < total_units;
         float part[IPV];
         if (u < U - 1 || __ballot(have) != 0) {               // (a wave wholly past the end looks nothing up)
-            if constexpr (M > 16) part[0] = score_wide<M>(lut, w[u]);
+            if constexpr (CW == 2) {
+                if constexpr (P > 16) part[0] = score_wide16<M>(lut, b, w[u]);
+                else score_vector16<M>(lut, b, w[u], part);
+            } else if constexpr (M > 16) part[0] = score_wide<M>(lut, w[u]);
             else score_vector<M, 1>(lut, w[u], part);
         } else {
 #pragma unroll
@@ -107,10 +130,17 @@ __global__ __launch_bounds__(NT) void scan_short_kernel(ScanArgs a) {
         if (blk == 0 && wave == 0) {
             const uint32_t tail_item = total_units * IPV + lane;
             if (tail_item < (uint32_t)a.N) {
-                const uint8_t* row = a.codes + (size_t)tail_item * M;
-                tail_sc = lut[row[0]];
+                const uint8_t* row = a.codes + (size_t)tail_item * P;
+                if constexpr (CW == 2) {
+                    const uint16_t* g = reinterpret_cast<const uint16_t*>(row);
+                    tail_sc = lut[g[0]];
 #pragma unroll
-                for (int k = 1; k < M; ++k) tail_sc = tail_sc + lut[k * kLutStride + row[k]];
+                    for (int k = 1; k < M; ++k) tail_sc = tail_sc + lut[(size_t)k * b + g[k]];
+                } else {
+                    tail_sc = lut[row[0]];
+#pragma unroll
+                    for (int k = 1; k < M; ++k) tail_sc = tail_sc + lut[k * kLutStride + row[k]];
+                }
             }
         }
         sc[R - 1] = tail_sc;

@@ -583,6 +583,39 @@ def assert_same_topk_u16(pq, oracle, G, S, K, tag=""):
     return ids, sc
 
 
+@pytest.mark.parametrize("m,b", [(4, 8192), (8, 1024), (8, 4096), (16, 2048), (4, 300)])
+def test_u16_short_scan_every_number_of_units_per_thread(pq, oracle, m, b):
+    # two-byte sub-ids, K < 32, a share per thread that fits its registers: the short kernel with the table in dynamic
+    # LDS, an instance per number of units a thread holds (code vectors; items of two vectors for m = 16); catalogue
+    # sizes that land on each, odd so that the last slot is ragged (and, for rows of 8 bytes, an item follows the last
+    # whole vector); the last item planted as the winner; against the oracle and against the general kernel's bits
+    unit_items = 2 if m == 4 else 1
+    max_units = 6 if m == 16 else 12
+    S = tables(m + b, 1, m, b)
+    for units in (1, 2, 3, 5, 6, 7, 9, 12):
+        if units > max_units:
+            continue
+        N = (units - 1) * 256 * 512 * unit_items + 50_001 * unit_items
+        G = W.codes_uniform_u16(N, m, b, seed=units + m)
+        G[N - 1] = S[0].argmax(axis=1)
+        for K in (1, 10, 31):
+            ids, sc = assert_same_topk_u16(pq, oracle, G, S, K, f"u16 short units={units}")
+            assert ids[0][0] == N - 1
+        prev = pq.pq_measure_force_general(1)
+        try:
+            ids2, sc2 = pq.pq_score_topk_u16(dev(G), dev(S), 31)
+            torch.cuda.synchronize()
+        finally:
+            pq.pq_measure_force_general(prev)
+        assert np.array_equal(ids, ids2.cpu().numpy()) and np.array_equal(sc.view(np.uint32), sc2.cpu().numpy().view(np.uint32))
+    # a batch (fewer workgroups per query) and heavy ties
+    G = W.codes_uniform_u16(200_001, m, b, seed=1)
+    assert_same_topk_u16(pq, oracle, G, tables(3, 5, m, b), 10, "u16 short batch")
+    Ge = np.full((150_001, m), b - 1, dtype=np.uint16)
+    ids, _ = assert_same_topk_u16(pq, oracle, Ge, tables(4, 1, m, b), 31, "u16 short all equal")
+    assert ids[0].tolist() == list(range(31))
+
+
 @pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 12, 16, 24])
 def test_u16_small_shapes(pq, oracle, m):
     for N in (1, 2, 3, 5, 63, 64, 65, 1000, 4099, 70_001):
