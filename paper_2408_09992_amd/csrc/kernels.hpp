@@ -51,7 +51,7 @@ namespace pqk {
 #define PQ_SHORT_U(X, M, U) X(M, U, kThreads, false)
 #define PQ_SHORT_INSTANCES_A(X) \
     PQ_SHORT_U(X, 8, 1) PQ_SHORT_U(X, 8, 2) PQ_SHORT_U(X, 8, 3) PQ_SHORT_U(X, 8, 4) PQ_SHORT_U(X, 8, 5) PQ_SHORT_U(X, 8, 6) \
-    PQ_SHORT_U(X, 8, 7) PQ_SHORT_U(X, 8, 8) \
+    PQ_SHORT_U(X, 8, 7) PQ_SHORT_U(X, 8, 8) PQ_SHORT_U(X, 8, 9) PQ_SHORT_U(X, 8, 10) PQ_SHORT_U(X, 8, 11) PQ_SHORT_U(X, 8, 12) \
     X(8, 1, kThreads, true) X(8, 2, kThreads, true) X(8, 3, kThreads, true) X(8, 4, kThreads, true) X(8, 5, kThreads, true) \
     X(8, 6, kThreads, true) X(8, 7, kThreads, true) X(8, 8, kThreads, true) \
     PQ_SHORT_U(X, 1, 1) PQ_SHORT_U(X, 1, 2) PQ_SHORT_U(X, 2, 1) PQ_SHORT_U(X, 2, 2) \

@@ -432,6 +432,10 @@ hipError_t launch_short_m(const ScanPlan& p, const ScanArgs& a, int B, hipStream
         case 6: return launch_short_units<M, 6>(p, a, B, st);
         case 7: return launch_short_units<M, 7>(p, a, B, st);
         case 8: return launch_short_units<M, 8>(p, a, B, st);
+        case 9: return launch_short_units<M, 9>(p, a, B, st);
+        case 10: return launch_short_units<M, 10>(p, a, B, st);
+        case 11: return launch_short_units<M, 11>(p, a, B, st);
+        case 12: return launch_short_units<M, 12>(p, a, B, st);
         default: return hipErrorInvalidValue;
     }
 }

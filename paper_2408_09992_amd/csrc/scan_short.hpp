@@ -5,8 +5,10 @@
 // fold.hpp, comparison.hpp.
 #pragma once
 
-// Most units (16-byte code vectors for m <= 16, items for m = 32 and 64) a thread of the short kernel holds.
-__host__ __device__ constexpr int short_max_units(int m) { return kRing * vec_per_thread(m); }
+// Most units (16-byte code vectors for m <= 16, items for m = 32 and 64) a thread of the short kernel holds.  (m = 8,
+// measured: up to 12 vectors it beats the general kernel by 2 us and more, 2.5M items 14.5 -> 12.3 us, two queries side
+// by side on 1.28M items 13.4 -> 12.0 us; at 16 it no longer does.)
+__host__ __device__ constexpr int short_max_units(int m) { return m == 8 ? 12 : kRing * vec_per_thread(m); }
 // ... with two-byte sub-ids (rows of 8, 16, 32 bytes: m = 4, 8, 16): code vectors, or items of two vectors for m = 16
 __host__ __device__ constexpr int short16_max_units(int m) { return m == 16 ? 6 : 12; }
 
