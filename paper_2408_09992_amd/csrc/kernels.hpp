@@ -46,20 +46,20 @@ namespace pqk {
     X(16, 1, kThreads, 2, true) X(16, 1, kBigThreads, 2, false) X(16, 1, kThreads, 2, false)
 // measurement instances (wall-clock stamps per wave) of the two kernels the named single-query workloads run
 #define PQ_SCAN_INSTANCES_STAMPED(X) X(8, 1, kThreads, 1, false, true) X(8, kTableCopies, kBigThreads, 1, false, true)
-// scan_short_kernel<M, U, NT, STAMP> instances: every number of units per thread up to short_max_units(M), in two
+// scan_short_kernel<M, U, NT, STAMP> instances: every number of units per thread up to short_max_units(M), in three
 // translation units; measurement instances for m = 8
 #define PQ_SHORT_U(X, M, U) X(M, U, kThreads, false)
+#define PQ_SHORT_U4(X, M, U) PQ_SHORT_U(X, M, U) PQ_SHORT_U(X, M, U + 1) PQ_SHORT_U(X, M, U + 2) PQ_SHORT_U(X, M, U + 3)
 #define PQ_SHORT_INSTANCES_A(X) \
-    PQ_SHORT_U(X, 8, 1) PQ_SHORT_U(X, 8, 2) PQ_SHORT_U(X, 8, 3) PQ_SHORT_U(X, 8, 4) PQ_SHORT_U(X, 8, 5) PQ_SHORT_U(X, 8, 6) \
-    PQ_SHORT_U(X, 8, 7) PQ_SHORT_U(X, 8, 8) PQ_SHORT_U(X, 8, 9) PQ_SHORT_U(X, 8, 10) PQ_SHORT_U(X, 8, 11) PQ_SHORT_U(X, 8, 12) \
+    PQ_SHORT_U4(X, 8, 1) PQ_SHORT_U4(X, 8, 5) PQ_SHORT_U4(X, 8, 9) \
     X(8, 1, kThreads, true) X(8, 2, kThreads, true) X(8, 3, kThreads, true) X(8, 4, kThreads, true) X(8, 5, kThreads, true) \
     X(8, 6, kThreads, true) X(8, 7, kThreads, true) X(8, 8, kThreads, true) \
     PQ_SHORT_U(X, 1, 1) PQ_SHORT_U(X, 1, 2) PQ_SHORT_U(X, 2, 1) PQ_SHORT_U(X, 2, 2) \
-    PQ_SHORT_U(X, 4, 1) PQ_SHORT_U(X, 4, 2) PQ_SHORT_U(X, 4, 3) PQ_SHORT_U(X, 4, 4)
+    PQ_SHORT_U4(X, 4, 1) PQ_SHORT_U(X, 4, 5) PQ_SHORT_U(X, 4, 6)
 #define PQ_SHORT_INSTANCES_B(X) \
-    PQ_SHORT_U(X, 16, 1) PQ_SHORT_U(X, 16, 2) PQ_SHORT_U(X, 16, 3) PQ_SHORT_U(X, 16, 4) PQ_SHORT_U(X, 16, 5) \
-    PQ_SHORT_U(X, 16, 6) PQ_SHORT_U(X, 16, 7) PQ_SHORT_U(X, 16, 8) \
-    PQ_SHORT_U(X, 32, 1) PQ_SHORT_U(X, 32, 2) PQ_SHORT_U(X, 32, 3) PQ_SHORT_U(X, 32, 4) PQ_SHORT_U(X, 64, 1) PQ_SHORT_U(X, 64, 2)
+    PQ_SHORT_U4(X, 16, 1) PQ_SHORT_U4(X, 16, 5) PQ_SHORT_U4(X, 16, 9)
+#define PQ_SHORT_INSTANCES_C(X) \
+    PQ_SHORT_U4(X, 32, 1) PQ_SHORT_U4(X, 32, 5) PQ_SHORT_U4(X, 64, 1)
 // scan_short_kernel<M, U, NT, false, 2>: two-byte sub-ids, m = 4, 8 (up to 12 code vectors per thread), 16 (up to 6 items)
 #define PQ_SHORT16_U(X, M, U) X(M, U, kThreads, false, 2)
 #define PQ_SHORT16_INSTANCES(X) \
@@ -97,6 +97,7 @@ PQ_SCAN_INSTANCES_U16(PQ_SCAN_EXTERN)
 PQ_SCAN_INSTANCES_STAMPED(PQ_SCAN_EXTERN6)
 PQ_SHORT_INSTANCES_A(PQ_SHORT_EXTERN)
 PQ_SHORT_INSTANCES_B(PQ_SHORT_EXTERN)
+PQ_SHORT_INSTANCES_C(PQ_SHORT_EXTERN)
 PQ_SUBSET_INSTANCES(PQ_SUBSET_EXTERN)
 PQ_SHORT16_INSTANCES(PQ_SHORT16_EXTERN)
 PQ_TILED_INSTANCES(PQ_TILED_EXTERN)

@@ -5,10 +5,13 @@
 // fold.hpp, comparison.hpp.
 #pragma once
 
-// Most units (16-byte code vectors for m <= 16, items for m = 32 and 64) a thread of the short kernel holds.  (m = 8,
-// measured: up to 12 vectors it beats the general kernel by 2 us and more, 2.5M items 14.5 -> 12.3 us, two queries side
-// by side on 1.28M items 13.4 -> 12.0 us; at 16 it no longer does.)
-__host__ __device__ constexpr int short_max_units(int m) { return m == 8 ? 12 : kRing * vec_per_thread(m); }
+// Most units (16-byte code vectors for m <= 16, items for m = 32 and 64) a thread of the short kernel holds: as many as
+// still beat the general kernel (measured at batch 1, K = 10: m = 8, 2.5M items 14.5 -> 12.3 us, at 16 vectors no gain left;
+// m = 16, 1.28M items 14.0 -> 11.6 us; m = 32, 700K items 13.9 -> 11.9 us; m = 64, 500K items 15.6 -> 14.4 us, but
+// eight items of four vectors each no longer fit the registers; m = 4, 3M items 13.3 -> 11.3 us).
+__host__ __device__ constexpr int short_max_units(int m) {
+    return m == 1 ? 2 : m == 2 ? 2 : m == 4 ? 6 : m == 8 ? 12 : m == 16 ? 12 : m == 32 ? 8 : 4;
+}
 // ... with two-byte sub-ids (rows of 8, 16, 32 bytes: m = 4, 8, 16): code vectors, or items of two vectors for m = 16
 __host__ __device__ constexpr int short16_max_units(int m) { return m == 16 ? 6 : 12; }
 

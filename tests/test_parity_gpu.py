@@ -380,7 +380,7 @@ def test_short_scan_every_number_of_units_per_thread(pq, oracle, m):
     # per number of units a thread holds; catalogue sizes that land on each of them, odd so that the last slot is ragged
     # and items follow the last whole code vector; K = 1, 10 and 31 (the largest the short kernel and small fold take)
     unit_items = 16 // m if m <= 16 else 1
-    max_units = {1: 2, 2: 2, 4: 4, 8: 12, 16: 8, 32: 4, 64: 2}[m]
+    max_units = {1: 2, 2: 2, 4: 6, 8: 12, 16: 12, 32: 8, 64: 4}[m]
     S = tables(m, 1, m, 256)
     for units in range(1, max_units + 1):
         N = (units - 1) * 256 * 512 * unit_items + 77_001 * unit_items + 3
